@@ -1,0 +1,211 @@
+/*
+ * jupiter_stage.h -- C ABI of the MI355X (gfx950) stage kernel of Jupiter's
+ * intra-sequence pipeline parallelism.
+ *
+ * What the library computes.  A *stage* is a contiguous run of decoder layers
+ * held by one device (Jupiter paper, Sec. IV-A.1).  A prompt is cut into
+ * consecutive sub-sequences ("chunks") that are injected one after the other;
+ * when chunk s_i is processed, the stage reuses what it cached for
+ * s_1..s_{i-1}, which the causal mask makes sufficient (Sec. IV-A.2).  One call
+ * of jup_stage_prefill_chunk() is one stage forward over one chunk, i.e. one
+ * evaluation of the paper's latency function q(x, y) with x = n_tokens and
+ * y = pos_offset (Sec. IV-B.2).  Per layer it does, in the order of the decoder
+ * layer of Sec. II-A and in the Llama-2 form the paper evaluates (Sec. V-A):
+ *
+ *   1. RMSNorm of the chunk's hidden states, QKV projection (no bias)
+ *   2. rotary embedding of Q and K at absolute positions pos_offset + t
+ *      (pairs (i, i + head_dim/2), angle pos * theta^(-2i/head_dim))
+ *   3. K (after the rotation) and V appended to the KV cache at slots
+ *      [pos_offset, pos_offset + n_tokens)
+ *   4. causal attention of the chunk's queries over the cached prefix
+ *      0..pos_offset-1 plus the causal triangle inside the chunk (a token sees
+ *      itself), scale 1/sqrt(head_dim)
+ *   5. output projection, residual
+ *   6. RMSNorm, SwiGLU feed-forward  silu(x Wg^T) * (x Wu^T) Wd^T, residual
+ *
+ * Decode-sized chunks (speculative verification, Sec. V-A; outline branches
+ * that share the prompt's cache, Sec. V-B) are the same call with a small
+ * n_tokens, on a cache made with jup_kv_fork() and rolled back with
+ * jup_kv_truncate().
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers unless a comment says host.
+ *     The library never allocates or frees device memory: every buffer,
+ *     including its own packed weights and workspace, is provided by the caller
+ *     (normally through PyTorch) and is borrowed until the handle is destroyed.
+ *   - Matrices are row-major.  Weights are [out_features, in_features].
+ *   - dtype JUP_BF16: hidden states, weights, gains and the KV cache are
+ *     bfloat16; products accumulate in fp32 on the matrix cores and the residual
+ *     stream is kept in fp32 inside a call.  dtype JUP_F32 ("check mode"): the
+ *     same mathematics with fp32 storage and fp32 arithmetic throughout, on
+ *     plain (non matrix-core) kernels; it exists to pin indexing and semantics.
+ *   - Calls validate their arguments on the host before anything is enqueued;
+ *     on error nothing is enqueued, no state changes, and jup_last_error()
+ *     holds a message.  Kernel work is asynchronous on the given HIP stream.
+ *   - A stage owns one workspace: calls on the same stage must not overlap
+ *     (issue them on one stream, or synchronise between streams).
+ *   - The handles are host objects (malloc/free); they are not thread-safe.
+ */
+#ifndef JUPITER_STAGE_H
+#define JUPITER_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Marks the exported entry points (the library is built with hidden visibility otherwise). */
+#define JUP_API __attribute__((visibility("default")))
+
+typedef struct jup_stage jup_stage_t; /* opaque, host object */
+typedef struct jup_kv jup_kv_t;       /* opaque, host object */
+
+typedef enum { JUP_F32 = 0, JUP_BF16 = 1 } jup_dtype_t;
+
+typedef enum {
+    JUP_OK = 0,
+    JUP_EINVAL = -1,  /* null pointer, inconsistent or unsupported sizes, too-small buffer */
+    JUP_EPOS = -2,    /* pos_offset would leave a hole, or touches a shared (read-only) prefix */
+    JUP_ECAP = -3,    /* chunk does not fit the cache's max_positions or the stage's max_chunk_tokens */
+    JUP_EDEVICE = -4, /* a HIP call failed (no device, launch error) */
+    JUP_ENOMEM = -5   /* host allocation of a handle failed */
+} jup_status_t;
+
+/*
+ * Shape of a stage.  Requirements: d_model == n_heads * head_dim; head_dim even.
+ * JUP_BF16 additionally requires head_dim == 128, d_model % 256 == 0 and
+ * d_ffn % 128 == 0 (the matrix-core tilings); JUP_F32 accepts any sizes.
+ */
+typedef struct {
+    int32_t n_layers;
+    int32_t d_model;
+    int32_t n_heads;
+    int32_t head_dim;
+    int32_t d_ffn;
+    float rms_eps;    /* inside the square root: x / sqrt(mean(x^2) + eps) */
+    float rope_theta; /* rotary base, 1e4 for Llama-2 */
+    int32_t dtype;    /* jup_dtype_t */
+} jup_stage_config_t;
+
+/* One decoder layer's parameters; device pointers of the stage dtype. */
+typedef struct {
+    const void *wq, *wk, *wv, *wo; /* [d_model, d_model] */
+    const void *w_gate, *w_up;     /* [d_ffn, d_model]   */
+    const void *w_down;            /* [d_model, d_ffn]   */
+    const void *g_attn, *g_mlp;    /* [d_model] RMSNorm gains before attention / before the FFN */
+} jup_layer_weights_t;
+
+/* ---- stage ---------------------------------------------------------------------------------- */
+
+/* Bytes of device memory jup_stage_create() needs for its packed copy of the weights. 0 on bad cfg. */
+JUP_API size_t jup_stage_packed_bytes(const jup_stage_config_t *cfg);
+
+/* Bytes of device workspace for chunks of up to max_chunk_tokens tokens. 0 on bad arguments. */
+JUP_API size_t jup_stage_workspace_bytes(const jup_stage_config_t *cfg, int32_t max_chunk_tokens);
+
+/*
+ * Builds a stage (Sec. IV-A.1: a stage model made of consecutive decoder layers).
+ *   cfg, layers     host structs; layers[n_layers] hold device pointers
+ *   packed          device buffer of >= jup_stage_packed_bytes(cfg) bytes, 256-byte aligned.  The
+ *                   weights are copied into it in the layout the kernels read (Q/K/V rows fused,
+ *                   gate/up rows interleaved); the copy kernels are enqueued on `stream`, and once
+ *                   they have run the caller's originals are no longer referenced.
+ *   workspace       device buffer of >= jup_stage_workspace_bytes(cfg, max_chunk_tokens) bytes,
+ *                   256-byte aligned; contents are scratch.
+ *   stream          hipStream_t (NULL = the default stream)
+ * Errors: JUP_EINVAL (null pointer, bad shape, small buffer), JUP_ENOMEM, JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_stage_create(const jup_stage_config_t *cfg, const jup_layer_weights_t *layers, void *packed,
+                              size_t packed_bytes, void *workspace, size_t workspace_bytes,
+                              int32_t max_chunk_tokens, void *stream, jup_stage_t **out);
+
+/* Frees the host object only. NULL is allowed. */
+JUP_API void jup_stage_destroy(jup_stage_t *stage);
+
+/* ---- KV cache ------------------------------------------------------------------------------- */
+
+/*
+ * KV cache contract (Sec. II-A item 4, Sec. II-B: keys and values of all previous tokens, stored
+ * per decoder layer and reused without recomputation).  A cache of max_positions slots is one
+ * device buffer of elements of the stage dtype laid out as
+ *
+ *     kv[layer][which][head][position][i]      which: 0 = K after the rotation, 1 = V
+ *     element index = (((layer*2 + which)*n_heads + head)*max_positions + position)*head_dim + i
+ *
+ * A call for a chunk at pos_offset writes exactly the slots [pos_offset, pos_offset + n_tokens) of
+ * every (layer, which, head) and nothing else.
+ */
+JUP_API size_t jup_kv_bytes(const jup_stage_config_t *cfg, int32_t max_positions);
+
+/* Wraps a caller-provided device buffer (>= jup_kv_bytes, 256-byte aligned); length starts at 0. */
+JUP_API jup_status_t jup_kv_create(const jup_stage_config_t *cfg, int32_t max_positions, void *device_buf,
+                           size_t device_bytes, jup_kv_t **out);
+
+/*
+ * A cache that shares the first n_shared positions of `parent` read-only (Sec. V-B: the prompt's
+ * KVCache is shared across all point-extending requests) and owns positions
+ * [n_shared, max_positions).  Its buffer uses the layout above with max_positions replaced by
+ * (max_positions - n_shared) and position replaced by (position - n_shared).
+ * Requirements: parent is not itself a fork; 0 <= n_shared <= jup_kv_len(parent);
+ * max_positions > n_shared.  The fork starts with length n_shared.  The parent must outlive the
+ * fork, and while forks exist it must not be truncated below n_shared (calls that would do so
+ * return JUP_EPOS).
+ */
+JUP_API size_t jup_kv_fork_bytes(const jup_kv_t *parent, int32_t n_shared, int32_t max_positions);
+JUP_API jup_status_t jup_kv_fork(jup_kv_t *parent, int32_t n_shared, int32_t max_positions, void *device_buf,
+                         size_t device_bytes, jup_kv_t **out);
+
+/* Length back to 0 (to n_shared for a fork). Device memory is not touched.
+ * JUP_EPOS if live forks share positions of this cache. */
+JUP_API jup_status_t jup_kv_reset(jup_kv_t *kv);
+
+/*
+ * Drops positions >= new_len (Sec. V-A step 5: rejected candidate tokens are removed from the
+ * KVCache).  JUP_EPOS if new_len > length, < 0, below a fork's shared prefix, or below the
+ * n_shared of a live fork of this cache.
+ */
+JUP_API jup_status_t jup_kv_truncate(jup_kv_t *kv, int32_t new_len);
+
+JUP_API int32_t jup_kv_len(const jup_kv_t *kv);      /* positions currently valid; -1 for NULL */
+JUP_API int32_t jup_kv_capacity(const jup_kv_t *kv); /* max_positions; -1 for NULL */
+
+/*
+ * Would a chunk of n_tokens at pos_offset be accepted?  Pure host logic, the same check
+ * jup_stage_prefill_chunk() applies:
+ *   n_tokens < 0 or pos_offset < 0            -> JUP_EINVAL
+ *   pos_offset > length                       -> JUP_EPOS  (a hole: the prefix s_1..s_{i-1} would be incomplete)
+ *   pos_offset < n_shared of a fork           -> JUP_EPOS  (shared prefix is read-only)
+ *   pos_offset < n_shared of a live child     -> JUP_EPOS
+ *   pos_offset + n_tokens > max_positions     -> JUP_ECAP
+ * pos_offset < length is allowed and means "overwrite from here" (implicit truncate).
+ */
+JUP_API jup_status_t jup_kv_check_append(const jup_kv_t *kv, int32_t n_tokens, int32_t pos_offset);
+
+/* Frees the host object.  JUP_EINVAL if forks of it are still alive. NULL is allowed. */
+JUP_API jup_status_t jup_kv_destroy(jup_kv_t *kv);
+
+/* ---- the hot path --------------------------------------------------------------------------- */
+
+/*
+ * One stage forward over one chunk (Sec. IV-A.2), steps 1-6 above for every layer of the stage.
+ *   hidden_in   [n_tokens, d_model], stage dtype
+ *   n_tokens    any value >= 0 (0 is a no-op); must be <= the stage's max_chunk_tokens
+ *   pos_offset  number of tokens of the earlier chunks; see jup_kv_check_append()
+ *   kv          cache made for the same configuration as the stage
+ *   hidden_out  [n_tokens, d_model], stage dtype; may be the same buffer as hidden_in
+ *   stream      hipStream_t (NULL = default stream); all kernels are enqueued there
+ * On success the cache length becomes pos_offset + n_tokens.
+ * Errors: JUP_EINVAL, JUP_EPOS, JUP_ECAP (nothing enqueued, length unchanged), JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hidden_in, int32_t n_tokens,
+                                     int32_t pos_offset, jup_kv_t *kv, void *hidden_out, void *stream);
+
+/* Message of the last error on this thread ("" if none). Never NULL. */
+JUP_API const char *jup_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JUPITER_STAGE_H */

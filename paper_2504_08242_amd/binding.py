@@ -1,0 +1,222 @@
+"""ctypes binding of libjupiter_stage.so (see include/jupiter_stage.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch provides device memory and streams.  There is no fallback:
+if the library is missing, loading raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libjupiter_stage.so")
+
+JUP_F32, JUP_BF16 = 0, 1
+JUP_OK, JUP_EINVAL, JUP_EPOS, JUP_ECAP, JUP_EDEVICE, JUP_ENOMEM = 0, -1, -2, -3, -4, -5
+STATUS_NAMES = {0: "JUP_OK", -1: "JUP_EINVAL", -2: "JUP_EPOS", -3: "JUP_ECAP", -4: "JUP_EDEVICE", -5: "JUP_ENOMEM"}
+WEIGHT_NAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_mlp")
+
+
+class StageConfig(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("d_model", ctypes.c_int32), ("n_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("d_ffn", ctypes.c_int32), ("rms_eps", ctypes.c_float),
+                ("rope_theta", ctypes.c_float), ("dtype", ctypes.c_int32)]
+
+
+class LayerWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in WEIGHT_NAMES]
+
+
+class JupiterError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Loads the C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2504_08242_amd.build` "
+                "(there is no CPU or PyTorch fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        cfgp = ctypes.POINTER(StageConfig)
+        sig = {
+            "jup_stage_packed_bytes": (sz, [cfgp]),
+            "jup_stage_workspace_bytes": (sz, [cfgp, i32]),
+            "jup_stage_create": (i32, [cfgp, ctypes.POINTER(LayerWeights), vp, sz, vp, sz, i32, vp,
+                                       ctypes.POINTER(vp)]),
+            "jup_stage_destroy": (None, [vp]),
+            "jup_kv_bytes": (sz, [cfgp, i32]),
+            "jup_kv_create": (i32, [cfgp, i32, vp, sz, ctypes.POINTER(vp)]),
+            "jup_kv_fork_bytes": (sz, [vp, i32, i32]),
+            "jup_kv_fork": (i32, [vp, i32, i32, vp, sz, ctypes.POINTER(vp)]),
+            "jup_kv_reset": (i32, [vp]),
+            "jup_kv_truncate": (i32, [vp, i32]),
+            "jup_kv_len": (i32, [vp]),
+            "jup_kv_capacity": (i32, [vp]),
+            "jup_kv_check_append": (i32, [vp, i32, i32]),
+            "jup_kv_destroy": (i32, [vp]),
+            "jup_stage_prefill_chunk": (i32, [vp, vp, i32, i32, vp, vp, vp]),
+            "jup_last_error": (ctypes.c_char_p, []),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def last_error():
+    return lib().jup_last_error().decode()
+
+
+def _check(status):
+    if status != JUP_OK:
+        raise JupiterError(status, last_error())
+
+
+def make_config(cfg, dtype):
+    """cfg: dict with n_layers, d_model, n_heads, head_dim, d_ffn, rms_eps, rope_theta; dtype: 'f32' | 'bf16'."""
+    return StageConfig(cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ffn"],
+                       cfg["rms_eps"], cfg["rope_theta"], {"f32": JUP_F32, "bf16": JUP_BF16}[dtype])
+
+
+def _torch_dtype(dtype):
+    import torch
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+def _stream_handle(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class KvCache:
+    """jup_kv_t plus the torch tensor that backs it (layout: [layer][K|V][head][position][head_dim])."""
+
+    def __init__(self, cfg, dtype, max_positions, device="cuda:0", _fork_of=None, _n_shared=0):
+        import torch
+        self.cfg, self.dtype, self.max_positions = dict(cfg), dtype, int(max_positions)
+        self.parent, self.n_shared = _fork_of, int(_n_shared)
+        L = lib()
+        ccfg = make_config(cfg, dtype)
+        es = 4 if dtype == "f32" else 2
+        self.handle = ctypes.c_void_p()
+        if _fork_of is None:
+            nbytes = L.jup_kv_bytes(ctypes.byref(ccfg), self.max_positions)
+            if nbytes == 0:
+                raise JupiterError(JUP_EINVAL, "jup_kv_bytes rejected the configuration")
+            slots = self.max_positions
+            self.buf = torch.zeros(nbytes // es, dtype=_torch_dtype(dtype), device=device)
+            _check(L.jup_kv_create(ctypes.byref(ccfg), self.max_positions, ctypes.c_void_p(self.buf.data_ptr()),
+                                   nbytes, ctypes.byref(self.handle)))
+        else:
+            nbytes = L.jup_kv_fork_bytes(_fork_of.handle, self.n_shared, self.max_positions)
+            if nbytes == 0:
+                raise JupiterError(JUP_EINVAL, "jup_kv_fork_bytes rejected the arguments")
+            slots = self.max_positions - self.n_shared
+            self.buf = torch.zeros(nbytes // es, dtype=_torch_dtype(dtype), device=device)
+            _check(L.jup_kv_fork(_fork_of.handle, self.n_shared, self.max_positions,
+                                 ctypes.c_void_p(self.buf.data_ptr()), nbytes, ctypes.byref(self.handle)))
+        self.slots = slots
+
+    def fork(self, n_shared, max_positions):
+        return KvCache(self.cfg, self.dtype, max_positions, device=self.buf.device, _fork_of=self, _n_shared=n_shared)
+
+    def view(self):
+        """Own buffer as [n_layers, 2, n_heads, slots, head_dim]."""
+        c = self.cfg
+        return self.buf.view(c["n_layers"], 2, c["n_heads"], self.slots, c["head_dim"])
+
+    def __len__(self):
+        return int(lib().jup_kv_len(self.handle))
+
+    def reset(self):
+        _check(lib().jup_kv_reset(self.handle))
+
+    def truncate(self, new_len):
+        _check(lib().jup_kv_truncate(self.handle, int(new_len)))
+
+    def check_append(self, n_tokens, pos_offset):
+        return int(lib().jup_kv_check_append(self.handle, int(n_tokens), int(pos_offset)))
+
+    def destroy(self):
+        if self.handle:
+            _check(lib().jup_kv_destroy(self.handle))
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            if self.handle:
+                lib().jup_kv_destroy(self.handle)
+        except Exception:
+            pass
+
+
+class Stage:
+    """jup_stage_t plus the torch tensors that back its packed weights and workspace."""
+
+    def __init__(self, cfg, dtype, layers, max_chunk_tokens, device="cuda:0", stream=None):
+        """layers: list of dicts keyed by WEIGHT_NAMES holding torch tensors of the stage dtype on `device`."""
+        import torch
+        self.cfg, self.dtype, self.max_chunk_tokens = dict(cfg), dtype, int(max_chunk_tokens)
+        L = lib()
+        ccfg = make_config(cfg, dtype)
+        pb = L.jup_stage_packed_bytes(ctypes.byref(ccfg))
+        wb = L.jup_stage_workspace_bytes(ctypes.byref(ccfg), self.max_chunk_tokens)
+        if pb == 0 or wb == 0:
+            # let the library produce the message
+            self.packed = self.workspace = None
+        else:
+            self.packed = torch.empty(pb, dtype=torch.uint8, device=device)
+            self.workspace = torch.empty(wb, dtype=torch.uint8, device=device)
+        td = _torch_dtype(dtype)
+        arr = (LayerWeights * max(1, len(layers)))()
+        for i, w in enumerate(layers):
+            for n in WEIGHT_NAMES:
+                t = w[n]
+                assert t.dtype == td and t.is_contiguous() and t.device.type == "cuda", n
+                setattr(arr[i], n, t.data_ptr())
+        self.handle = ctypes.c_void_p()
+        _check(L.jup_stage_create(ctypes.byref(ccfg), arr,
+                                  ctypes.c_void_p(self.packed.data_ptr() if self.packed is not None else 0), pb,
+                                  ctypes.c_void_p(self.workspace.data_ptr() if self.workspace is not None else 0), wb,
+                                  self.max_chunk_tokens, _stream_handle(stream), ctypes.byref(self.handle)))
+
+    def prefill_chunk(self, hidden_in, pos_offset, kv, hidden_out=None, stream=None):
+        """hidden_in: [n_tokens, d_model] tensor of the stage dtype on the GPU. Returns hidden_out."""
+        import torch
+        n = int(hidden_in.shape[0])
+        assert hidden_in.is_contiguous() and hidden_in.dtype == _torch_dtype(self.dtype)
+        if hidden_out is None:
+            hidden_out = torch.empty_like(hidden_in)
+        _check(lib().jup_stage_prefill_chunk(self.handle, ctypes.c_void_p(hidden_in.data_ptr()), n, int(pos_offset),
+                                             kv.handle, ctypes.c_void_p(hidden_out.data_ptr()),
+                                             _stream_handle(stream)))
+        return hidden_out
+
+    def destroy(self):
+        if self.handle:
+            lib().jup_stage_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def upload_layers(layers_np, dtype, device="cuda:0"):
+    """numpy fp32 layer dicts (already bf16-representable when dtype == 'bf16') -> torch tensors on the GPU."""
+    import torch
+    td = _torch_dtype(dtype)
+    return [{n: torch.from_numpy(w[n]).to(device=device, dtype=td).contiguous() for n in WEIGHT_NAMES}
+            for w in layers_np]

@@ -1,0 +1,338 @@
+// Host side of the C ABI: argument validation, KV-cache bookkeeping, buffer layouts, dispatch to the
+// fp32 check-mode path or the bf16 matrix-core path.  No device memory is allocated here.
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "jup_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+jup_status_t fail(jup_status_t code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+size_t elem_size(const jup_stage_config_t& c) { return c.dtype == JUP_BF16 ? 2 : 4; }
+
+// Empty string when the configuration is usable, otherwise the reason.
+const char* check_cfg(const jup_stage_config_t* c) {
+    if (!c) return "cfg is NULL";
+    if (c->dtype != JUP_F32 && c->dtype != JUP_BF16) return "dtype must be JUP_F32 or JUP_BF16";
+    if (c->n_layers < 0 || c->n_layers > 4096) return "n_layers out of range";
+    if (c->d_model <= 0 || c->n_heads <= 0 || c->head_dim <= 0 || c->d_ffn <= 0) return "sizes must be positive";
+    if ((int64_t)c->n_heads * c->head_dim != c->d_model) return "d_model must equal n_heads * head_dim";
+    if (c->head_dim & 1) return "head_dim must be even";
+    if (c->head_dim > 256) return "head_dim above 256 is not supported";
+    if (!(c->rms_eps >= 0.0f)) return "rms_eps must be >= 0";
+    if (!(c->rope_theta > 0.0f)) return "rope_theta must be > 0";
+    if (c->dtype == JUP_BF16) {
+        if (c->head_dim != 128) return "JUP_BF16 requires head_dim == 128";
+        if (c->d_model % 256) return "JUP_BF16 requires d_model % 256 == 0";
+        if (c->d_ffn % 128) return "JUP_BF16 requires d_ffn % 128 == 0";
+    }
+    return "";
+}
+
+bool same_shape(const jup_stage_config_t& a, const jup_stage_config_t& b) {
+    return a.n_layers == b.n_layers && a.d_model == b.d_model && a.n_heads == b.n_heads &&
+           a.head_dim == b.head_dim && a.dtype == b.dtype;
+}
+
+size_t kv_bytes_for(const jup_stage_config_t& c, int64_t slots) {
+    return (size_t)c.n_layers * 2 * (size_t)c.n_heads * (size_t)slots * (size_t)c.head_dim * elem_size(c);
+}
+
+bool misaligned(const void* p) { return ((uintptr_t)p % jup::kAlign) != 0; }
+
+}  // namespace
+
+namespace jup {
+
+PackedLayout packed_layout(const jup_stage_config_t& c) {
+    const size_t e = elem_size(c), d = c.d_model, f = c.d_ffn;
+    PackedLayout p{};
+    size_t off = 0;
+    p.wqkv = off;   off += align_up(3 * d * d * e);
+    p.wo = off;     off += align_up(d * d * e);
+    p.wgu = off;    off += align_up(2 * f * d * e);
+    p.wdown = off;  off += align_up(d * f * e);
+    p.g_attn = off; off += align_up(d * e);
+    p.g_mlp = off;  off += align_up(d * e);
+    p.layer_bytes = off;
+    return p;
+}
+
+WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T) {
+    const size_t e = elem_size(c), d = c.d_model, f = c.d_ffn, t = (size_t)T;
+    const bool f32 = c.dtype == JUP_F32;
+    WorkspaceLayout w{};
+    size_t off = 0;
+    w.x32 = off;  off += align_up(t * d * 4);
+    w.xn = off;   off += align_up(t * d * e);
+    w.q = off;    off += align_up(t * d * e * (f32 ? 3 : 1));
+    w.o = off;    off += align_up(t * d * e);
+    w.gu = off;   off += f32 ? align_up(t * 2 * f * e) : 0;
+    w.act = off;  off += align_up(t * f * e);
+    w.rope = off; off += align_up(t * (size_t)(c.head_dim / 2) * 8);
+    w.total = off;
+    return w;
+}
+
+}  // namespace jup
+
+extern "C" {
+
+const char* jup_last_error(void) { return g_err; }
+
+size_t jup_stage_packed_bytes(const jup_stage_config_t* cfg) {
+    if (*check_cfg(cfg)) return 0;
+    return jup::packed_layout(*cfg).layer_bytes * (size_t)cfg->n_layers + jup::kAlign;
+}
+
+size_t jup_stage_workspace_bytes(const jup_stage_config_t* cfg, int32_t max_chunk_tokens) {
+    if (*check_cfg(cfg) || max_chunk_tokens <= 0) return 0;
+    return jup::workspace_layout(*cfg, max_chunk_tokens).total + jup::kAlign;
+}
+
+jup_status_t jup_stage_create(const jup_stage_config_t* cfg, const jup_layer_weights_t* layers, void* packed,
+                              size_t packed_bytes, void* workspace, size_t workspace_bytes,
+                              int32_t max_chunk_tokens, void* stream, jup_stage_t** out) {
+    if (out) *out = nullptr;
+    const char* why = check_cfg(cfg);
+    if (*why) return fail(JUP_EINVAL, "jup_stage_create: %s", why);
+    if (!out) return fail(JUP_EINVAL, "jup_stage_create: out is NULL");
+    if (cfg->n_layers > 0 && !layers) return fail(JUP_EINVAL, "jup_stage_create: layers is NULL");
+    if (max_chunk_tokens <= 0) return fail(JUP_EINVAL, "jup_stage_create: max_chunk_tokens must be positive");
+    if (!packed || !workspace) return fail(JUP_EINVAL, "jup_stage_create: packed and workspace must not be NULL");
+    if (misaligned(packed) || misaligned(workspace))
+        return fail(JUP_EINVAL, "jup_stage_create: packed and workspace must be 256-byte aligned");
+    if (packed_bytes < jup_stage_packed_bytes(cfg))
+        return fail(JUP_EINVAL, "jup_stage_create: packed buffer has %zu bytes, %zu needed", packed_bytes,
+                    jup_stage_packed_bytes(cfg));
+    if (workspace_bytes < jup_stage_workspace_bytes(cfg, max_chunk_tokens))
+        return fail(JUP_EINVAL, "jup_stage_create: workspace has %zu bytes, %zu needed", workspace_bytes,
+                    jup_stage_workspace_bytes(cfg, max_chunk_tokens));
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const jup_layer_weights_t& w = layers[l];
+        if (!w.wq || !w.wk || !w.wv || !w.wo || !w.w_gate || !w.w_up || !w.w_down || !w.g_attn || !w.g_mlp)
+            return fail(JUP_EINVAL, "jup_stage_create: layer %d has a NULL weight pointer", l);
+    }
+
+    jup_stage* st = new (std::nothrow) jup_stage();
+    if (!st) return fail(JUP_ENOMEM, "jup_stage_create: out of host memory");
+    st->cfg = *cfg;
+    st->packed = packed;
+    st->workspace = workspace;
+    st->max_chunk_tokens = max_chunk_tokens;
+    st->pl = jup::packed_layout(*cfg);
+    st->wl = jup::workspace_layout(*cfg, max_chunk_tokens);
+
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    if (cfg->dtype == JUP_F32) {
+        // Check mode reads the matrices as given: copy them section by section.
+        const size_t d = cfg->d_model, f = cfg->d_ffn;
+        for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
+            char* base = (char*)packed + (size_t)l * st->pl.layer_bytes;
+            const jup_layer_weights_t& w = layers[l];
+            struct { size_t off; const void* src; size_t bytes; } jobs[] = {
+                {st->pl.wqkv, w.wq, d * d * 4},
+                {st->pl.wqkv + d * d * 4, w.wk, d * d * 4},
+                {st->pl.wqkv + 2 * d * d * 4, w.wv, d * d * 4},
+                {st->pl.wo, w.wo, d * d * 4},
+                {st->pl.wgu, w.w_gate, f * d * 4},
+                {st->pl.wgu + f * d * 4, w.w_up, f * d * 4},
+                {st->pl.wdown, w.w_down, d * f * 4},
+                {st->pl.g_attn, w.g_attn, d * 4},
+                {st->pl.g_mlp, w.g_mlp, d * 4},
+            };
+            for (auto& j : jobs) {
+                e = hipMemcpyAsync(base + j.off, j.src, j.bytes, hipMemcpyDeviceToDevice, s);
+                if (e != hipSuccess) break;
+            }
+        }
+    } else {
+        e = jup::bf16_pack_weights(*st, layers, s);
+    }
+    if (e != hipSuccess) {
+        delete st;
+        return fail(JUP_EDEVICE, "jup_stage_create: %s", hipGetErrorString(e));
+    }
+    *out = st;
+    return JUP_OK;
+}
+
+void jup_stage_destroy(jup_stage_t* stage) { delete stage; }
+
+// ---- KV cache ---------------------------------------------------------------------------------
+
+size_t jup_kv_bytes(const jup_stage_config_t* cfg, int32_t max_positions) {
+    if (*check_cfg(cfg) || max_positions <= 0) return 0;
+    return kv_bytes_for(*cfg, max_positions);
+}
+
+jup_status_t jup_kv_create(const jup_stage_config_t* cfg, int32_t max_positions, void* device_buf,
+                           size_t device_bytes, jup_kv_t** out) {
+    if (out) *out = nullptr;
+    const char* why = check_cfg(cfg);
+    if (*why) return fail(JUP_EINVAL, "jup_kv_create: %s", why);
+    if (!out) return fail(JUP_EINVAL, "jup_kv_create: out is NULL");
+    if (max_positions <= 0) return fail(JUP_EINVAL, "jup_kv_create: max_positions must be positive");
+    if (!device_buf || misaligned(device_buf))
+        return fail(JUP_EINVAL, "jup_kv_create: device_buf must be non-NULL and 256-byte aligned");
+    if (device_bytes < kv_bytes_for(*cfg, max_positions))
+        return fail(JUP_EINVAL, "jup_kv_create: buffer has %zu bytes, %zu needed", device_bytes,
+                    kv_bytes_for(*cfg, max_positions));
+    jup_kv* kv = new (std::nothrow) jup_kv();
+    if (!kv) return fail(JUP_ENOMEM, "jup_kv_create: out of host memory");
+    kv->cfg = *cfg;
+    kv->buf = device_buf;
+    kv->max_positions = max_positions;
+    kv->len = 0;
+    kv->parent = nullptr;
+    kv->n_shared = 0;
+    kv->n_children = 0;
+    kv->max_child_shared = 0;
+    *out = kv;
+    return JUP_OK;
+}
+
+size_t jup_kv_fork_bytes(const jup_kv_t* parent, int32_t n_shared, int32_t max_positions) {
+    if (!parent || n_shared < 0 || max_positions <= n_shared) return 0;
+    return kv_bytes_for(parent->cfg, (int64_t)max_positions - n_shared);
+}
+
+jup_status_t jup_kv_fork(jup_kv_t* parent, int32_t n_shared, int32_t max_positions, void* device_buf,
+                         size_t device_bytes, jup_kv_t** out) {
+    if (out) *out = nullptr;
+    if (!parent || !out) return fail(JUP_EINVAL, "jup_kv_fork: parent and out must not be NULL");
+    if (parent->parent) return fail(JUP_EINVAL, "jup_kv_fork: the parent is itself a fork");
+    if (n_shared < 0 || n_shared > parent->len)
+        return fail(JUP_EPOS, "jup_kv_fork: n_shared=%d outside [0, parent length %d]", n_shared, parent->len);
+    if (max_positions <= n_shared)
+        return fail(JUP_EINVAL, "jup_kv_fork: max_positions=%d must exceed n_shared=%d", max_positions, n_shared);
+    if (!device_buf || misaligned(device_buf))
+        return fail(JUP_EINVAL, "jup_kv_fork: device_buf must be non-NULL and 256-byte aligned");
+    const size_t need = kv_bytes_for(parent->cfg, (int64_t)max_positions - n_shared);
+    if (device_bytes < need) return fail(JUP_EINVAL, "jup_kv_fork: buffer has %zu bytes, %zu needed", device_bytes, need);
+    jup_kv* kv = new (std::nothrow) jup_kv();
+    if (!kv) return fail(JUP_ENOMEM, "jup_kv_fork: out of host memory");
+    kv->cfg = parent->cfg;
+    kv->buf = device_buf;
+    kv->max_positions = max_positions;
+    kv->len = n_shared;
+    kv->parent = parent;
+    kv->n_shared = n_shared;
+    kv->n_children = 0;
+    kv->max_child_shared = 0;
+    parent->n_children += 1;
+    if (n_shared > parent->max_child_shared) parent->max_child_shared = n_shared;
+    *out = kv;
+    return JUP_OK;
+}
+
+jup_status_t jup_kv_reset(jup_kv_t* kv) {
+    if (!kv) return fail(JUP_EINVAL, "jup_kv_reset: kv is NULL");
+    if (kv->n_children > 0 && kv->max_child_shared > 0)
+        return fail(JUP_EPOS, "jup_kv_reset: live forks share the first %d positions", kv->max_child_shared);
+    kv->len = kv->n_shared;
+    return JUP_OK;
+}
+
+jup_status_t jup_kv_truncate(jup_kv_t* kv, int32_t new_len) {
+    if (!kv) return fail(JUP_EINVAL, "jup_kv_truncate: kv is NULL");
+    if (new_len < 0 || new_len > kv->len)
+        return fail(JUP_EPOS, "jup_kv_truncate: new_len=%d outside [0, %d]", new_len, kv->len);
+    if (new_len < kv->n_shared)
+        return fail(JUP_EPOS, "jup_kv_truncate: new_len=%d cuts into the shared prefix of %d", new_len, kv->n_shared);
+    if (kv->n_children > 0 && new_len < kv->max_child_shared)
+        return fail(JUP_EPOS, "jup_kv_truncate: live forks share the first %d positions", kv->max_child_shared);
+    kv->len = new_len;
+    return JUP_OK;
+}
+
+int32_t jup_kv_len(const jup_kv_t* kv) { return kv ? kv->len : -1; }
+int32_t jup_kv_capacity(const jup_kv_t* kv) { return kv ? kv->max_positions : -1; }
+
+jup_status_t jup_kv_check_append(const jup_kv_t* kv, int32_t n_tokens, int32_t pos_offset) {
+    if (!kv) return fail(JUP_EINVAL, "kv is NULL");
+    if (n_tokens < 0) return fail(JUP_EINVAL, "n_tokens=%d is negative", n_tokens);
+    if (pos_offset < 0) return fail(JUP_EINVAL, "pos_offset=%d is negative", pos_offset);
+    if (pos_offset > kv->len)
+        return fail(JUP_EPOS, "pos_offset=%d leaves a hole after the %d cached positions", pos_offset, kv->len);
+    if (pos_offset < kv->n_shared)
+        return fail(JUP_EPOS, "pos_offset=%d lies inside the read-only shared prefix of %d", pos_offset, kv->n_shared);
+    if (kv->n_children > 0 && pos_offset < kv->max_child_shared)
+        return fail(JUP_EPOS, "pos_offset=%d would overwrite positions shared with live forks (%d)", pos_offset,
+                    kv->max_child_shared);
+    if ((int64_t)pos_offset + n_tokens > kv->max_positions)
+        return fail(JUP_ECAP, "pos_offset=%d + n_tokens=%d exceeds max_positions=%d", pos_offset, n_tokens,
+                    kv->max_positions);
+    return JUP_OK;
+}
+
+jup_status_t jup_kv_destroy(jup_kv_t* kv) {
+    if (!kv) return JUP_OK;
+    if (kv->n_children > 0) return fail(JUP_EINVAL, "jup_kv_destroy: %d forks are still alive", kv->n_children);
+    if (kv->parent) {
+        kv->parent->n_children -= 1;
+        if (kv->parent->n_children == 0) kv->parent->max_child_shared = 0;
+    }
+    delete kv;
+    return JUP_OK;
+}
+
+// ---- the hot path -----------------------------------------------------------------------------
+
+jup_status_t jup_stage_prefill_chunk(jup_stage_t* stage, const void* hidden_in, int32_t n_tokens,
+                                     int32_t pos_offset, jup_kv_t* kv, void* hidden_out, void* stream) {
+    if (!stage) return fail(JUP_EINVAL, "jup_stage_prefill_chunk: stage is NULL");
+    if (!kv) return fail(JUP_EINVAL, "jup_stage_prefill_chunk: kv is NULL");
+    if (!same_shape(stage->cfg, kv->cfg))
+        return fail(JUP_EINVAL, "jup_stage_prefill_chunk: the cache was made for another configuration");
+    jup_status_t rc = jup_kv_check_append(kv, n_tokens, pos_offset);
+    if (rc != JUP_OK) {
+        char tmp[400];
+        snprintf(tmp, sizeof(tmp), "%s", g_err);
+        return fail(rc, "jup_stage_prefill_chunk: %s", tmp);
+    }
+    if (n_tokens > stage->max_chunk_tokens)
+        return fail(JUP_ECAP, "jup_stage_prefill_chunk: n_tokens=%d exceeds the stage's max_chunk_tokens=%d", n_tokens,
+                    stage->max_chunk_tokens);
+    if (kv->parent && kv->parent->len < kv->n_shared)
+        return fail(JUP_EPOS, "jup_stage_prefill_chunk: the parent cache holds %d positions, fewer than the %d shared",
+                    kv->parent->len, kv->n_shared);
+    if (n_tokens == 0) {
+        kv->len = pos_offset;
+        return JUP_OK;
+    }
+    if (!hidden_in || !hidden_out)
+        return fail(JUP_EINVAL, "jup_stage_prefill_chunk: hidden_in and hidden_out must not be NULL");
+
+    jup::KvView view{};
+    view.own = kv->buf;
+    view.parent = kv->parent ? kv->parent->buf : nullptr;
+    view.n_shared = kv->n_shared;
+    view.own_cap = kv->max_positions - kv->n_shared;
+    view.parent_cap = kv->parent ? kv->parent->max_positions : 0;
+
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (stage->cfg.dtype == JUP_F32)
+        e = jup::f32_forward(*stage, (const float*)hidden_in, n_tokens, pos_offset, view, (float*)hidden_out, s);
+    else
+        e = jup::bf16_forward(*stage, hidden_in, n_tokens, pos_offset, view, hidden_out, s);
+    if (e != hipSuccess) return fail(JUP_EDEVICE, "jup_stage_prefill_chunk: %s", hipGetErrorString(e));
+    kv->len = pos_offset + n_tokens;
+    return JUP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+"""Shared plumbing of the GPU parity tests: the same seeded numpy inputs go to the CPU oracle and to
+the HIP library; results come back as numpy fp32."""
+import numpy as np
+
+import oracle
+from paper_2504_08242_amd import binding as jb
+from paper_2504_08242_amd import synth_inputs as si
+
+# Tolerances of the parity bar.
+F32_MAX_ABS, F32_REL_L2 = 1e-3, 1e-4
+BF16_REL_L2 = 2e-2
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def to_numpy(t):
+    import torch
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+class Pair:
+    """An oracle stage and a GPU stage built from the same seeded tensors."""
+
+    def __init__(self, cfg, dtype, seed, max_positions, max_chunk_tokens, weight_std=0.02, layers_np=None):
+        import torch
+        self.cfg, self.dtype, self.seed = dict(cfg), dtype, seed
+        bf16 = dtype == "bf16"
+        self.layers_np = layers_np if layers_np is not None else si.make_layers(cfg, seed, bf16=bf16,
+                                                                                weight_std=weight_std)
+        self.oracle = oracle.OracleStage(cfg, self.layers_np, max_positions)
+        dev_layers = jb.upload_layers(self.layers_np, dtype)
+        self.stage = jb.Stage(cfg, dtype, dev_layers, max_chunk_tokens)
+        torch.cuda.synchronize()
+        del dev_layers  # the stage keeps its own packed copy
+        self.kv = jb.KvCache(cfg, dtype, max_positions)
+        self.td = torch.float32 if dtype == "f32" else torch.bfloat16
+
+    def hidden(self, n_tokens, tag=0):
+        return si.make_hidden(self.cfg, self.seed, n_tokens, tag=tag, bf16=self.dtype == "bf16")
+
+    def gpu_chunk(self, hidden_np, pos, kv=None):
+        import torch
+        x = torch.from_numpy(hidden_np).to(device="cuda:0", dtype=self.td)
+        y = self.stage.prefill_chunk(x, pos, kv if kv is not None else self.kv)
+        torch.cuda.synchronize()
+        return to_numpy(y)
+
+    def run_both(self, hidden_np, chunks, reset=True):
+        """Feeds the chunks to both sides; returns (gpu_out, oracle_out) concatenated over the chunks."""
+        if reset:
+            self.kv.reset()
+            self.oracle.reset()
+        g, o, p = [], [], len(self.kv)
+        row = 0
+        for n in chunks:
+            h = hidden_np[row:row + n]
+            g.append(self.gpu_chunk(h, p))
+            o.append(self.oracle.prefill_chunk(h, p))
+            p += n
+            row += n
+        return np.concatenate(g, axis=0), np.concatenate(o, axis=0)
+
+    def kv_gpu(self):
+        return to_numpy(self.kv.view())
+
+    def check(self, got, want, what=""):
+        if self.dtype == "f32":
+            assert np.max(np.abs(got - want)) <= F32_MAX_ABS, (what, float(np.max(np.abs(got - want))))
+            assert rel_l2(got, want) <= F32_REL_L2, (what, rel_l2(got, want))
+        else:
+            assert np.all(np.isfinite(got)), what
+            assert rel_l2(got, want) <= BF16_REL_L2, (what, rel_l2(got, want))

@@ -1,0 +1,339 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI, on the same seeded inputs.
+
+Bars: fp32 check mode max-abs <= 1e-3 and rel-L2 <= 1e-4; bf16 rel-L2 <= 2e-2 on hidden_out and on the
+cached K/V values; which cache slots are written, and nothing else, bit-exact.
+"""
+import numpy as np
+import pytest
+
+from helpers import BF16_REL_L2, Pair, rel_l2, to_numpy
+from paper_2504_08242_amd import binding as jb
+from paper_2504_08242_amd import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def kv_bits(kv):
+    torch = torch_mod()
+    v = kv.view()
+    return v.view(torch.int32 if kv.dtype == "f32" else torch.int16).cpu().numpy().copy()
+
+
+def fill_sentinel(kv):
+    torch = torch_mod()
+    if kv.dtype == "f32":
+        kv.buf.view(torch.int32).fill_(0x7FC12345)  # a NaN payload no kernel produces
+    else:
+        kv.buf.view(torch.int16).fill_(0x7FC1)
+    torch.cuda.synchronize()
+
+
+def assert_only_slots_changed(before, after, lo, hi, what=""):
+    """Slots [lo, hi) of every (layer, K|V, head) changed, all others are bit-identical."""
+    assert np.array_equal(before[:, :, :, :lo], after[:, :, :, :lo]), what
+    assert np.array_equal(before[:, :, :, hi:], after[:, :, :, hi:]), what
+    changed = before[:, :, :, lo:hi] != after[:, :, :, lo:hi]
+    assert changed.all(), what  # sentinel is a NaN pattern: every written element differs
+
+
+# ------------------------------------------------------------------------------------------------
+# fp32 check mode
+# ------------------------------------------------------------------------------------------------
+def test_c1_tiny_stage_four_chunks_and_one_shot():
+    """Config 1: 2 layers, d=256, 4x64 heads, FFN 688; 128 tokens as 4x32, and one shot."""
+    p = Pair(si.TINY, "f32", seed=0, max_positions=128, max_chunk_tokens=128)
+    hidden = p.hidden(128)
+    g4, o4 = p.run_both(hidden, [32, 32, 32, 32])
+    p.check(g4, o4, "4x32")
+    kv4 = p.kv_gpu()
+    p.check(kv4, p.oracle.kv, "kv 4x32")
+    g1, o1 = p.run_both(hidden, [128])
+    p.check(g1, o1, "1x128")
+    p.check(g1, o4, "one-shot vs chunked oracle")
+    p.check(g4, g1, "chunked vs one-shot on the GPU")
+    p.check(p.kv_gpu(), kv4, "kv one-shot vs chunked")
+
+
+def test_f32_ragged_chunks_write_exactly_their_cache_slots():
+    cfg = dict(si.TINY, n_layers=3)
+    p = Pair(cfg, "f32", seed=5, max_positions=140, max_chunk_tokens=70, weight_std=1.0 / 16.0)
+    hidden = p.hidden(131)
+    fill_sentinel(p.kv)
+    pos, outs = 0, []
+    for n in [1, 5, 37, 64, 3, 21]:
+        before = kv_bits(p.kv)
+        g = p.gpu_chunk(hidden[pos:pos + n], pos)
+        after = kv_bits(p.kv)
+        assert_only_slots_changed(before, after, pos, pos + n, f"chunk at {pos}")
+        o = p.oracle.prefill_chunk(hidden[pos:pos + n], pos)
+        p.check(g, o, f"chunk at {pos}")
+        pos += n
+        assert len(p.kv) == pos
+    p.check(p.kv_gpu()[:, :, :, :pos], p.oracle.kv[:, :, :, :pos], "kv")
+
+
+def test_f32_odd_shapes():
+    cfg = dict(n_layers=2, d_model=120, n_heads=3, head_dim=40, d_ffn=172, rms_eps=1e-6, rope_theta=500.0)
+    p = Pair(cfg, "f32", seed=8, max_positions=40, max_chunk_tokens=33, weight_std=0.09)
+    hidden = p.hidden(40)
+    g, o = p.run_both(hidden, [33, 7])
+    p.check(g, o)
+    p.check(p.kv_gpu(), p.oracle.kv, "kv")
+
+
+def test_f32_zero_output_projections_pass_input_through_bitwise():
+    cfg = si.TINY
+    layers = si.make_layers(cfg, seed=2)
+    for w in layers:
+        w["wo"] = np.zeros_like(w["wo"])
+        w["w_down"] = np.zeros_like(w["w_down"])
+    p = Pair(cfg, "f32", seed=2, max_positions=16, max_chunk_tokens=16, layers_np=layers)
+    hidden = p.hidden(16)
+    g = p.gpu_chunk(hidden, 0)
+    assert np.array_equal(g, hidden)
+
+
+def test_error_codes_through_prefill_and_cache_length_bookkeeping():
+    torch = torch_mod()
+    p = Pair(si.TINY, "f32", seed=1, max_positions=48, max_chunk_tokens=32)
+    x = torch.from_numpy(p.hidden(32)).cuda()
+    st, kv = p.stage, p.kv
+    with pytest.raises(jb.JupiterError) as e:
+        st.prefill_chunk(x, 1, kv)  # hole
+    assert e.value.status == jb.JUP_EPOS and len(kv) == 0
+    st.prefill_chunk(x, 0, kv)
+    assert len(kv) == 32
+    with pytest.raises(jb.JupiterError) as e:
+        st.prefill_chunk(x, 32, kv)  # 32 + 32 > 48
+    assert e.value.status == jb.JUP_ECAP and len(kv) == 32
+    with pytest.raises(jb.JupiterError) as e:
+        st.prefill_chunk(torch.zeros(33, 256, device="cuda"), 0, kv)  # above max_chunk_tokens
+    assert e.value.status == jb.JUP_ECAP
+    st.prefill_chunk(x[:0], 32, kv)  # empty chunk: no-op
+    assert len(kv) == 32
+    st.prefill_chunk(x[:16], 16, kv)  # overwrite from 16: implicit truncate
+    assert len(kv) == 32
+    st.prefill_chunk(x[:4], 8, kv)
+    assert len(kv) == 12
+    other = jb.KvCache(dict(si.TINY, n_heads=2, head_dim=128), "f32", 48)
+    with pytest.raises(jb.JupiterError) as e:
+        st.prefill_chunk(x, 0, other)
+    assert e.value.status == jb.JUP_EINVAL
+    torch.cuda.synchronize()
+
+
+def test_f32_hidden_out_may_alias_hidden_in():
+    torch = torch_mod()
+    p = Pair(si.TINY, "f32", seed=3, max_positions=24, max_chunk_tokens=24)
+    h = p.hidden(24)
+    want = p.gpu_chunk(h, 0)
+    p.kv.reset()
+    x = torch.from_numpy(h).cuda()
+    p.stage.prefill_chunk(x, 0, p.kv, hidden_out=x)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_numpy(x), want)
+
+
+def test_f32_truncate_after_rejected_candidates_equals_never_appending_them():
+    """Speculative verification (Sec. V-A steps 3 and 5): candidates are cached, the rejected ones removed."""
+    p = Pair(si.TINY, "f32", seed=4, max_positions=64, max_chunk_tokens=32)
+    h = p.hidden(40)
+    cand = p.hidden(5, tag=1)
+    p.gpu_chunk(h[:20], 0)
+    p.gpu_chunk(cand, 20)          # 1 token + 4 drafts
+    p.kv.truncate(22)              # two accepted
+    a = p.gpu_chunk(h[20:30], 22)
+    kv_a = kv_bits(p.kv)[:, :, :, :32]
+    p.kv.reset()
+    p.gpu_chunk(h[:20], 0)
+    p.gpu_chunk(cand[:2], 20)
+    b = p.gpu_chunk(h[20:30], 22)
+    assert np.array_equal(a, b)
+    assert np.array_equal(kv_a, kv_bits(p.kv)[:, :, :, :32])
+
+
+def run_fork_case(p, n_prefix, n_private, n_chunk, n_branches):
+    """Shared prompt prefix, per-branch private tokens, then one small chunk per branch (Sec. V-B)."""
+    cfg = p.cfg
+    prefix = p.hidden(n_prefix)
+    p.kv.reset()
+    p.oracle.reset()
+    pos = 0
+    step = p.stage.max_chunk_tokens
+    while pos < n_prefix:  # prefill the shared prompt on both sides
+        n = min(step, n_prefix - pos)
+        p.gpu_chunk(prefix[pos:pos + n], pos)
+        p.oracle.prefill_chunk(prefix[pos:pos + n], pos)
+        pos += n
+    parent_bits = kv_bits(p.kv)
+    oracle_prefix_kv = p.oracle.kv.copy()
+    forks = [p.kv.fork(n_prefix, n_prefix + n_private + n_chunk) for _ in range(n_branches)]
+    for b, fk in enumerate(forks):
+        assert len(fk) == n_prefix
+        priv = p.hidden(n_private, tag=100 + b)
+        chunk = p.hidden(n_chunk, tag=200 + b)
+        p.oracle.kv[...] = oracle_prefix_kv  # the oracle works on an unshared copy of the prefix
+        o_priv = p.oracle.prefill_chunk(priv, n_prefix)
+        o_chunk = p.oracle.prefill_chunk(chunk, n_prefix + n_private)
+        g_priv = p.gpu_chunk(priv, n_prefix, kv=fk)
+        g_chunk = p.gpu_chunk(chunk, n_prefix + n_private, kv=fk)
+        p.check(g_priv, o_priv, f"branch {b} private tokens")
+        p.check(g_chunk, o_chunk, f"branch {b} chunk")
+        assert len(fk) == n_prefix + n_private + n_chunk
+        own = to_numpy(fk.view())
+        p.check(own, p.oracle.kv[:, :, :, n_prefix:n_prefix + n_private + n_chunk], f"branch {b} private kv")
+        with pytest.raises(jb.JupiterError) as e:
+            p.stage.prefill_chunk(p_tensor(p, chunk), n_prefix - 1, fk)  # inside the shared prefix
+        assert e.value.status == jb.JUP_EPOS
+    assert np.array_equal(parent_bits, kv_bits(p.kv))  # the shared prefix was only read
+    with pytest.raises(jb.JupiterError) as e:
+        p.kv.truncate(n_prefix - 1)  # forks still share it
+    assert e.value.status == jb.JUP_EPOS
+    for fk in forks:
+        fk.destroy()
+    p.kv.truncate(n_prefix - 1)
+
+
+def p_tensor(p, a):
+    torch = torch_mod()
+    return torch.from_numpy(a).to(device="cuda:0", dtype=p.td)
+
+
+def test_f32_forked_caches_share_the_prompt_prefix():
+    p = Pair(si.TINY, "f32", seed=6, max_positions=40, max_chunk_tokens=16)
+    run_fork_case(p, n_prefix=37, n_private=9, n_chunk=5, n_branches=3)
+
+
+def test_same_call_twice_is_bitwise_identical():
+    p = Pair(si.TINY, "f32", seed=7, max_positions=64, max_chunk_tokens=64)
+    h = p.hidden(64)
+    a = p.gpu_chunk(h, 0)
+    p.kv.reset()
+    b = p.gpu_chunk(h, 0)
+    assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------------------------------------
+# bf16 matrix-core path
+# ------------------------------------------------------------------------------------------------
+LLAMA7B_2L = dict(si.LLAMA7B_STAGE, n_layers=2)
+
+
+def test_bf16_two_layer_7b_shape_ragged_chunks_and_cache_slots():
+    p = Pair(LLAMA7B_2L, "bf16", seed=11, max_positions=300, max_chunk_tokens=128)
+    hidden = p.hidden(277)
+    fill_sentinel(p.kv)
+    pos = 0
+    for n in [64, 37, 5, 128, 1, 42]:
+        before = kv_bits(p.kv)
+        g = p.gpu_chunk(hidden[pos:pos + n], pos)
+        after = kv_bits(p.kv)
+        assert_only_slots_changed(before, after, pos, pos + n, f"chunk at {pos}")
+        o = p.oracle.prefill_chunk(hidden[pos:pos + n], pos)
+        p.check(g, o, f"chunk at {pos}")
+        pos += n
+    kv = p.kv_gpu()[:, :, :, :pos]
+    for l in range(2):
+        for which in range(2):
+            assert rel_l2(kv[l, which], p.oracle.kv[l, which, :, :pos]) <= BF16_REL_L2, (l, which)
+
+
+def test_bf16_layer0_cache_is_bit_identical_across_chunkings_and_runs():
+    """K and V of the first layer are row-local functions of the input: chunking must not change a bit."""
+    p = Pair(LLAMA7B_2L, "bf16", seed=12, max_positions=256, max_chunk_tokens=256)
+    hidden = p.hidden(256)
+    outs, kvs = [], []
+    for chunks in ([256], [64, 64, 64, 64], [100, 29, 127], [256]):
+        p.kv.reset()
+        pos, g = 0, []
+        for n in chunks:
+            g.append(p.gpu_chunk(hidden[pos:pos + n], pos))
+            pos += n
+        outs.append(np.concatenate(g))
+        kvs.append(kv_bits(p.kv))
+    assert np.array_equal(outs[0], outs[3]) and np.array_equal(kvs[0], kvs[3])  # same call twice
+    for i in (1, 2):
+        assert np.array_equal(kvs[0][0], kvs[i][0]), "layer-0 cache differs between chunkings"
+        assert rel_l2(outs[i], outs[0]) <= BF16_REL_L2
+
+
+def test_bf16_forked_caches_share_the_prompt_prefix_small():
+    p = Pair(LLAMA7B_2L, "bf16", seed=13, max_positions=80, max_chunk_tokens=64)
+    run_fork_case(p, n_prefix=70, n_private=11, n_chunk=5, n_branches=2)
+
+
+def test_bf16_zero_output_projections_pass_input_through_bitwise():
+    cfg = LLAMA7B_2L
+    layers = si.make_layers(cfg, seed=14, bf16=True)
+    for w in layers:
+        w["wo"] = np.zeros_like(w["wo"])
+        w["w_down"] = np.zeros_like(w["w_down"])
+    p = Pair(cfg, "bf16", seed=14, max_positions=70, max_chunk_tokens=70, layers_np=layers)
+    hidden = p.hidden(70)
+    assert np.array_equal(p.gpu_chunk(hidden, 0), hidden)
+
+
+def test_c2_7b_stage_512_tokens_in_8_chunks_of_64():
+    """Config 2: 8 layers of Llama-2-7B shape, bf16, 512-token prompt as 8 chunks of 64."""
+    p = Pair(si.LLAMA7B_STAGE, "bf16", seed=20, max_positions=512, max_chunk_tokens=64)
+    hidden = p.hidden(512)
+    g, o = p.run_both(hidden, [64] * 8)
+    p.check(g, o, "hidden_out")
+    for c in range(8):
+        p.check(g[c * 64:(c + 1) * 64], o[c * 64:(c + 1) * 64], f"chunk {c}")
+    kv = p.kv_gpu()
+    for l in range(8):
+        assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, l
+
+
+@pytest.mark.slow
+def test_c3_7b_stage_2048_tokens_chunk_sizes_128_256_512():
+    """Config 3: the same stage, 2048-token prompt, chunkings 16x128, 8x256, 4x512 against one oracle run
+    (the oracle's own chunk invariance is pinned on the CPU)."""
+    p = Pair(si.LLAMA7B_STAGE, "bf16", seed=30, max_positions=2048, max_chunk_tokens=512)
+    hidden = p.hidden(2048)
+    o = []
+    for c in range(4):
+        o.append(p.oracle.prefill_chunk(hidden[c * 512:(c + 1) * 512], c * 512))
+        print(f"oracle chunk {c} done", flush=True)
+    o = np.concatenate(o)
+    for size in (512, 256, 128):
+        p.kv.reset()
+        g = np.concatenate([p.gpu_chunk(hidden[s:s + size], s) for s in range(0, 2048, size)])
+        p.check(g, o, f"chunk size {size}")
+        p.check(g[-size:], o[-size:], f"last chunk of size {size}")
+        kv = p.kv_gpu()
+        for l in range(8):
+            assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, (size, l)
+
+
+@pytest.mark.slow
+def test_c4_13b_stage_1024_tokens_in_8_chunks_of_128():
+    """Config 4: 10 layers of Llama-2-13B shape, bf16, 1024 tokens as 8x128."""
+    p = Pair(si.LLAMA13B_STAGE, "bf16", seed=40, max_positions=1024, max_chunk_tokens=128)
+    hidden = p.hidden(1024)
+    g, o = [], []
+    for c in range(8):
+        h = hidden[c * 128:(c + 1) * 128]
+        g.append(p.gpu_chunk(h, c * 128))
+        o.append(p.oracle.prefill_chunk(h, c * 128))
+        p.check(g[-1], o[-1], f"chunk {c}")
+        print(f"chunk {c} done", flush=True)
+    p.check(np.concatenate(g), np.concatenate(o), "hidden_out")
+    kv = p.kv_gpu()
+    for l in range(10):
+        assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, l
+
+
+@pytest.mark.slow
+def test_c5_decode_sized_chunks_on_eight_branches_sharing_a_512_token_prefix():
+    """Config 5: 8 branches share a 512-token prompt cache, hold 64 private tokens each, and submit a
+    5-token chunk (1 token + 4 drafts) with a causal mask inside the chunk."""
+    p = Pair(si.LLAMA7B_STAGE, "bf16", seed=50, max_positions=512, max_chunk_tokens=128)
+    run_fork_case(p, n_prefix=512, n_private=64, n_chunk=5, n_branches=8)
