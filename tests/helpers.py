@@ -25,13 +25,14 @@ def to_numpy(t):
 class Pair:
     """An oracle stage and a GPU stage built from the same seeded tensors."""
 
-    def __init__(self, cfg, dtype, seed, max_positions, max_chunk_tokens, weight_std=0.02, layers_np=None):
+    def __init__(self, cfg, dtype, seed, max_positions, max_chunk_tokens, weight_std=0.02, layers_np=None,
+                 oracle_positions=None):
         import torch
         self.cfg, self.dtype, self.seed = dict(cfg), dtype, seed
         bf16 = dtype == "bf16"
         self.layers_np = layers_np if layers_np is not None else si.make_layers(cfg, seed, bf16=bf16,
                                                                                 weight_std=weight_std)
-        self.oracle = oracle.OracleStage(cfg, self.layers_np, max_positions)
+        self.oracle = oracle.OracleStage(cfg, self.layers_np, oracle_positions or max_positions)
         dev_layers = jb.upload_layers(self.layers_np, dtype)
         self.stage = jb.Stage(cfg, dtype, dev_layers, max_chunk_tokens)
         torch.cuda.synchronize()

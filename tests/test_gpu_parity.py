@@ -188,6 +188,7 @@ def run_fork_case(p, n_prefix, n_private, n_chunk, n_branches):
         assert len(fk) == n_prefix + n_private + n_chunk
         own = to_numpy(fk.view())
         p.check(own, p.oracle.kv[:, :, :, n_prefix:n_prefix + n_private + n_chunk], f"branch {b} private kv")
+        assert np.array_equal(p.oracle.kv[:, :, :, :n_prefix], oracle_prefix_kv[:, :, :, :n_prefix])
         with pytest.raises(jb.JupiterError) as e:
             p.stage.prefill_chunk(p_tensor(p, chunk), n_prefix - 1, fk)  # inside the shared prefix
         assert e.value.status == jb.JUP_EPOS
@@ -206,7 +207,7 @@ def p_tensor(p, a):
 
 
 def test_f32_forked_caches_share_the_prompt_prefix():
-    p = Pair(si.TINY, "f32", seed=6, max_positions=40, max_chunk_tokens=16)
+    p = Pair(si.TINY, "f32", seed=6, max_positions=40, max_chunk_tokens=16, oracle_positions=51)
     run_fork_case(p, n_prefix=37, n_private=9, n_chunk=5, n_branches=3)
 
 
@@ -264,7 +265,7 @@ def test_bf16_layer0_cache_is_bit_identical_across_chunkings_and_runs():
 
 
 def test_bf16_forked_caches_share_the_prompt_prefix_small():
-    p = Pair(LLAMA7B_2L, "bf16", seed=13, max_positions=80, max_chunk_tokens=64)
+    p = Pair(LLAMA7B_2L, "bf16", seed=13, max_positions=80, max_chunk_tokens=64, oracle_positions=86)
     run_fork_case(p, n_prefix=70, n_private=11, n_chunk=5, n_branches=2)
 
 
@@ -335,5 +336,5 @@ def test_c4_13b_stage_1024_tokens_in_8_chunks_of_128():
 def test_c5_decode_sized_chunks_on_eight_branches_sharing_a_512_token_prefix():
     """Config 5: 8 branches share a 512-token prompt cache, hold 64 private tokens each, and submit a
     5-token chunk (1 token + 4 drafts) with a causal mask inside the chunk."""
-    p = Pair(si.LLAMA7B_STAGE, "bf16", seed=50, max_positions=512, max_chunk_tokens=128)
+    p = Pair(si.LLAMA7B_STAGE, "bf16", seed=50, max_positions=512, max_chunk_tokens=128, oracle_positions=581)
     run_fork_case(p, n_prefix=512, n_private=64, n_chunk=5, n_branches=8)
