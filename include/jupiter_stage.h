@@ -202,6 +202,39 @@ JUP_API jup_status_t jup_kv_destroy(jup_kv_t *kv);
 JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hidden_in, int32_t n_tokens,
                                      int32_t pos_offset, jup_kv_t *kv, void *hidden_out, void *stream);
 
+/* ---- per-kernel timing (benchmarks) ----------------------------------------------------------- */
+
+/*
+ * Kernels of one layer of the JUP_BF16 path, in launch order.  The profiler of the paper records
+ * per-layer run-time traces of the prefill (Sec. III, step 1); these ids let a benchmark time one
+ * kernel class in place, with HIP events recorded on the stream the kernel is launched on.
+ */
+typedef enum {
+    JUP_K_RMSNORM = 0,
+    JUP_K_GEMM_QKV = 1,    /* QKV projection + rotary + KV append */
+    JUP_K_ATTENTION = 2,   /* prefix + causal chunk attention */
+    JUP_K_GEMM_O = 3,      /* output projection + residual */
+    JUP_K_GEMM_GATE_UP = 4, /* gate/up projection + SwiGLU */
+    JUP_K_GEMM_DOWN = 5,   /* down projection + residual */
+    JUP_K_COUNT = 6
+} jup_kernel_id_t;
+
+/*
+ * Starts timing every launch of kernel class `kernel_id` made by later jup_stage_prefill_chunk()
+ * calls on this stage: an event pair brackets each launch (at most max_launches pairs; further
+ * launches run untimed and are counted as dropped).  kernel_id = -1 stops tracing and releases the
+ * events.  Tracing perturbs the stream slightly: time whole calls with tracing off.
+ * Errors: JUP_EINVAL (NULL stage, bad id, max_launches <= 0), JUP_ENOMEM, JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_stage_trace(jup_stage_t *stage, int32_t kernel_id, int32_t max_launches);
+
+/*
+ * Waits for the recorded events, returns the summed duration in milliseconds and the number of
+ * launches timed / dropped (host pointers, each may be NULL), and rewinds the event pool.
+ * JUP_EINVAL if the stage is not tracing.
+ */
+JUP_API jup_status_t jup_stage_trace_read(jup_stage_t *stage, double *total_ms, int32_t *launches, int32_t *dropped);
+
 /* Message of the last error on this thread ("" if none). Never NULL. */
 JUP_API const char *jup_last_error(void);
 

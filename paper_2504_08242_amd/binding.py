@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libjupiter_stage.so")
 JUP_F32, JUP_BF16 = 0, 1
 JUP_OK, JUP_EINVAL, JUP_EPOS, JUP_ECAP, JUP_EDEVICE, JUP_ENOMEM = 0, -1, -2, -3, -4, -5
 STATUS_NAMES = {0: "JUP_OK", -1: "JUP_EINVAL", -2: "JUP_EPOS", -3: "JUP_ECAP", -4: "JUP_EDEVICE", -5: "JUP_ENOMEM"}
+KERNEL_IDS = {"rmsnorm": 0, "gemm_qkv": 1, "attention": 2, "gemm_o": 3, "gemm_gate_up": 4, "gemm_down": 5}
 WEIGHT_NAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_mlp")
 
 
@@ -63,6 +64,9 @@ def lib():
             "jup_kv_check_append": (i32, [vp, i32, i32]),
             "jup_kv_destroy": (i32, [vp]),
             "jup_stage_prefill_chunk": (i32, [vp, vp, i32, i32, vp, vp, vp]),
+            "jup_stage_trace": (i32, [vp, i32, i32]),
+            "jup_stage_trace_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32),
+                                           ctypes.POINTER(i32)]),
             "jup_last_error": (ctypes.c_char_p, []),
         }
         for name, (res, args) in sig.items():
@@ -201,6 +205,16 @@ class Stage:
                                              kv.handle, ctypes.c_void_p(hidden_out.data_ptr()),
                                              _stream_handle(stream)))
         return hidden_out
+
+    def trace(self, kernel_id, max_launches=4096):
+        """Times every launch of one kernel class (KERNEL_IDS) with HIP events; -1 stops."""
+        _check(lib().jup_stage_trace(self.handle, int(kernel_id), int(max_launches)))
+
+    def trace_read(self):
+        """(total milliseconds, launches timed, launches dropped) since the last read."""
+        ms, n, dr = ctypes.c_double(), ctypes.c_int32(), ctypes.c_int32()
+        _check(lib().jup_stage_trace_read(self.handle, ctypes.byref(ms), ctypes.byref(n), ctypes.byref(dr)))
+        return ms.value, n.value, dr.value
 
     def destroy(self):
         if self.handle:

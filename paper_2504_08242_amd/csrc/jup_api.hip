@@ -134,6 +134,7 @@ jup_status_t jup_stage_create(const jup_stage_config_t* cfg, const jup_layer_wei
     st->max_chunk_tokens = max_chunk_tokens;
     st->pl = jup::packed_layout(*cfg);
     st->wl = jup::workspace_layout(*cfg, max_chunk_tokens);
+    st->trace = nullptr;
 
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
@@ -170,7 +171,70 @@ jup_status_t jup_stage_create(const jup_stage_config_t* cfg, const jup_layer_wei
     return JUP_OK;
 }
 
-void jup_stage_destroy(jup_stage_t* stage) { delete stage; }
+static void trace_release(jup_stage* st) {
+    if (!st->trace) return;
+    for (int i = 0; i < 2 * st->trace->capacity; ++i)
+        if (st->trace->ev[i]) (void)hipEventDestroy(st->trace->ev[i]);
+    delete[] st->trace->ev;
+    delete st->trace;
+    st->trace = nullptr;
+}
+
+void jup_stage_destroy(jup_stage_t* stage) {
+    if (!stage) return;
+    trace_release(stage);
+    delete stage;
+}
+
+jup_status_t jup_stage_trace(jup_stage_t* stage, int32_t kernel_id, int32_t max_launches) {
+    if (!stage) return fail(JUP_EINVAL, "jup_stage_trace: stage is NULL");
+    if (kernel_id == -1) {
+        trace_release(stage);
+        return JUP_OK;
+    }
+    if (kernel_id < 0 || kernel_id >= JUP_K_COUNT) return fail(JUP_EINVAL, "jup_stage_trace: bad kernel id %d", kernel_id);
+    if (max_launches <= 0 || max_launches > (1 << 20))
+        return fail(JUP_EINVAL, "jup_stage_trace: max_launches=%d out of range", max_launches);
+    trace_release(stage);
+    jup_trace* t = new (std::nothrow) jup_trace();
+    if (!t) return fail(JUP_ENOMEM, "jup_stage_trace: out of host memory");
+    t->kernel_id = kernel_id;
+    t->capacity = max_launches;
+    t->used = t->dropped = 0;
+    t->ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_launches]();
+    if (!t->ev) {
+        delete t;
+        return fail(JUP_ENOMEM, "jup_stage_trace: out of host memory");
+    }
+    stage->trace = t;
+    for (int i = 0; i < 2 * max_launches; ++i) {
+        hipError_t e = hipEventCreate(&t->ev[i]);
+        if (e != hipSuccess) {
+            t->ev[i] = nullptr;
+            trace_release(stage);
+            return fail(JUP_EDEVICE, "jup_stage_trace: %s", hipGetErrorString(e));
+        }
+    }
+    return JUP_OK;
+}
+
+jup_status_t jup_stage_trace_read(jup_stage_t* stage, double* total_ms, int32_t* launches, int32_t* dropped) {
+    if (!stage || !stage->trace) return fail(JUP_EINVAL, "jup_stage_trace_read: the stage is not tracing");
+    jup_trace* t = stage->trace;
+    double sum = 0.0;
+    for (int i = 0; i < t->used; ++i) {
+        hipError_t e = hipEventSynchronize(t->ev[2 * i + 1]);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, t->ev[2 * i], t->ev[2 * i + 1]);
+        if (e != hipSuccess) return fail(JUP_EDEVICE, "jup_stage_trace_read: %s", hipGetErrorString(e));
+        sum += ms;
+    }
+    if (total_ms) *total_ms = sum;
+    if (launches) *launches = t->used;
+    if (dropped) *dropped = t->dropped;
+    t->used = t->dropped = 0;
+    return JUP_OK;
+}
 
 // ---- KV cache ---------------------------------------------------------------------------------
 

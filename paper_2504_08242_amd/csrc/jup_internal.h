@@ -62,6 +62,15 @@ struct jup_kv {
     int32_t max_child_shared; // largest n_shared among live children (recomputed lazily is overkill: kept as a bound)
 };
 
+// Optional per-kernel timing with HIP events on the caller's stream (benchmarks only).
+struct jup_trace {
+    int32_t kernel_id;  // jup_kernel_id_t being timed
+    hipEvent_t* ev;     // pairs (start, stop)
+    int32_t capacity;   // number of pairs
+    int32_t used;
+    int32_t dropped;    // launches not timed because the pool was full
+};
+
 struct jup_stage {
     jup_stage_config_t cfg;
     void* packed;
@@ -69,9 +78,28 @@ struct jup_stage {
     int32_t max_chunk_tokens;
     jup::PackedLayout pl;
     jup::WorkspaceLayout wl;
+    jup_trace* trace;  // NULL when tracing is off
 };
 
 namespace jup {
+
+// Brackets one kernel launch with a pair of events when the stage traces that kernel id.
+struct TraceScope {
+    jup_trace* t;
+    hipStream_t s;
+    int slot;
+    TraceScope(const jup_stage& st, int kernel_id, hipStream_t stream) : t(st.trace), s(stream), slot(-1) {
+        if (!t || t->kernel_id != kernel_id) { t = nullptr; return; }
+        if (t->used >= t->capacity) { t->dropped++; t = nullptr; return; }
+        slot = t->used++;
+        (void)hipEventRecord(t->ev[2 * slot], s);
+    }
+    ~TraceScope() {
+        if (t) (void)hipEventRecord(t->ev[2 * slot + 1], s);
+    }
+    TraceScope(const TraceScope&) = delete;
+    TraceScope& operator=(const TraceScope&) = delete;
+};
 
 // ---- check-mode (fp32) path: kernels_f32.hip ------------------------------------------------------
 hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int pos, const KvView& kv,

@@ -549,38 +549,59 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         const u16* g1 = (const u16*)(wb + st.pl.g_attn);
         const u16* g2 = (const u16*)(wb + st.pl.g_mlp);
 
+        {
+        TraceScope ts(st, JUP_K_RMSNORM, s);
         if (l == 0)
             hipLaunchKernelGGL(rmsnorm_bf16<true>, dim3(n), dim3(256), 0, s, hidden_in, x32, g1, xn, d, c.rms_eps);
         else
             hipLaunchKernelGGL(rmsnorm_bf16<false>, dim3(n), dim3(256), 0, s, (const void*)x32, x32, g1, xn, d,
                                c.rms_eps);
+        }
 
         GemmArgs a{};
         a.A = xn; a.W = (const u16*)(wb + st.pl.wqkv); a.M = n; a.N = 3 * d; a.K = d;
         a.q_out = q; a.rope = rope; a.kv = kv; a.layer = l; a.n_heads = H; a.d_model = d; a.pos0 = pos;
-        launch_gemm<EPI_QKV>(a, s);
+        {
+            TraceScope ts(st, JUP_K_GEMM_QKV, s);
+            launch_gemm<EPI_QKV>(a, s);
+        }
 
-        if (n <= 32)
-            hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3((n + 31) / 32, H), dim3(256), 0, s, q, o, n, d, H, pos, kv,
-                               l, scale_log2e);
-        else
-            hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64, H), dim3(256), 0, s, q, o, n, d, H, pos, kv,
-                               l, scale_log2e);
+        {
+            TraceScope ts(st, JUP_K_ATTENTION, s);
+            if (n <= 32)
+                hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3((n + 31) / 32, H), dim3(256), 0, s, q, o, n, d, H, pos,
+                                   kv, l, scale_log2e);
+            else
+                hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64, H), dim3(256), 0, s, q, o, n, d, H, pos,
+                                   kv, l, scale_log2e);
+        }
 
         GemmArgs b{};
         b.A = o; b.W = (const u16*)(wb + st.pl.wo); b.M = n; b.N = d; b.K = d; b.x32 = x32;
-        launch_gemm<EPI_RESID>(b, s);
-
-        hipLaunchKernelGGL(rmsnorm_bf16<false>, dim3(n), dim3(256), 0, s, (const void*)x32, x32, g2, xn, d, c.rms_eps);
+        {
+            TraceScope ts(st, JUP_K_GEMM_O, s);
+            launch_gemm<EPI_RESID>(b, s);
+        }
+        {
+            TraceScope ts(st, JUP_K_RMSNORM, s);
+            hipLaunchKernelGGL(rmsnorm_bf16<false>, dim3(n), dim3(256), 0, s, (const void*)x32, x32, g2, xn, d,
+                               c.rms_eps);
+        }
 
         GemmArgs g{};
         g.A = xn; g.W = (const u16*)(wb + st.pl.wgu); g.M = n; g.N = 2 * f; g.K = d; g.act = act;
-        launch_gemm<EPI_SWIGLU>(g, s);
+        {
+            TraceScope ts(st, JUP_K_GEMM_GATE_UP, s);
+            launch_gemm<EPI_SWIGLU>(g, s);
+        }
 
         GemmArgs dn{};
         dn.A = act; dn.W = (const u16*)(wb + st.pl.wdown); dn.M = n; dn.N = d; dn.K = f; dn.x32 = x32;
         dn.final_out = (l == c.n_layers - 1) ? (u16*)hidden_out : nullptr;
-        launch_gemm<EPI_RESID>(dn, s);
+        {
+            TraceScope ts(st, JUP_K_GEMM_DOWN, s);
+            launch_gemm<EPI_RESID>(dn, s);
+        }
     }
     return hipGetLastError();
 }
