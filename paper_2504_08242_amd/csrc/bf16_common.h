@@ -1,0 +1,82 @@
+// Types and small device helpers shared by the bf16 (matrix-core) translation units.
+#pragma once
+
+#include "jup_internal.h"
+
+namespace jup {
+
+typedef unsigned short u16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ inline u16 f2bf(float f) {
+    __bf16 b = (__bf16)f;  // round to nearest even
+    return __builtin_bit_cast(u16, b);
+}
+__device__ inline float bf2f(u16 b) { return __uint_as_float((unsigned)b << 16); }
+__device__ inline unsigned pack_bf16x2(float lo, float hi) { return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16); }
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Cache plane (layer, K|V, head) -> row pointers.  Positions below n_shared live in the parent's buffer.
+__device__ inline const u16* kv_row_bf16(const KvView& kv, size_t plane, int pos) {
+    if (pos < kv.n_shared) return (const u16*)kv.parent + (plane * kv.parent_cap + (size_t)pos) * 128;
+    return (const u16*)kv.own + (plane * kv.own_cap + (size_t)(pos - kv.n_shared)) * 128;
+}
+__device__ inline u16* kv_slot_bf16(const KvView& kv, int layer, int which, int head, int n_heads, int pos) {
+    const size_t plane = ((size_t)layer * 2 + which) * n_heads + head;
+    return (u16*)kv.own + (plane * kv.own_cap + (size_t)(pos - kv.n_shared)) * 128;
+}
+
+// ---- GEMM (bf16_gemm.hip) -----------------------------------------------------------------------
+enum { EPI_QKV = 0, EPI_PARTIAL = 1, EPI_SWIGLU = 2 };
+
+struct GemmArgs {
+    const u16* A;  // [M, K] activations, row-major
+    const u16* W;  // [N, K] packed weights, row-major
+    int M, N, K;
+    int m_tiles, n_tiles, splits;  // grid = m_tiles * n_tiles * splits workgroups
+    int n_stride;                  // columns between consecutive N tiles (tile width actually owned)
+    int kt_per_split;              // K tiles of 32 per split
+    int xcd_swizzle;               // 1: workgroup ids are spread so that one XCD owns whole (n, split) groups
+    // EPI_QKV
+    u16* q_out;          // [M, d_model] rotated queries
+    const float2* rope;  // [M, 64] (cos, sin)
+    KvView kv;
+    int layer, n_heads, d_model, pos0;
+    // EPI_PARTIAL
+    float* partial;  // [splits][M][N] fp32
+    // EPI_SWIGLU
+    u16* act;  // [M, N/2]
+};
+
+enum GemmKind { GEMM_QKV, GEMM_O, GEMM_GATE_UP, GEMM_DOWN };
+
+// Fills the tiling fields of `a` for the given problem and launches.  Returns the number of K splits
+// used (the caller sums that many partial buffers for EPI_PARTIAL).
+int gemm_plan_splits(int M, int N, int K);
+hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s);
+hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s);
+hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s);
+hipError_t gemm_configure();  // raises the dynamic-LDS limit of every instantiation (once per process)
+
+// ---- attention (bf16_attention.hip) ---------------------------------------------------------------
+void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
+                            int layer, hipStream_t s);
+
+// ---- packing, rotary table, reduce + norm (bf16_misc.hip) -------------------------------------------
+void launch_pack_qkv(u16* dst, const u16* wq, const u16* wk, const u16* wv, int d, hipStream_t s);
+void launch_pack_gate_up(u16* dst, const u16* wg, const u16* wu, int d, int f, hipStream_t s);
+void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s);
+// x32 <- (hidden_in ? hidden_in : x32) + sum_s partial[s];  xn <- rmsnorm(x32) * g (if g);  out <- bf16(x32) (if out)
+void launch_reduce_norm(float* x32, const u16* hidden_in, const float* partial, int splits, size_t split_stride,
+                        const u16* g, u16* xn, u16* out, int n, int d, float eps, hipStream_t s);
+
+}  // namespace jup

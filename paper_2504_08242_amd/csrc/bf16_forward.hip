@@ -1,0 +1,105 @@
+// Orchestration of the bf16 (matrix-core) path: one stage forward over one sub-sequence with its
+// cached prefix (Jupiter paper, Sec. IV-A.2); decoder layer of Sec. II-A in its Llama-2 form.
+//
+// Per layer, seven launches on the caller's stream:
+//   reduce+norm  ->  QKV GEMM (+ rotary + KV append)  ->  chunk attention  ->  O GEMM (K-split partials)
+//   ->  reduce+norm  ->  gate/up GEMM (+ SwiGLU)  ->  down GEMM (K-split partials)
+// The projections back to d_model are too narrow to fill 256 CUs with tall tiles, so they split K and
+// write fp32 partial tiles; the next reduce+norm pass adds them to the fp32 residual stream in a fixed
+// order (bitwise reproducible) on its way to the normalised bf16 rows it has to produce anyway.
+#include "bf16_common.h"
+
+namespace jup {
+
+hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s) {
+    const jup_stage_config_t& c = st.cfg;
+    const size_t d = c.d_model, f = c.d_ffn;
+    hipError_t e = gemm_configure();
+    if (e != hipSuccess) return e;
+    for (int l = 0; l < c.n_layers; ++l) {
+        char* base = (char*)st.packed + (size_t)l * st.pl.layer_bytes;
+        const jup_layer_weights_t& w = layers[l];
+        launch_pack_qkv((u16*)(base + st.pl.wqkv), (const u16*)w.wq, (const u16*)w.wk, (const u16*)w.wv, c.d_model, s);
+        launch_pack_gate_up((u16*)(base + st.pl.wgu), (const u16*)w.w_gate, (const u16*)w.w_up, c.d_model, c.d_ffn, s);
+        e = hipMemcpyAsync(base + st.pl.wo, w.wo, d * d * 2, hipMemcpyDeviceToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(base + st.pl.wdown, w.w_down, d * f * 2, hipMemcpyDeviceToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(base + st.pl.g_attn, w.g_attn, d * 2, hipMemcpyDeviceToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(base + st.pl.g_mlp, w.g_mlp, d * 2, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipGetLastError();
+}
+
+hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int pos, const KvView& kv,
+                        void* hidden_out, hipStream_t s) {
+    const jup_stage_config_t& c = st.cfg;
+    const int d = c.d_model, f = c.d_ffn, H = c.n_heads;
+    char* ws = (char*)st.workspace;
+    float* x32 = (float*)(ws + st.wl.x32);
+    u16* xn = (u16*)(ws + st.wl.xn);
+    u16* q = (u16*)(ws + st.wl.q);
+    u16* o = (u16*)(ws + st.wl.o);
+    u16* act = (u16*)(ws + st.wl.act);
+    float* partial = (float*)(ws + st.wl.partial);
+    float2* rope = (float2*)(ws + st.wl.rope);
+    const size_t split_stride = (size_t)n * d;
+
+    if (c.n_layers == 0) return hipMemcpyAsync(hidden_out, hidden_in, (size_t)n * d * 2, hipMemcpyDeviceToDevice, s);
+    launch_rope_table(rope, n, pos, c.rope_theta, s);
+
+    const int splits_o = gemm_plan_splits(n, d, d), splits_down = gemm_plan_splits(n, d, f);
+    hipError_t e = hipSuccess;
+    for (int l = 0; l < c.n_layers && e == hipSuccess; ++l) {
+        const char* wb = (const char*)st.packed + (size_t)l * st.pl.layer_bytes;
+        const u16* g1 = (const u16*)(wb + st.pl.g_attn);
+        const u16* g2 = (const u16*)(wb + st.pl.g_mlp);
+        {
+            TraceScope ts(st, JUP_K_RMSNORM, s);
+            if (l == 0)
+                launch_reduce_norm(x32, (const u16*)hidden_in, nullptr, 0, 0, g1, xn, nullptr, n, d, c.rms_eps, s);
+            else
+                launch_reduce_norm(x32, nullptr, partial, splits_down, split_stride, g1, xn, nullptr, n, d, c.rms_eps,
+                                   s);
+        }
+        {
+            TraceScope ts(st, JUP_K_GEMM_QKV, s);
+            GemmArgs a{};
+            a.A = xn; a.W = (const u16*)(wb + st.pl.wqkv); a.M = n; a.N = 3 * d; a.K = d;
+            a.q_out = q; a.rope = rope; a.kv = kv; a.layer = l; a.n_heads = H; a.d_model = d; a.pos0 = pos;
+            e = launch_gemm_qkv(a, s);
+        }
+        {
+            TraceScope ts(st, JUP_K_ATTENTION, s);
+            launch_chunk_attention(q, o, n, d, H, pos, kv, l, s);
+        }
+        {
+            TraceScope ts(st, JUP_K_GEMM_O, s);
+            GemmArgs a{};
+            a.A = o; a.W = (const u16*)(wb + st.pl.wo); a.M = n; a.N = d; a.K = d; a.partial = partial;
+            if (e == hipSuccess) e = launch_gemm_partial(a, s);
+        }
+        {
+            TraceScope ts(st, JUP_K_RMSNORM, s);
+            launch_reduce_norm(x32, nullptr, partial, splits_o, split_stride, g2, xn, nullptr, n, d, c.rms_eps, s);
+        }
+        {
+            TraceScope ts(st, JUP_K_GEMM_GATE_UP, s);
+            GemmArgs a{};
+            a.A = xn; a.W = (const u16*)(wb + st.pl.wgu); a.M = n; a.N = 2 * f; a.K = d; a.act = act;
+            if (e == hipSuccess) e = launch_gemm_swiglu(a, s);
+        }
+        {
+            TraceScope ts(st, JUP_K_GEMM_DOWN, s);
+            GemmArgs a{};
+            a.A = act; a.W = (const u16*)(wb + st.pl.wdown); a.M = n; a.N = d; a.K = f; a.partial = partial;
+            if (e == hipSuccess) e = launch_gemm_partial(a, s);
+        }
+    }
+    if (e != hipSuccess) return e;
+    // last layer's down-projection partials + residual -> hidden_out
+    launch_reduce_norm(x32, nullptr, partial, splits_down, split_stride, nullptr, nullptr, (u16*)hidden_out, n, d,
+                       c.rms_eps, s);
+    return hipGetLastError();
+}
+
+}  // namespace jup

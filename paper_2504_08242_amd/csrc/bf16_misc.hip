@@ -1,0 +1,124 @@
+// Small memory-bound kernels of the bf16 path: weight packing (once, at stage creation), the rotary
+// table of a chunk, and the fused "sum the K-split partials + residual + RMSNorm" pass.
+#include "bf16_common.h"
+
+namespace jup {
+namespace {
+
+// Q and K heads are stored so that the rotary partners i and i + 64 (Llama half-split pairing) sit in
+// adjacent 16-column blocks: packed row 32j + 16a + c of a head holds original row 16j + c + 64a
+// (j < 4, a in {0,1}, c < 16).  V rows keep their order.
+__device__ inline int rope_packed_to_orig(int packed) {
+    return 16 * (packed >> 5) + (packed & 15) + 64 * ((packed >> 4) & 1);
+}
+
+// dst: [3d, d].  Rows [0,d): Q heads, [d,2d): K heads, [2d,3d): V heads.
+__global__ void pack_qkv(u16* __restrict__ dst, const u16* __restrict__ wq, const u16* __restrict__ wk,
+                         const u16* __restrict__ wv, int d) {
+    const int r = blockIdx.x;
+    const int which = r / d, rr = r % d;
+    const int head = rr >> 7, in_head = rr & 127;
+    const int src_row = head * 128 + (which == 2 ? in_head : rope_packed_to_orig(in_head));
+    const u16* src = (which == 0 ? wq : which == 1 ? wk : wv) + (size_t)src_row * d;
+    const u32x4* s4 = (const u32x4*)src;
+    u32x4* d4 = (u32x4*)(dst + (size_t)r * d);
+    for (int i = threadIdx.x; i < d / 8; i += blockDim.x) d4[i] = s4[i];
+}
+
+// dst: [2f, d].  Packed row 2j is gate row j, packed row 2j+1 is up row j.
+__global__ void pack_gate_up(u16* __restrict__ dst, const u16* __restrict__ wg, const u16* __restrict__ wu, int d) {
+    const int r = blockIdx.x;
+    const u16* src = ((r & 1) ? wu : wg) + (size_t)(r >> 1) * d;
+    const u32x4* s4 = (const u32x4*)src;
+    u32x4* d4 = (u32x4*)(dst + (size_t)r * d);
+    for (int i = threadIdx.x; i < d / 8; i += blockDim.x) d4[i] = s4[i];
+}
+
+// tab[t][i] = (cos, sin)((pos0 + t) * theta^(-2i/128)); angles in fp64 so that large positions stay exact.
+__global__ void rope_table(float2* __restrict__ tab, int n, int pos0, float theta) {
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= n * 64) return;
+    const int i = gid & 63, t = gid >> 6;
+    const double ang = (double)(pos0 + t) * pow((double)theta, -(double)i / 64.0);
+    tab[gid] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+// One 256-thread block per row; the row (d <= 8192) stays in registers between the two passes.
+//   v    = (hidden_in ? bf16 row of hidden_in : x32 row) + sum over splits of the partial rows
+//   x32 <- v                              (when anything was added or the row came from hidden_in)
+//   xn  <- bf16(v * rsqrt(mean v^2 + eps) * g)   (when g != NULL)
+//   out <- bf16(v)                        (when out != NULL)
+__global__ __launch_bounds__(256) void reduce_norm(float* __restrict__ x32, const u16* __restrict__ hidden_in,
+                                                   const float* __restrict__ partial, int splits, size_t split_stride,
+                                                   const u16* __restrict__ g, u16* __restrict__ xn,
+                                                   u16* __restrict__ out, int d, float eps) {
+    __shared__ float part[4];
+    const size_t row = blockIdx.x;
+    const int nvec = d >> 2;  // float4 per row
+    float4 v[8];
+    float ss = 0.f;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int idx = threadIdx.x + it * 256;
+        if (idx < nvec) {
+            float4 x;
+            if (hidden_in) {
+                const u32x2 h = *(const u32x2*)(hidden_in + row * d + idx * 4);
+                x = make_float4(__uint_as_float(h[0] << 16), __uint_as_float(h[0] & 0xffff0000u),
+                                __uint_as_float(h[1] << 16), __uint_as_float(h[1] & 0xffff0000u));
+            } else {
+                x = *(const float4*)(x32 + row * d + idx * 4);
+            }
+            for (int s = 0; s < splits; ++s) {
+                const float4 p = *(const float4*)(partial + s * split_stride + row * d + idx * 4);
+                x.x += p.x; x.y += p.y; x.z += p.z; x.w += p.w;
+            }
+            if (hidden_in || splits > 0) *(float4*)(x32 + row * d + idx * 4) = x;
+            if (out) {
+                u32x2 o;
+                o[0] = pack_bf16x2(x.x, x.y);
+                o[1] = pack_bf16x2(x.z, x.w);
+                *(u32x2*)(out + row * d + idx * 4) = o;
+            }
+            v[it] = x;
+            ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+        }
+    }
+    if (!g) return;
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float inv = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)d + eps);
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int idx = threadIdx.x + it * 256;
+        if (idx < nvec) {
+            const u32x2 gg = *(const u32x2*)(g + idx * 4);
+            u32x2 o;
+            o[0] = pack_bf16x2(v[it].x * inv * __uint_as_float(gg[0] << 16),
+                               v[it].y * inv * __uint_as_float(gg[0] & 0xffff0000u));
+            o[1] = pack_bf16x2(v[it].z * inv * __uint_as_float(gg[1] << 16),
+                               v[it].w * inv * __uint_as_float(gg[1] & 0xffff0000u));
+            *(u32x2*)(xn + row * d + idx * 4) = o;
+        }
+    }
+}
+
+}  // namespace
+
+void launch_pack_qkv(u16* dst, const u16* wq, const u16* wk, const u16* wv, int d, hipStream_t s) {
+    hipLaunchKernelGGL(pack_qkv, dim3(3 * d), dim3(256), 0, s, dst, wq, wk, wv, d);
+}
+void launch_pack_gate_up(u16* dst, const u16* wg, const u16* wu, int d, int f, hipStream_t s) {
+    hipLaunchKernelGGL(pack_gate_up, dim3(2 * f), dim3(256), 0, s, dst, wg, wu, d);
+}
+void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s) {
+    hipLaunchKernelGGL(rope_table, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, theta);
+}
+void launch_reduce_norm(float* x32, const u16* hidden_in, const float* partial, int splits, size_t split_stride,
+                        const u16* g, u16* xn, u16* out, int n, int d, float eps, hipStream_t s) {
+    hipLaunchKernelGGL(reduce_norm, dim3(n), dim3(256), 0, s, x32, hidden_in, partial, splits, split_stride, g, xn, out,
+                       d, eps);
+}
+
+}  // namespace jup

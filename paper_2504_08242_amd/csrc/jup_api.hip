@@ -35,7 +35,7 @@ const char* check_cfg(const jup_stage_config_t* c) {
     if (!(c->rope_theta > 0.0f)) return "rope_theta must be > 0";
     if (c->dtype == JUP_BF16) {
         if (c->head_dim != 128) return "JUP_BF16 requires head_dim == 128";
-        if (c->d_model % 256) return "JUP_BF16 requires d_model % 256 == 0";
+        if (c->d_model % 256 || c->d_model > 8192) return "JUP_BF16 requires d_model % 256 == 0 and d_model <= 8192";
         if (c->d_ffn % 128) return "JUP_BF16 requires d_ffn % 128 == 0";
     }
     return "";
@@ -82,6 +82,7 @@ WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T) {
     w.gu = off;   off += f32 ? align_up(t * 2 * f * e) : 0;
     w.act = off;  off += align_up(t * f * e);
     w.rope = off; off += align_up(t * (size_t)(c.head_dim / 2) * 8);
+    w.partial = off; off += f32 ? 0 : align_up(8 * t * d * 4);
     w.total = off;
     return w;
 }

@@ -35,6 +35,7 @@ struct WorkspaceLayout {
     size_t gu;    // fp32 only: [T, 2f] gate|up
     size_t act;   // [T, f] silu(gate) * up
     size_t rope;  // [T, head_dim/2] float2 (cos, sin) of the chunk's positions
+    size_t partial;  // bf16 only: [8][T, d] fp32 K-split partial sums of the O / down projections
     size_t total;
 };
 WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T);
