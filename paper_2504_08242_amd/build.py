@@ -11,7 +11,7 @@ SOURCES = ["jup_api.hip", "kernels_f32.hip", "bf16_forward.hip", "bf16_gemm.hip"
            "bf16_misc.hip"]
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
+    "-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     # packed-fp32 instructions are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",

@@ -35,12 +35,23 @@ __device__ inline u16* kv_slot_bf16(const KvView& kv, int layer, int which, int 
     return (u16*)kv.own + (plane * kv.own_cap + (size_t)(pos - kv.n_shared)) * 128;
 }
 
+// GEMM operand layout, used for the weights and for every activation matrix a GEMM reads:
+// [rows/32 row blocks][K/32 stages][2 KB].  A 2 KB block is the LDS image of 32 rows x 32 columns: rows are
+// 64 bytes, four rows form a 256-byte super-row, and the 16-byte chunk ch of row r sits at slot
+// ((4*(r&3) + ch) ^ ((r>>2)&3)) of super-row r>>2.  Returns the bf16-element offset of chunk k_chunk = k/8
+// of row `row`; element k sits at +(k % 8).  Row counts are padded up to a multiple of 32.
+__device__ __host__ inline size_t tiled_offset(int row, int k_chunk, int k_stages) {
+    const int r = row & 31, ch = k_chunk & 3;
+    const size_t block = (size_t)(row >> 5) * k_stages + (k_chunk >> 2);
+    return block * 1024 + (r >> 2) * 128 + ((((r & 3) << 2) + ch) ^ ((r >> 2) & 3)) * 8;
+}
+
 // ---- GEMM (bf16_gemm.hip) -----------------------------------------------------------------------
 enum { EPI_QKV = 0, EPI_PARTIAL = 1, EPI_SWIGLU = 2 };
 
 struct GemmArgs {
-    const u16* A;  // [M, K] activations, row-major
-    const u16* W;  // [N, K] packed weights, row-major
+    const u16* A;  // [M, K] activations in the tiled layout (rows padded to a multiple of 32)
+    const u16* W;  // [N, K] weights in the tiled layout written by the pack kernels ([N/32][K/32][2 KB])
     int M, N, K;
     int m_tiles, n_tiles, splits;  // grid = m_tiles * n_tiles * splits workgroups
     int n_stride;                  // columns between consecutive N tiles (tile width actually owned)
@@ -54,7 +65,7 @@ struct GemmArgs {
     // EPI_PARTIAL
     float* partial;  // [splits][M][N] fp32
     // EPI_SWIGLU
-    u16* act;  // [M, N/2]
+    u16* act;  // [M, N/2] in the tiled layout (it is the down projection's A operand)
 };
 
 enum GemmKind { GEMM_QKV, GEMM_O, GEMM_GATE_UP, GEMM_DOWN };
@@ -68,14 +79,18 @@ hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s);
 hipError_t gemm_configure();  // raises the dynamic-LDS limit of every instantiation (once per process)
 
 // ---- attention (bf16_attention.hip) ---------------------------------------------------------------
+// o is written in the tiled layout (it is the output projection's A operand)
+hipError_t attention_configure();  // raises the dynamic-LDS limit (once per process)
 void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
                             int layer, hipStream_t s);
 
 // ---- packing, rotary table, reduce + norm (bf16_misc.hip) -------------------------------------------
 void launch_pack_qkv(u16* dst, const u16* wq, const u16* wk, const u16* wv, int d, hipStream_t s);
 void launch_pack_gate_up(u16* dst, const u16* wg, const u16* wu, int d, int f, hipStream_t s);
+void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s);
 void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s);
-// x32 <- (hidden_in ? hidden_in : x32) + sum_s partial[s];  xn <- rmsnorm(x32) * g (if g);  out <- bf16(x32) (if out)
+// x32 <- (hidden_in ? hidden_in : x32) + sum_s partial[s];  xn <- rmsnorm(x32) * g (if g), tiled layout;
+// out <- bf16(x32) (if out), row-major
 void launch_reduce_norm(float* x32, const u16* hidden_in, const float* partial, int splits, size_t split_stride,
                         const u16* g, u16* xn, u16* out, int n, int d, float eps, hipStream_t s);
 

@@ -13,17 +13,18 @@ namespace jup {
 
 hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s) {
     const jup_stage_config_t& c = st.cfg;
-    const size_t d = c.d_model, f = c.d_ffn;
+    const size_t d = c.d_model;
     hipError_t e = gemm_configure();
+    if (e == hipSuccess) e = attention_configure();
     if (e != hipSuccess) return e;
     for (int l = 0; l < c.n_layers; ++l) {
         char* base = (char*)st.packed + (size_t)l * st.pl.layer_bytes;
         const jup_layer_weights_t& w = layers[l];
         launch_pack_qkv((u16*)(base + st.pl.wqkv), (const u16*)w.wq, (const u16*)w.wk, (const u16*)w.wv, c.d_model, s);
         launch_pack_gate_up((u16*)(base + st.pl.wgu), (const u16*)w.w_gate, (const u16*)w.w_up, c.d_model, c.d_ffn, s);
-        e = hipMemcpyAsync(base + st.pl.wo, w.wo, d * d * 2, hipMemcpyDeviceToDevice, s);
-        if (e == hipSuccess) e = hipMemcpyAsync(base + st.pl.wdown, w.w_down, d * f * 2, hipMemcpyDeviceToDevice, s);
-        if (e == hipSuccess) e = hipMemcpyAsync(base + st.pl.g_attn, w.g_attn, d * 2, hipMemcpyDeviceToDevice, s);
+        launch_pack_plain((u16*)(base + st.pl.wo), (const u16*)w.wo, c.d_model, c.d_model, s);
+        launch_pack_plain((u16*)(base + st.pl.wdown), (const u16*)w.w_down, c.d_model, c.d_ffn, s);
+        e = hipMemcpyAsync(base + st.pl.g_attn, w.g_attn, d * 2, hipMemcpyDeviceToDevice, s);
         if (e == hipSuccess) e = hipMemcpyAsync(base + st.pl.g_mlp, w.g_mlp, d * 2, hipMemcpyDeviceToDevice, s);
         if (e != hipSuccess) return e;
     }

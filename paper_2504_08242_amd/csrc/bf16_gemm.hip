@@ -15,12 +15,18 @@
 //   * LDS rows are 64 bytes (32 bf16).  Four rows form a 256-byte super-row; chunk c of row r sits at
 //     16-byte slot ((4*(r&3) + c) ^ ((r>>2)&3)) of super-row r>>2, so that 16 consecutive rows read at
 //     one chunk column touch all 64 banks exactly once.
+//   * Both operands are stored pre-tiled as [rows/32 row blocks][K/32 stages][2 KB], each 2 KB block being
+//     the LDS image of its 32 rows x 32 columns, swizzle included (W at stage creation, activations by
+//     the kernels that produce them).  A wave-wide load instruction then copies 1 KB of consecutive
+//     bytes, which the L2 -> LDS path moves about three times faster than 16 pieces of 64 bytes, and a
+//     workgroup streams each row block of W front to back in long sequential bursts.
 //   * Workgroup ids are decoded so that the tiles sharing a slice of W run on the same XCD (same L2).
 //
 // MFMA 32x32x16 bf16 operand layout (lane = 32*hh + c):
 //   A: lane supplies A[m = c][k = 8*hh + e], e < 8;  B: lane supplies B[k = 8*hh + e][n = c];
 //   D: lane holds D[m = 8*(i/4) + 4*hh + (i%4)][n = c] in register i < 16.
 #include <type_traits>
+#include <utility>
 
 #include "bf16_common.h"
 
@@ -33,7 +39,8 @@
 namespace jup {
 namespace {
 
-constexpr int G_BM = 256, G_BK = 32, G_STAGES = 5;
+constexpr int G_BM = 256, G_BK = 32;
+constexpr int kLdsBudget = 160 * 1024;
 
 template <int NB>
 struct Shape {
@@ -41,7 +48,10 @@ struct Shape {
     static constexpr int STAGE_BYTES = ROWS * 64;
     static constexpr int N_LOAD = ROWS / 16;        // wave-wide load instructions per stage (1 KB each)
     static constexpr int LPW = (N_LOAD + 3) / 4;    // per wave (the last ones may repeat a neighbour's)
-    static constexpr int LDS_BYTES = G_STAGES * STAGE_BYTES;
+    // as many ring slots as LDS holds (at most 8: the in-flight count must fit the 6-bit vmcnt)
+    static constexpr int STAGES = kLdsBudget / STAGE_BYTES > 8 ? 8 : kLdsBudget / STAGE_BYTES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static_assert(STAGES >= 4 && (STAGES - 2) * LPW < 64, "ring depth");
 };
 
 __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -56,7 +66,7 @@ __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // s_waitcnt with only the vector-memory counter constrained.
 template <int N>
 __device__ inline void wait_vmcnt() {
-    static_assert(G_STAGES == 5 && N >= 0 && N < 64, "vmcnt is a 6-bit field");
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
 }
 __device__ inline void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0), others free
@@ -113,25 +123,24 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
     const int nt = grp % a.n_tiles, split = grp / a.n_tiles;
     const int m0 = mt * G_BM, n0 = nt * a.n_stride;
     const int KT = a.kt_per_split;
-    const size_t k_base = (size_t)split * KT * G_BK;
 
     // ---- global -> LDS load slots of this wave --------------------------------------------------------
     // Instruction j covers LDS rows [16j, 16j+16) = 1 KB; lane i lands at byte 16*i of it, which is
     // super-row i>>4, slot i&15, i.e. row 16j + 4*(i>>4) + ((i&15)>>2), chunk (i&3) ^ (i>>4).
     const u16* gp[S::LPW];
-    int ldst[S::LPW];
+    int ldst[S::LPW];  // LDS byte offset inside a stage
+    const int kt_total = a.K / G_BK;
 #pragma unroll
     for (int q = 0; q < S::LPW; ++q) {
         const int j = min(wave + 4 * q, S::N_LOAD - 1);
-        const int sl = lane >> 4, p = lane & 15;
-        const int r = 16 * j + 4 * sl + (p >> 2);
-        const int ch = (p & 3) ^ sl;
-        if (r < G_BM) {
-            const int row = min(m0 + r, a.M - 1);  // rows past M repeat the last row; never stored
-            gp[q] = a.A + (size_t)row * a.K + k_base + ch * 8;
+        // Both operands are pre-tiled: an instruction copies half of a 2 KB block, lanes in address order.
+        if (j < G_BM / 16) {
+            const int blk = min(m0 / 32 + (j >> 1), (a.M + 31) / 32 - 1);  // blocks past M repeat the last one
+            gp[q] = a.A + ((size_t)blk * kt_total + (size_t)split * KT) * 1024 + (j & 1) * 512 + lane * 8;
         } else {
-            const int row = min(n0 + (r - G_BM), a.N - 1);
-            gp[q] = a.W + (size_t)row * a.K + k_base + ch * 8;
+            const int jw = j - G_BM / 16;
+            const int blk = min(n0 / 32 + (jw >> 1), a.N / 32 - 1);  // blocks past N repeat the last one
+            gp[q] = a.W + ((size_t)blk * kt_total + (size_t)split * KT) * 1024 + (jw & 1) * 512 + lane * 8;
         }
         ldst[q] = j * 1024;
     }
@@ -139,7 +148,7 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
         for (int q = 0; q < S::LPW; ++q) {
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(gp[q] + (size_t)kt * G_BK),
+                (const __attribute__((address_space(1))) void*)(gp[q] + (size_t)kt * 1024),
                 (__attribute__((address_space(3))) void*)(smem + stage * S::STAGE_BYTES + ldst[q]), 16, 0, 0);
         }
     };
@@ -177,38 +186,46 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
     };
 
     // ---- prologue: fill all but one slot of the ring, fetch the first fragments -----------------------------
+    constexpr int ST = S::STAGES;
 #pragma unroll
-    for (int s = 0; s < G_STAGES - 1; ++s)
+    for (int s = 0; s < ST - 1; ++s)
         if (s < KT) issue(s, s);
-    if (KT >= G_STAGES - 1) wait_vmcnt<(G_STAGES - 2) * S::LPW>();  // stage 0 landed, the others may be in flight
+    if (KT >= ST - 1) wait_vmcnt<(ST - 2) * S::LPW>();  // stage 0 landed, the others may be in flight
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     Frags<NB> f0, f1;
     load_frags(f0, 0, 0);
     wait_lgkmcnt0();
 
+    // Waits until at most g of this wave's load groups (one group = one stage) are still in flight.
+    auto wait_groups = [&](int g) {
+        if (g >= ST - 3) wait_vmcnt<(ST - 3) * S::LPW>();
+        else if (g == 4) wait_vmcnt<(ST > 7 ? 4 : 0) * S::LPW>();
+        else if (g == 3) wait_vmcnt<(ST > 6 ? 3 : 0) * S::LPW>();
+        else if (g == 2) wait_vmcnt<(ST > 5 ? 2 : 0) * S::LPW>();
+        else if (g == 1) wait_vmcnt<1 * S::LPW>();
+        else wait_vmcnt<0>();
+    };
+
     // Stage kt.  On entry f0 holds its sub-step 0.  The barrier at the top publishes stage kt+1 (whose
     // sub-step 0 is prefetched in the second half) and retires stage kt-1, which every wave finished
-    // reading half a stage ago; that slot is refilled with stage kt+4 right away.  The barrier falls
+    // reading half a stage ago; that slot is refilled with stage kt+ST-1 right away.  The barrier falls
     // while the previous stage's last MFMAs are still in the pipe, and each half issues 2 + NB fragment
     // reads under 2 * NB MFMAs.
     //
-    // STEADY stages (kt + 4 < KT) have no conditions at all; the main loop runs five of them per trip with
-    // the ring slots as compile-time constants, so a trip is one straight run of instructions (taken
+    // STEADY stages (kt + ST - 1 < KT) have no conditions at all; the main loop runs ST of them per trip
+    // with the ring slots as compile-time constants, so a trip is one straight run of instructions (taken
     // branches starve the MFMA pipe: the instruction buffer refills while nothing issues).
     auto do_stage = [&](auto steady, int kt, int stage, int pstage, int nstage) {
         constexpr bool STEADY = decltype(steady)::value;
         if (STEADY) {
-            wait_vmcnt<(G_STAGES - 3) * S::LPW>();
+            wait_vmcnt<(ST - 3) * S::LPW>();
             if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
-            if (!(GEMM_EXPERIMENT & 1)) issue(pstage, kt + G_STAGES - 1);
+            if (!(GEMM_EXPERIMENT & 1)) issue(pstage, kt + ST - 1);
         } else if (kt + 1 < KT) {
-            const int left = KT - 1 - (kt + 1);  // stages issued after kt+1 that may stay in flight
-            if (left >= G_STAGES - 3) wait_vmcnt<(G_STAGES - 3) * S::LPW>();
-            else if (left == 1) wait_vmcnt<1 * S::LPW>();
-            else wait_vmcnt<0>();
+            wait_groups(KT - 1 - (kt + 1));  // stages issued after kt+1 may stay in flight
             if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
-            if (!(GEMM_EXPERIMENT & 1) && kt + G_STAGES - 1 < KT) issue(pstage, kt + G_STAGES - 1);
+            if (!(GEMM_EXPERIMENT & 1) && kt + ST - 1 < KT) issue(pstage, kt + ST - 1);
         }
         if (!(GEMM_EXPERIMENT & 4) || kt == 0) load_frags(f1, stage, 1);
         mma(f0, 0, NB);
@@ -223,73 +240,94 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
         wait_lgkmcnt0();
     };
     int kt = 0;
-    for (; kt + 2 * G_STAGES - 1 <= KT; kt += G_STAGES) {  // all five stages of the trip are steady
-        do_stage(std::true_type{}, kt + 0, 0, 4, 1);
-        do_stage(std::true_type{}, kt + 1, 1, 0, 2);
-        do_stage(std::true_type{}, kt + 2, 2, 1, 3);
-        do_stage(std::true_type{}, kt + 3, 3, 2, 4);
-        do_stage(std::true_type{}, kt + 4, 4, 3, 0);
+    for (; kt + 2 * ST - 1 <= KT; kt += ST) {  // every stage of the trip is steady
+        [&]<int... I>(std::integer_sequence<int, I...>) {
+            (do_stage(std::true_type{}, kt + I, I, (I + ST - 1) % ST, (I + 1) % ST), ...);
+        }(std::make_integer_sequence<int, ST>{});
     }
     for (int stage = 0; kt < KT; ++kt) {  // the last few stages, with the tail conditions
-        const int nstage = stage + 1 == G_STAGES ? 0 : stage + 1;
-        const int pstage = stage == 0 ? G_STAGES - 1 : stage - 1;
+        const int nstage = stage + 1 == ST ? 0 : stage + 1;
+        const int pstage = stage == 0 ? ST - 1 : stage - 1;
         do_stage(std::false_type{}, kt, stage, pstage, nstage);
         stage = nstage;
     }
 
     // ---- epilogues ---------------------------------------------------------------------------------------
+    // Lane (c, hh) holds, for block (mb, nb), column n0 + 32 nb + c and rows row0(mb) + 8*(i/4) + 4*hh + (i%4).
     const int n_end = min(n0 + a.n_stride, a.N);  // columns [n0, n_end) belong to this tile
+    const int row_base = m0 + wave * 64 + 4 * hh;
+    auto row_of = [&](int mb, int i) { return row_base + mb * 32 + 8 * (i >> 2) + (i & 3); };
+
+    if (EPI == EPI_PARTIAL) {
+        float* pbase = a.partial + (size_t)split * a.M * a.N + n0 + c;
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
+        for (int nb = 0; nb < NB; ++nb) {
+            if (n0 + nb * 32 + c >= n_end) continue;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int m = m0 + wave * 64 + mb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
-            if (EPI == EPI_PARTIAL) {
-                if (m < a.M) {
-                    float* prow = a.partial + ((size_t)split * a.M + m) * a.N;
+            for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const int n = n0 + nb * 32 + c;
-                        if (n < n_end) prow[n] = acc[mb][nb][i];
-                    }
+                for (int i = 0; i < 16; ++i) {
+                    const int m = row_of(mb, i);
+                    if (m < a.M) pbase[(size_t)m * a.N + nb * 32] = acc[mb][nb][i];
                 }
-            } else if (EPI == EPI_SWIGLU) {
-                // packed column 2j = gate_j, 2j+1 = up_j: the even lane pairs with its right neighbour
+        }
+    } else if (EPI == EPI_SWIGLU) {
+        // packed column 2j = gate_j, 2j+1 = up_j: the even lane pairs with its right neighbour
+        const int half_n = a.N >> 1;
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
+        for (int nb = 0; nb < NB; ++nb) {
+            const int n = n0 + nb * 32 + c;
+            const bool col_ok = !(c & 1) && n < n_end;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
                     const float own = acc[mb][nb][i];
                     const float other = __builtin_bit_cast(
                         float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, own), 0xB1, 0xF, 0xF, true));
-                    const int n = n0 + nb * 32 + c;
-                    if (!(c & 1) && m < a.M && n < n_end) {
-                        const float s = own / (1.0f + __expf(-own)) * other;
-                        a.act[(size_t)m * (a.N >> 1) + (n >> 1)] = f2bf(s);
-                    }
+                    const int m = row_of(mb, i);
+                    if (col_ok && m < a.M)
+                        a.act[tiled_offset(m, n >> 4, half_n >> 5) + ((n >> 1) & 7)] = f2bf(own / (1.0f + __expf(-own)) * other);
                 }
-            } else {  // EPI_QKV
-                // Packed column 32j + 16a + c' of a Q/K head is rotary index 16j + c' + 64a: lanes c and
-                // c ^ 16 of one block hold the partners i and i + 64.  V columns keep their order.
+        }
+    } else {  // EPI_QKV
+        // Packed column 32j + 16a + c' of a Q/K head is rotary index 16j + c' + 64a: lanes c and c ^ 16 of
+        // one block hold the partners i and i + 64.  V columns keep their order.
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
+        for (int nb = 0; nb < NB; ++nb) {
+            const int col = n0 + nb * 32;  // packed column of the block: one (q|k|v, head, j) for all lanes
+            const bool blk_ok = col < n_end;
+            const int which = col / a.d_model;
+            const int in_model = col - which * a.d_model;
+            const int head = in_model >> 7, j = (in_model & 127) >> 5;
+            const int hi = c >> 4, i_lo = 16 * j + (c & 15);
+            // destination of row m is dst + m * stride
+            u16* dst;
+            size_t stride;
+            if (which == 0) {
+                dst = a.q_out + head * 128 + i_lo + 64 * hi;
+                stride = a.d_model;
+            } else {
+                dst = kv_slot_bf16(a.kv, a.layer, which - 1, head, a.n_heads, a.pos0) + (which == 2 ? 32 * j + c : i_lo + 64 * hi);
+                stride = 128;
+            }
+            const float2* rp = a.rope + i_lo;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
                     const float own = acc[mb][nb][i];
                     const float other = __shfl_xor(own, 16, 64);
-                    const int col = n0 + nb * 32;  // packed column of the block (multiple of 32)
-                    if (m >= a.M || col >= n_end) continue;
-                    const int which = col / a.d_model;
-                    const int in_model = col - which * a.d_model;
-                    const int head = in_model >> 7, j = (in_model & 127) >> 5;
-                    if (which == 2) {
-                        kv_slot_bf16(a.kv, a.layer, 1, head, a.n_heads, a.pos0 + m)[32 * j + c] = f2bf(own);
-                    } else {
-                        const int hi = c >> 4, i_lo = 16 * j + (c & 15);
-                        const float2 cs = a.rope[(size_t)m * 64 + i_lo];
-                        u16* dst = which == 0 ? a.q_out + (size_t)m * a.d_model + head * 128
-                                              : kv_slot_bf16(a.kv, a.layer, 0, head, a.n_heads, a.pos0 + m);
+                    const int m = row_of(mb, i);
+                    if (!blk_ok || m >= a.M) continue;
+                    float out = own;
+                    if (which != 2) {
+                        const float2 cs = rp[(size_t)m * 64];
                         // lo' = lo cos - hi sin ; hi' = hi cos + lo sin
-                        dst[i_lo + 64 * hi] = f2bf(hi ? own * cs.x + other * cs.y : own * cs.x - other * cs.y);
+                        out = hi ? own * cs.x + other * cs.y : own * cs.x - other * cs.y;
                     }
+                    dst[(size_t)m * stride] = f2bf(out);
                 }
-            }
         }
     }
 }

@@ -12,26 +12,29 @@ __device__ inline int rope_packed_to_orig(int packed) {
     return 16 * (packed >> 5) + (packed & 15) + 64 * ((packed >> 4) & 1);
 }
 
-// dst: [3d, d].  Rows [0,d): Q heads, [d,2d): K heads, [2d,3d): V heads.
-__global__ void pack_qkv(u16* __restrict__ dst, const u16* __restrict__ wq, const u16* __restrict__ wk,
-                         const u16* __restrict__ wv, int d) {
-    const int r = blockIdx.x;
-    const int which = r / d, rr = r % d;
-    const int head = rr >> 7, in_head = rr & 127;
-    const int src_row = head * 128 + (which == 2 ? in_head : rope_packed_to_orig(in_head));
-    const u16* src = (which == 0 ? wq : which == 1 ? wk : wv) + (size_t)src_row * d;
-    const u32x4* s4 = (const u32x4*)src;
-    u32x4* d4 = (u32x4*)(dst + (size_t)r * d);
-    for (int i = threadIdx.x; i < d / 8; i += blockDim.x) d4[i] = s4[i];
-}
+enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 
-// dst: [2f, d].  Packed row 2j is gate row j, packed row 2j+1 is up row j.
-__global__ void pack_gate_up(u16* __restrict__ dst, const u16* __restrict__ wg, const u16* __restrict__ wu, int d) {
-    const int r = blockIdx.x;
-    const u16* src = ((r & 1) ? wu : wg) + (size_t)(r >> 1) * d;
-    const u32x4* s4 = (const u32x4*)src;
-    u32x4* d4 = (u32x4*)(dst + (size_t)r * d);
-    for (int i = threadIdx.x; i < d / 8; i += blockDim.x) d4[i] = s4[i];
+// One block per packed row n; copies that row's K/8 chunks into the tiled layout.
+//   PACK_QKV:     rows [0,d) Q heads, [d,2d) K heads, [2d,3d) V heads (s0, s1, s2 = wq, wk, wv; rows_per = d)
+//   PACK_GATE_UP: packed row 2j = gate row j, 2j+1 = up row j (s0, s1 = w_gate, w_up)
+//   PACK_PLAIN:   row n of s0
+__global__ void pack_tiled(u16* __restrict__ dst, const u16* __restrict__ s0, const u16* __restrict__ s1,
+                           const u16* __restrict__ s2, int K, int rows_per, int mode) {
+    const int n = blockIdx.x;
+    const u16* src;
+    if (mode == PACK_QKV) {
+        const int which = n / rows_per, rr = n % rows_per;
+        const int head = rr >> 7, in_head = rr & 127;
+        const int src_row = head * 128 + (which == 2 ? in_head : rope_packed_to_orig(in_head));
+        src = (which == 0 ? s0 : which == 1 ? s1 : s2) + (size_t)src_row * K;
+    } else if (mode == PACK_GATE_UP) {
+        src = ((n & 1) ? s1 : s0) + (size_t)(n >> 1) * K;
+    } else {
+        src = s0 + (size_t)n * K;
+    }
+    const int k_stages = K / 32;
+    for (int ck = threadIdx.x; ck < K / 8; ck += blockDim.x)
+        *(u32x4*)(dst + tiled_offset(n, ck, k_stages)) = *(const u32x4*)(src + ck * 8);
 }
 
 // tab[t][i] = (cos, sin)((pos0 + t) * theta^(-2i/128)); angles in fp64 so that large positions stay exact.
@@ -99,7 +102,7 @@ __global__ __launch_bounds__(256) void reduce_norm(float* __restrict__ x32, cons
                                v[it].y * inv * __uint_as_float(gg[0] & 0xffff0000u));
             o[1] = pack_bf16x2(v[it].z * inv * __uint_as_float(gg[1] << 16),
                                v[it].w * inv * __uint_as_float(gg[1] & 0xffff0000u));
-            *(u32x2*)(xn + row * d + idx * 4) = o;
+            *(u32x2*)(xn + tiled_offset((int)row, idx >> 1, d >> 5) + (idx & 1) * 4) = o;
         }
     }
 }
@@ -107,10 +110,15 @@ __global__ __launch_bounds__(256) void reduce_norm(float* __restrict__ x32, cons
 }  // namespace
 
 void launch_pack_qkv(u16* dst, const u16* wq, const u16* wk, const u16* wv, int d, hipStream_t s) {
-    hipLaunchKernelGGL(pack_qkv, dim3(3 * d), dim3(256), 0, s, dst, wq, wk, wv, d);
+    hipLaunchKernelGGL(pack_tiled, dim3(3 * d), dim3(256), 0, s, dst, wq, wk, wv, d, d, (int)PACK_QKV);
 }
 void launch_pack_gate_up(u16* dst, const u16* wg, const u16* wu, int d, int f, hipStream_t s) {
-    hipLaunchKernelGGL(pack_gate_up, dim3(2 * f), dim3(256), 0, s, dst, wg, wu, d);
+    hipLaunchKernelGGL(pack_tiled, dim3(2 * f), dim3(256), 0, s, dst, wg, wu, (const u16*)nullptr, d, 0,
+                       (int)PACK_GATE_UP);
+}
+void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s) {
+    hipLaunchKernelGGL(pack_tiled, dim3(n_rows), dim3(256), 0, s, dst, w, (const u16*)nullptr, (const u16*)nullptr, k,
+                       0, (int)PACK_PLAIN);
 }
 void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s) {
     hipLaunchKernelGGL(rope_table, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, theta);

@@ -71,8 +71,10 @@ PackedLayout packed_layout(const jup_stage_config_t& c) {
 }
 
 WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T) {
-    const size_t e = elem_size(c), d = c.d_model, f = c.d_ffn, t = (size_t)T;
+    const size_t e = elem_size(c), d = c.d_model, f = c.d_ffn;
     const bool f32 = c.dtype == JUP_F32;
+    // the matrix-core path stores GEMM operands in 32-row blocks
+    const size_t t = f32 ? (size_t)T : ((size_t)T + 31) / 32 * 32;
     WorkspaceLayout w{};
     size_t off = 0;
     w.x32 = off;  off += align_up(t * d * 4);
