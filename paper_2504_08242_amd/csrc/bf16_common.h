@@ -66,6 +66,7 @@ struct GemmArgs {
     float* partial;  // [splits][M][N] fp32
     // EPI_SWIGLU
     u16* act;  // [M, N/2] in the tiled layout (it is the down projection's A operand)
+    unsigned long long* timeline;  // timing experiments only (GEMM_TIMELINE builds): 8 counters per workgroup
 };
 
 enum GemmKind { GEMM_QKV, GEMM_O, GEMM_GATE_UP, GEMM_DOWN };

@@ -7,7 +7,10 @@
 // tile width so that the number of tiles matches the number of CUs.  That is the largest tile the
 // problem allows, which is what keeps the L2 -> LDS traffic per flop low.
 //
-//   * 4 waves; wave w owns rows [64w, 64w+64) x all NB 32-column blocks: 2*NB MFMA 32x32x16 per K/16.
+//   * Waves form a WM x WN grid over the tile; a wave owns 8/WM row blocks x NB/WN column blocks of
+//     32 x 32.  What limits a wave is its own instruction stream: every LDS read and every global->LDS
+//     load occupies the issue port for tens of cycles, so the layouts are chosen for few memory
+//     instructions per MFMA (2 x 2 waves of 128 x 96 for the widest tile: 7 fragment reads per 12 MFMAs).
 //     (The 16x16x32 form sustains only ~70 % of the 32x32x16 rate on this chip, measured.)
 //   * K advances in stages of 32 through a 5-stage LDS ring filled by direct global->LDS loads
 //     (16 bytes per lane, no register staging).  A stage holds two K/16 sub-steps; the fragments of
@@ -35,6 +38,11 @@
 #ifndef GEMM_EXPERIMENT
 #define GEMM_EXPERIMENT 0
 #endif
+// 1 = every workgroup's wave 0 accumulates cycle counts of its stalls into GemmArgs::partial (timing
+// experiments only: the buffer is then not a result).
+#ifndef GEMM_TIMELINE
+#define GEMM_TIMELINE 0
+#endif
 
 namespace jup {
 namespace {
@@ -42,12 +50,17 @@ namespace {
 constexpr int G_BM = 256, G_BK = 32;
 constexpr int kLdsBudget = 160 * 1024;
 
-template <int NB>
+template <int NB, int WM, int WN>
 struct Shape {
+    static constexpr int NBW = NB / WN;             // column blocks per wave
+    static constexpr int MBW = 8 / WM;              // row blocks per wave (the tile has 8)
+    static constexpr int WAVES = WM * WN;
     static constexpr int ROWS = G_BM + 32 * NB;     // LDS rows per stage: A rows then W rows
     static constexpr int STAGE_BYTES = ROWS * 64;
-    static constexpr int N_LOAD = ROWS / 16;        // wave-wide load instructions per stage (1 KB each)
-    static constexpr int LPW = (N_LOAD + 3) / 4;    // per wave (the last ones may repeat a neighbour's)
+    static constexpr int SRW = ROWS / 4 / WAVES;    // 256-byte super-rows (4 rows) each wave loads per stage
+    static constexpr int LPW = (SRW + 3) / 4;       // wave-wide load instructions per wave and stage (the last
+                                                    // one may have only some of its four 16-lane groups active)
+    static_assert(NB % WN == 0 && 8 % WM == 0 && (ROWS / 4) % WAVES == 0, "tile does not split evenly over the waves");
     // as many ring slots as LDS holds (at most 8: the in-flight count must fit the 6-bit vmcnt)
     static constexpr int STAGES = kLdsBudget / STAGE_BYTES > 8 ? 8 : kLdsBudget / STAGE_BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
@@ -96,19 +109,21 @@ __device__ __forceinline__ void sched_half() {
     }
 }
 
-// Fragments of one K/16 sub-step of a wave: 2 row blocks, NB column blocks.
-template <int NB>
+// Fragments of one K/16 sub-step of a wave: MB row blocks, NB column blocks.
+template <int MB, int NB>
 struct Frags {
-    bf16x8 a[2];
+    bf16x8 a[MB];
     bf16x8 b[NB];
 };
 
-template <int NB, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
-    using S = Shape<NB>;
+template <int NB, int WM, int WN, int EPI>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
+    using S = Shape<NB, WM, WN>;
+    constexpr int NBW = S::NBW, MBW = S::MBW;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;  // wave owns row blocks [wm MBW, +MBW) x column blocks [wn NBW, +NBW)
 
     // ---- which tile ---------------------------------------------------------------------------------
     int mt, grp;
@@ -125,31 +140,41 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
     const int KT = a.kt_per_split;
 
     // ---- global -> LDS load slots of this wave --------------------------------------------------------
-    // Instruction j covers LDS rows [16j, 16j+16) = 1 KB; lane i lands at byte 16*i of it, which is
-    // super-row i>>4, slot i&15, i.e. row 16j + 4*(i>>4) + ((i&15)>>2), chunk (i&3) ^ (i>>4).
+    // A stage is ROWS/4 super-rows of 256 bytes (4 rows of 64 bytes), A rows first, then W rows; wave w
+    // copies super-rows [w SRW, (w+1) SRW).  One load instruction moves four super-rows: its 16-lane group g
+    // copies one, lane i of the group 16 bytes of it, and lands at byte 16*(16g + i) of the instruction's
+    // 1 KB.  Both operands are pre-tiled, so a super-row is 256 consecutive bytes of a 2 KB block.
     const u16* gp[S::LPW];
-    int ldst[S::LPW];  // LDS byte offset inside a stage
+    bool gact[S::LPW];
     const int kt_total = a.K / G_BK;
 #pragma unroll
     for (int q = 0; q < S::LPW; ++q) {
-        const int j = min(wave + 4 * q, S::N_LOAD - 1);
-        // Both operands are pre-tiled: an instruction copies half of a 2 KB block, lanes in address order.
-        if (j < G_BM / 16) {
-            const int blk = min(m0 / 32 + (j >> 1), (a.M + 31) / 32 - 1);  // blocks past M repeat the last one
-            gp[q] = a.A + ((size_t)blk * kt_total + (size_t)split * KT) * 1024 + (j & 1) * 512 + lane * 8;
+        const int local = 4 * q + (lane >> 4);
+        gact[q] = local < S::SRW;
+        const int sr = wave * S::SRW + min(local, S::SRW - 1);
+        const u16* base;
+        int blk, within;
+        if (sr < G_BM / 4) {
+            blk = min(m0 / 32 + (sr >> 3), (a.M + 31) / 32 - 1);  // blocks past M repeat the last one
+            within = sr & 7;
+            base = a.A;
         } else {
-            const int jw = j - G_BM / 16;
-            const int blk = min(n0 / 32 + (jw >> 1), a.N / 32 - 1);  // blocks past N repeat the last one
-            gp[q] = a.W + ((size_t)blk * kt_total + (size_t)split * KT) * 1024 + (jw & 1) * 512 + lane * 8;
+            const int srw = sr - G_BM / 4;
+            blk = min(n0 / 32 + (srw >> 3), a.N / 32 - 1);  // blocks past N repeat the last one
+            within = srw & 7;
+            base = a.W;
         }
-        ldst[q] = j * 1024;
+        gp[q] = base + ((size_t)blk * kt_total + (size_t)split * KT) * 1024 + within * 128 + (lane & 15) * 8;
     }
+    const int ldst0 = wave * S::SRW * 256;
     auto issue = [&](int stage, int kt) {
 #pragma unroll
         for (int q = 0; q < S::LPW; ++q) {
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(gp[q] + (size_t)kt * 1024),
-                (__attribute__((address_space(3))) void*)(smem + stage * S::STAGE_BYTES + ldst[q]), 16, 0, 0);
+            if (4 * q + 4 <= S::SRW || gact[q])
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(gp[q] + (size_t)kt * 1024),
+                    (__attribute__((address_space(3))) void*)(smem + stage * S::STAGE_BYTES + ldst0 + q * 1024), 16,
+                    0, 0);
         }
     };
 
@@ -161,28 +186,28 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
         lane_off[ks] = (c >> 2) * 256 + ((((c & 3) << 2) + 2 * ks + hh) ^ ((c >> 2) & 3)) * 16;
-    const int a_base = wave * (64 * 64), b_base = G_BM * 64;
-    auto load_frags = [&](Frags<NB>& f, int stage, int ks) {
+    const int a_base = wm * MBW * 2048, b_base = G_BM * 64 + wn * NBW * 2048;
+    auto load_frags = [&](Frags<MBW, NBW>& f, int stage, int ks) {
         const unsigned char* sb = smem + stage * S::STAGE_BYTES + lane_off[ks];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) f.a[mb] = *(const bf16x8*)(sb + a_base + mb * 2048);
+        for (int mb = 0; mb < MBW; ++mb) f.a[mb] = *(const bf16x8*)(sb + a_base + mb * 2048);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) f.b[nb] = *(const bf16x8*)(sb + b_base + nb * 2048);
+        for (int nb = 0; nb < NBW; ++nb) f.b[nb] = *(const bf16x8*)(sb + b_base + nb * 2048);
     };
 
-    f32x16 acc[2][NB];
+    f32x16 acc[MBW][NBW];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
 
-    auto mma = [&](const Frags<NB>& f, int nb_lo, int nb_hi) {
+    auto mma = [&](const Frags<MBW, NBW>& f, int nb_lo, int nb_hi) {
 #pragma unroll
         for (int nb = nb_lo; nb < nb_hi; ++nb)
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) acc[mb][nb] = mfma32(f.a[mb], f.b[nb], acc[mb][nb]);
+            for (int mb = 0; mb < MBW; ++mb) acc[mb][nb] = mfma32(f.a[mb], f.b[nb], acc[mb][nb]);
     };
 
     // ---- prologue: fill all but one slot of the ring, fetch the first fragments -----------------------------
@@ -193,7 +218,7 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
     if (KT >= ST - 1) wait_vmcnt<(ST - 2) * S::LPW>();  // stage 0 landed, the others may be in flight
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    Frags<NB> f0, f1;
+    Frags<MBW, NBW> f0, f1;
     load_frags(f0, 0, 0);
     wait_lgkmcnt0();
 
@@ -216,11 +241,27 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
     // STEADY stages (kt + ST - 1 < KT) have no conditions at all; the main loop runs ST of them per trip
     // with the ring slots as compile-time constants, so a trip is one straight run of instructions (taken
     // branches starve the MFMA pipe: the instruction buffer refills while nothing issues).
+#if GEMM_TIMELINE
+    unsigned long long tl_vm = 0, tl_bar = 0, tl_n = 0, tl_first = 0, tl_last = 0;
+    const unsigned long long tl_start = __builtin_amdgcn_s_memtime();
+    const unsigned long long tl_rstart = __builtin_amdgcn_s_memrealtime();
+#endif
     auto do_stage = [&](auto steady, int kt, int stage, int pstage, int nstage) {
         constexpr bool STEADY = decltype(steady)::value;
         if (STEADY) {
+#if GEMM_TIMELINE
+            const unsigned long long t0 = __builtin_amdgcn_s_memtime();
+            wait_vmcnt<(ST - 3) * S::LPW>();
+            const unsigned long long t1 = __builtin_amdgcn_s_memtime();
+            __builtin_amdgcn_s_barrier();
+            const unsigned long long t2 = __builtin_amdgcn_s_memtime();
+            tl_vm += t1 - t0; tl_bar += t2 - t1; tl_n += 1;
+            if (tl_first == 0) tl_first = t0;
+            tl_last = t2;
+#else
             wait_vmcnt<(ST - 3) * S::LPW>();
             if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
+#endif
             if (!(GEMM_EXPERIMENT & 1)) issue(pstage, kt + ST - 1);
         } else if (kt + 1 < KT) {
             wait_groups(KT - 1 - (kt + 1));  // stages issued after kt+1 may stay in flight
@@ -228,12 +269,12 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
             if (!(GEMM_EXPERIMENT & 1) && kt + ST - 1 < KT) issue(pstage, kt + ST - 1);
         }
         if (!(GEMM_EXPERIMENT & 4) || kt == 0) load_frags(f1, stage, 1);
-        mma(f0, 0, NB);
+        mma(f0, 0, NBW);
         if (!(GEMM_EXPERIMENT & 4) && (STEADY || kt + 1 < KT)) load_frags(f0, nstage, 0);
-        mma(f1, 0, NB);
+        mma(f1, 0, NBW);
         if (STEADY && GEMM_EXPERIMENT == 0) {
-            sched_half<2 * NB, 2 + NB, (S::LPW + 1) / 2>();
-            sched_half<2 * NB, 2 + NB, S::LPW / 2>();
+            sched_half<MBW * NBW, MBW + NBW, (S::LPW + 1) / 2>();
+            sched_half<MBW * NBW, MBW + NBW, S::LPW / 2>();
         }
         // f0 (next stage) has had the last MFMAs to arrive; waiting here keeps the next stage's reads out of
         // the wait and leaves no LDS read of this wave outstanding at the barrier.
@@ -252,19 +293,24 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
         stage = nstage;
     }
 
+#if GEMM_TIMELINE
+    const unsigned long long tl_loop_end = __builtin_amdgcn_s_memtime();
+#endif
     // ---- epilogues ---------------------------------------------------------------------------------------
     // Lane (c, hh) holds, for block (mb, nb), column n0 + 32 nb + c and rows row0(mb) + 8*(i/4) + 4*hh + (i%4).
     const int n_end = min(n0 + a.n_stride, a.N);  // columns [n0, n_end) belong to this tile
-    const int row_base = m0 + wave * 64 + 4 * hh;
+    constexpr int WROWS = 32 * MBW;  // rows of this wave
+    const int row_base = m0 + wm * WROWS + 4 * hh;
+    const int nw0 = n0 + wn * NBW * 32;  // first column of this wave
     auto row_of = [&](int mb, int i) { return row_base + mb * 32 + 8 * (i >> 2) + (i & 3); };
 
     if (EPI == EPI_PARTIAL) {
-        float* pbase = a.partial + (size_t)split * a.M * a.N + n0 + c;
+        float* pbase = a.partial + (size_t)split * a.M * a.N + nw0 + c;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            if (n0 + nb * 32 + c >= n_end) continue;
+        for (int nb = 0; nb < NBW; ++nb) {
+            if (nw0 + nb * 32 + c >= n_end) continue;
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+            for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int m = row_of(mb, i);
@@ -272,81 +318,138 @@ __global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
                 }
         }
     } else if (EPI == EPI_SWIGLU) {
-        // packed column 2j = gate_j, 2j+1 = up_j: the even lane pairs with its right neighbour
-        const int half_n = a.N >> 1;
+        // Packed column 2j = gate_j, 2j+1 = up_j: the even lane pairs with its right neighbour.  Results go
+        // through a wave-private LDS strip [32*MBW rows][16*NBW outputs] so that the global stores are whole
+        // 16-byte chunks of the tiled operand layout instead of single elements.
+        constexpr int OUTW = 16 * NBW;         // outputs per row of this wave
+        constexpr int ROWB = OUTW * 2;         // bytes per strip row
+        __builtin_amdgcn_s_barrier();          // every wave is done with the ring (no reads or DMA in flight)
+        unsigned char* strip = smem + wave * (WROWS * ROWB);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int n = n0 + nb * 32 + c;
-            const bool col_ok = !(c & 1) && n < n_end;
+        for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+            for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const float own = acc[mb][nb][i];
                     const float other = __builtin_bit_cast(
                         float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, own), 0xB1, 0xF, 0xF, true));
-                    const int m = row_of(mb, i);
-                    if (col_ok && m < a.M)
-                        a.act[tiled_offset(m, n >> 4, half_n >> 5) + ((n >> 1) & 7)] = f2bf(own / (1.0f + __expf(-own)) * other);
+                    const int rl = mb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+                    if (!(c & 1))
+                        *(u16*)(strip + rl * ROWB + (nb * 16 + (c >> 1)) * 2) =
+                            f2bf(own * __builtin_amdgcn_rcpf(1.0f + __expf(-own)) * other);
                 }
+        wait_lgkmcnt0();
+        __builtin_amdgcn_wave_barrier();
+        const int half_n = a.N >> 1;
+        constexpr int CH = OUTW / 8;  // 16-byte chunks per row
+#pragma unroll
+        for (int p = 0; p < (WROWS * CH + 63) / 64; ++p) {
+            const int idx = p * 64 + lane;
+            const int rl = idx / CH, ch = idx - rl * CH;
+            const int m = m0 + wm * WROWS + rl;
+            const int col = (nw0 >> 1) + ch * 8;  // first output column of the chunk
+            if (idx < WROWS * CH && m < a.M && 2 * col < n_end)
+                *(u32x4*)(a.act + tiled_offset(m, col >> 3, half_n >> 5)) = *(const u32x4*)(strip + rl * ROWB + ch * 16);
         }
     } else {  // EPI_QKV
-        // Packed column 32j + 16a + c' of a Q/K head is rotary index 16j + c' + 64a: lanes c and c ^ 16 of
-        // one block hold the partners i and i + 64.  V columns keep their order.
+        // Packed column 32j + 16a + c' of a Q/K head is rotary index 16j + c' + 64a (a = 0/1: partners i and
+        // i + 64); V columns keep their order.  The accumulators go through a wave-private fp32 strip
+        // [32*MBW rows][32*NBW columns] in LDS; then a lane rotates 8 consecutive indices of one row and stores
+        // 16 bytes.
+        constexpr int SW = 32 * NBW + 8;  // strip row stride in floats (rows 4 apart fall 32 banks apart)
+        __builtin_amdgcn_s_barrier();     // every wave is done with the ring (no reads or DMA in flight)
+        float* strip = (float*)smem + wave * (WROWS * SW);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int col = n0 + nb * 32;  // packed column of the block: one (q|k|v, head, j) for all lanes
-            const bool blk_ok = col < n_end;
+        for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+            for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    strip[(mb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3)) * SW + nb * 32 + c] = acc[mb][nb][i];
+        wait_lgkmcnt0();
+        __builtin_amdgcn_wave_barrier();
+        // lane = 4 * row_in_pass + sub: 16 rows per pass, sub picks 8 of a block's 32 packed columns
+        const int sub = lane & 3, rl0 = lane >> 2;
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) {
+            const int col = nw0 + nb * 32;  // packed column of the block: one (q|k|v, head, j) for all lanes
+            if (col >= n_end) continue;
             const int which = col / a.d_model;
             const int in_model = col - which * a.d_model;
             const int head = in_model >> 7, j = (in_model & 127) >> 5;
-            const int hi = c >> 4, i_lo = 16 * j + (c & 15);
-            // destination of row m is dst + m * stride
+            const int hi = sub >> 1, i_lo = 16 * j + 8 * (sub & 1);
             u16* dst;
             size_t stride;
             if (which == 0) {
                 dst = a.q_out + head * 128 + i_lo + 64 * hi;
                 stride = a.d_model;
             } else {
-                dst = kv_slot_bf16(a.kv, a.layer, which - 1, head, a.n_heads, a.pos0) + (which == 2 ? 32 * j + c : i_lo + 64 * hi);
+                dst = kv_slot_bf16(a.kv, a.layer, which - 1, head, a.n_heads, a.pos0) +
+                      (which == 2 ? 32 * j + 8 * sub : i_lo + 64 * hi);
                 stride = 128;
             }
-            const float2* rp = a.rope + i_lo;
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+            for (int p = 0; p < WROWS / 16; ++p) {
+                const int rl = p * 16 + rl0;
+                const int m = m0 + wm * WROWS + rl;
+                if (m >= a.M) continue;
+                const float* sp = strip + rl * SW + nb * 32;
+                float v[8];
+                if (which == 2) {
+                    const float4 x0 = *(const float4*)(sp + 8 * sub), x1 = *(const float4*)(sp + 8 * sub + 4);
+                    v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+                } else {
+                    const int o8 = 8 * (sub & 1);
+                    const float4 l0 = *(const float4*)(sp + o8), l1 = *(const float4*)(sp + o8 + 4);
+                    const float4 h0 = *(const float4*)(sp + 16 + o8), h1 = *(const float4*)(sp + 16 + o8 + 4);
+                    const float lo[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
+                    const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+                    const float4* rp = (const float4*)(a.rope + (size_t)m * 64 + i_lo);  // 8 (cos, sin) pairs
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float own = acc[mb][nb][i];
-                    const float other = __shfl_xor(own, 16, 64);
-                    const int m = row_of(mb, i);
-                    if (!blk_ok || m >= a.M) continue;
-                    float out = own;
-                    if (which != 2) {
-                        const float2 cs = rp[(size_t)m * 64];
+                    for (int e2 = 0; e2 < 4; ++e2) {
+                        const float4 cs = rp[e2];  // (cos, sin) of indices 2*e2 and 2*e2 + 1
                         // lo' = lo cos - hi sin ; hi' = hi cos + lo sin
-                        out = hi ? own * cs.x + other * cs.y : own * cs.x - other * cs.y;
+                        v[2 * e2] = hi ? hv[2 * e2] * cs.x + lo[2 * e2] * cs.y : lo[2 * e2] * cs.x - hv[2 * e2] * cs.y;
+                        v[2 * e2 + 1] = hi ? hv[2 * e2 + 1] * cs.z + lo[2 * e2 + 1] * cs.w
+                                           : lo[2 * e2 + 1] * cs.z - hv[2 * e2 + 1] * cs.w;
                     }
-                    dst[(size_t)m * stride] = f2bf(out);
                 }
+                u32x4 out;
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) out[e2] = pack_bf16x2(v[2 * e2], v[2 * e2 + 1]);
+                *(u32x4*)(dst + (size_t)m * stride) = out;
+            }
         }
     }
+#if GEMM_TIMELINE
+    {
+        const unsigned long long tl_end = __builtin_amdgcn_s_memtime();
+        if (tid == 0 && a.timeline) {
+            unsigned long long* t = a.timeline + (size_t)blockIdx.x * 8;
+            t[0] = tl_vm; t[1] = tl_bar; t[2] = tl_n; t[3] = tl_last - tl_first; t[4] = tl_first - tl_start;
+            t[5] = tl_loop_end - tl_last; t[6] = __builtin_amdgcn_s_memrealtime() - tl_rstart; t[7] = tl_end - tl_start;
+        }
+    }
+#endif
 }
 
 // ---- host side: tiling policy and launch -----------------------------------------------------------------
 
 constexpr int kCUs = 256;
 
-template <int NB, int EPI>
+template <int NB, int WM, int WN, int EPI>
 hipError_t launch(const GemmArgs& a, hipStream_t s) {
     const int grid = a.m_tiles * a.n_tiles * a.splits;
-    hipLaunchKernelGGL((gemm_bf16<NB, EPI>), dim3(grid), dim3(256), Shape<NB>::LDS_BYTES, s, a);
+    constexpr size_t lds_bytes = Shape<NB, WM, WN>::LDS_BYTES;
+    hipLaunchKernelGGL((gemm_bf16<NB, WM, WN, EPI>), dim3(grid), dim3(64 * WM * WN), lds_bytes, s, a);
     return hipGetLastError();
 }
 
-template <int NB, int EPI>
+template <int NB, int WM, int WN, int EPI>
 hipError_t configure_one() {
-    return hipFuncSetAttribute((const void*)gemm_bf16<NB, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               Shape<NB>::LDS_BYTES);
+    return hipFuncSetAttribute((const void*)gemm_bf16<NB, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               Shape<NB, WM, WN>::LDS_BYTES);
 }
 
 void finish_plan(GemmArgs& a) {
@@ -363,14 +466,14 @@ int div_up(int x, int y) { return (x + y - 1) / y; }
 hipError_t gemm_configure() {
     hipError_t e = hipSuccess;
     auto acc = [&](hipError_t r) { if (e == hipSuccess) e = r; };
-    acc(configure_one<1, EPI_QKV>());
-    acc(configure_one<2, EPI_QKV>());
-    acc(configure_one<3, EPI_QKV>());
-    acc(configure_one<2, EPI_SWIGLU>());
-    acc(configure_one<3, EPI_SWIGLU>());
-    acc(configure_one<4, EPI_SWIGLU>());
-    acc(configure_one<6, EPI_SWIGLU>());
-    acc(configure_one<4, EPI_PARTIAL>());
+    acc(configure_one<1, 4, 1, EPI_QKV>());
+    acc(configure_one<2, 4, 1, EPI_QKV>());
+    acc(configure_one<3, 4, 1, EPI_QKV>());
+    acc(configure_one<2, 4, 1, EPI_SWIGLU>());
+    acc(configure_one<3, 4, 1, EPI_SWIGLU>());
+    acc(configure_one<4, 2, 2, EPI_SWIGLU>());
+    acc(configure_one<6, 2, 2, EPI_SWIGLU>());
+    acc(configure_one<4, 2, 2, EPI_PARTIAL>());
     return e;
 }
 
@@ -408,9 +511,9 @@ hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s) {
     a.n_stride = 32 * nb;
     a.n_tiles = div_up(a.N, a.n_stride);
     finish_plan(a);
-    if (nb == 3) return launch<3, EPI_QKV>(a, s);
-    if (nb == 2) return launch<2, EPI_QKV>(a, s);
-    return launch<1, EPI_QKV>(a, s);
+    if (nb == 3) return launch<3, 4, 1, EPI_QKV>(a, s);
+    if (nb == 2) return launch<2, 4, 1, EPI_QKV>(a, s);
+    return launch<1, 4, 1, EPI_QKV>(a, s);
 }
 
 hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
@@ -420,10 +523,10 @@ hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
     a.n_stride = 32 * nb;
     a.n_tiles = div_up(a.N, a.n_stride);
     finish_plan(a);
-    if (nb == 6) return launch<6, EPI_SWIGLU>(a, s);
-    if (nb == 4) return launch<4, EPI_SWIGLU>(a, s);
-    if (nb == 3) return launch<3, EPI_SWIGLU>(a, s);
-    return launch<2, EPI_SWIGLU>(a, s);
+    if (nb == 6) return launch<6, 2, 2, EPI_SWIGLU>(a, s);
+    if (nb == 4) return launch<4, 2, 2, EPI_SWIGLU>(a, s);
+    if (nb == 3) return launch<3, 4, 1, EPI_SWIGLU>(a, s);
+    return launch<2, 4, 1, EPI_SWIGLU>(a, s);
 }
 
 hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
@@ -431,7 +534,7 @@ hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
     a.n_stride = 128;
     a.n_tiles = div_up(a.N, 128);
     finish_plan(a);
-    return launch<4, EPI_PARTIAL>(a, s);
+    return launch<4, 2, 2, EPI_PARTIAL>(a, s);
 }
 
 }  // namespace jup
