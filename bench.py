@@ -39,7 +39,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--chunk", type=int, default=512, help="chunk size (128, 256, 512 or 2048)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024,
+                    help="the oracle is timed on the first this-many tokens of the prompt, fed in the same chunks")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (a kernel of known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build covers one GPU (one stage of the pipeline); run with --gpus 1")
@@ -73,6 +77,14 @@ def main():
         for c in range(n_chunks):
             lo = c * chunk
             stage.prefill_chunk(hidden[lo:lo + chunk], lo, kv, hidden_out=out[lo:lo + chunk])
+
+    if args.calibrate_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -109,18 +121,20 @@ def main():
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
-        ns = args.cpu_sample_tokens
+        ns = min(max(args.cpu_sample_tokens, 1), PROMPT_TOKENS)
         ora = oracle.OracleStage(cfg, layers_np, ns)
+        ref = np.empty((ns, cfg["d_model"]), np.float32)
         t0 = time.perf_counter()
-        ref = ora.prefill_chunk(hidden_np[:ns], 0)
+        for lo in range(0, ns, chunk):
+            hi = min(lo + chunk, ns)
+            ref[lo:hi] = ora.prefill_chunk(hidden_np[lo:hi], lo)
         dt = time.perf_counter() - t0
-        got = out[:ns].float().cpu().numpy() if chunk >= ns else None
+        got = out[:ns].float().cpu().numpy().astype(np.float64)
         cpu_baseline = {"value": round(ns / dt, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
                         "kind": "oracle", "seconds": round(dt, 2),
-                        "sample": f"first {ns} tokens of the prompt (pos_offset 0) through all {cfg['n_layers']} layers"}
-        if got is not None:
-            cpu_baseline["gpu_vs_oracle_rel_l2"] = float(
-                np.linalg.norm(got.astype(np.float64) - ref) / np.linalg.norm(ref.astype(np.float64)))
+                        "sample": f"first {ns} of the {PROMPT_TOKENS} prompt tokens in chunks of {chunk}, all "
+                                  f"{cfg['n_layers']} layers",
+                        "gpu_vs_oracle_rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref.astype(np.float64)))}
 
     print(json.dumps({
         "metric": "prefill_tokens_per_s_per_stage",
@@ -135,9 +149,9 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"llama2-7b-shaped 8-layer stage, {PROMPT_TOKENS}-token prompt as {n_chunks}x{chunk} chunks",
-                   "n_layers": cfg["n_layers"], "d_model": cfg["d_model"], "n_heads": cfg["n_heads"],
-                   "d_ffn": cfg["d_ffn"], "prompt_tokens": PROMPT_TOKENS, "chunk_tokens": chunk},
+        "config": {"workload": f"configs[2]: 8-layer stage of Llama-2-7B shape (d 4096, 32 heads x 128, FFN 11008), "
+                               f"{PROMPT_TOKENS}-token prompt as {n_chunks} chunks of {chunk}",
+                   "prompt_tokens": PROMPT_TOKENS, "chunk_tokens": chunk},
         "tflops": round(step_tflops, 1),
         "frac_of_bf16_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline,

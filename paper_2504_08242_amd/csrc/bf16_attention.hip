@@ -58,8 +58,10 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31, hh = lane >> 5;
-    const int head = blockIdx.y;
-    const int q0 = blockIdx.x * (QB * 32);
+    // Workgroup b runs on XCD b % 8: heads vary fastest so that every query block of a head reads that
+    // head's keys and values through the same L2; the longest query blocks (most visible keys) start first.
+    const int head = blockIdx.x % n_heads;
+    const int q0 = ((int)(gridDim.x / n_heads) - 1 - (int)(blockIdx.x / n_heads)) * (QB * 32);
     const int q_last = min(q0 + QB * 32, n) - 1;  // last real query of this block
     const int n_keys = pos0 + q_last + 1;         // keys 0 .. n_keys-1 are visible to the block
     const int n_tiles = (n_keys + kKT - 1) / kKT;
@@ -288,10 +290,10 @@ void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_head
                             int layer, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
     if (n <= 32)
-        hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3((n + 31) / 32, n_heads), dim3(256), 4 * kWaveLds, s, q, o, n,
+        hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3((n + 31) / 32 * n_heads), dim3(256), 4 * kWaveLds, s, q, o, n,
                            d_model, n_heads, pos0, kv, layer, scale_log2e);
     else
-        hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64, n_heads), dim3(256), 4 * kWaveLds, s, q, o, n,
+        hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(256), 4 * kWaveLds, s, q, o, n,
                            d_model, n_heads, pos0, kv, layer, scale_log2e);
 }
 

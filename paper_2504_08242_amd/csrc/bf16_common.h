@@ -56,7 +56,6 @@ struct GemmArgs {
     int m_tiles, n_tiles, splits;  // grid = m_tiles * n_tiles * splits workgroups
     int n_stride;                  // columns between consecutive N tiles (tile width actually owned)
     int kt_per_split;              // K tiles of 32 per split
-    int xcd_swizzle;               // 1: workgroup ids are spread so that one XCD owns whole (n, split) groups
     // EPI_QKV
     u16* q_out;          // [M, d_model] rotated queries
     const float2* rope;  // [M, 64] (cos, sin)

@@ -8,9 +8,9 @@
 // problem allows, which is what keeps the L2 -> LDS traffic per flop low.
 //
 //   * Waves form a WM x WN grid over the tile; a wave owns 8/WM row blocks x NB/WN column blocks of
-//     32 x 32.  What limits a wave is its own instruction stream: every LDS read and every global->LDS
-//     load occupies the issue port for tens of cycles, so the layouts are chosen for few memory
-//     instructions per MFMA (2 x 2 waves of 128 x 96 for the widest tile: 7 fragment reads per 12 MFMAs).
+//     32 x 32.  Measured at M = 512: eight waves (4 x 2, two per SIMD, 64 x 96 each) beat four waves of
+//     128 x 96 (2 x 2) by 20 % although the latter read a third less from LDS: with one wave per SIMD
+//     every wait of that wave idles the matrix pipe, with two the other wave's MFMAs cover it.
 //     (The 16x16x32 form sustains only ~70 % of the 32x32x16 rate on this chip, measured.)
 //   * K advances in stages of 32 through a 5-stage LDS ring filled by direct global->LDS loads
 //     (16 bytes per lane, no register staging).  A stage holds two K/16 sub-steps; the fragments of
@@ -126,14 +126,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
     const int wm = wave % WM, wn = wave / WM;  // wave owns row blocks [wm MBW, +MBW) x column blocks [wn NBW, +NBW)
 
     // ---- which tile ---------------------------------------------------------------------------------
+    // Workgroup b runs on XCD b % 8.  Tiles are numbered so that each XCD owns one contiguous range of
+    // them, M tiles fastest: the workgroups that read the same weight rows (all M tiles of an N tile) and
+    // neighbouring N tiles (same activation rows) then share one L2.
     int mt, grp;
-    if (a.xcd_swizzle) {
+    {
+        const int q = gridDim.x >> 3, r = gridDim.x & 7;
         const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-        mt = local % a.m_tiles;
-        grp = xcd + 8 * (local / a.m_tiles);
-    } else {
-        mt = blockIdx.x % a.m_tiles;
-        grp = blockIdx.x / a.m_tiles;
+        const int tile = xcd * q + min(xcd, r) + local;
+        mt = tile % a.m_tiles;
+        grp = tile / a.m_tiles;
     }
     const int nt = grp % a.n_tiles, split = grp / a.n_tiles;
     const int m0 = mt * G_BM, n0 = nt * a.n_stride;
@@ -454,8 +456,6 @@ hipError_t configure_one() {
 
 void finish_plan(GemmArgs& a) {
     a.m_tiles = (a.M + G_BM - 1) / G_BM;
-    const int total = a.m_tiles * a.n_tiles * a.splits;
-    a.xcd_swizzle = (total % (8 * a.m_tiles)) == 0;
     a.kt_per_split = a.K / G_BK / a.splits;
 }
 
@@ -471,9 +471,9 @@ hipError_t gemm_configure() {
     acc(configure_one<3, 4, 1, EPI_QKV>());
     acc(configure_one<2, 4, 1, EPI_SWIGLU>());
     acc(configure_one<3, 4, 1, EPI_SWIGLU>());
-    acc(configure_one<4, 2, 2, EPI_SWIGLU>());
-    acc(configure_one<6, 2, 2, EPI_SWIGLU>());
-    acc(configure_one<4, 2, 2, EPI_PARTIAL>());
+    acc(configure_one<4, 4, 2, EPI_SWIGLU>());
+    acc(configure_one<6, 4, 2, EPI_SWIGLU>());
+    acc(configure_one<4, 4, 2, EPI_PARTIAL>());
     return e;
 }
 
@@ -523,8 +523,8 @@ hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
     a.n_stride = 32 * nb;
     a.n_tiles = div_up(a.N, a.n_stride);
     finish_plan(a);
-    if (nb == 6) return launch<6, 2, 2, EPI_SWIGLU>(a, s);
-    if (nb == 4) return launch<4, 2, 2, EPI_SWIGLU>(a, s);
+    if (nb == 6) return launch<6, 4, 2, EPI_SWIGLU>(a, s);
+    if (nb == 4) return launch<4, 4, 2, EPI_SWIGLU>(a, s);
     if (nb == 3) return launch<3, 4, 1, EPI_SWIGLU>(a, s);
     return launch<2, 4, 1, EPI_SWIGLU>(a, s);
 }
@@ -534,7 +534,7 @@ hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
     a.n_stride = 128;
     a.n_tiles = div_up(a.N, 128);
     finish_plan(a);
-    return launch<4, 2, 2, EPI_PARTIAL>(a, s);
+    return launch<4, 4, 2, EPI_PARTIAL>(a, s);
 }
 
 }  // namespace jup
