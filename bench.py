@@ -21,6 +21,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+# HBM bytes per launch of the dominant kernel at chunk 512, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+# script scaled by a 256 MiB copy (--calibrate-copy); the summary of those runs lies under profiles/.
+GATE_UP_TRAFFIC_BYTES = {512: (106863.5 * 2.0 + 11046.2 * 1.0) * 1024}
 PROMPT_TOKENS = 2048
 
 
@@ -116,7 +119,10 @@ def main():
     achieved = dom_flops / (dom["avg_us"] * 1e-6) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_bf16_nt<gate_up+swiglu>", "achieved": round(achieved, 1),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "avg_launch_us": round(dom["avg_us"], 2), "flop_per_launch": dom_flops, "traffic": None}
+                "avg_launch_us": round(dom["avg_us"], 2), "flop_per_launch": dom_flops, "traffic": GATE_UP_TRAFFIC_BYTES.get(chunk),
+                "traffic_unit": "bytes per launch (offline rocprofv3 counters)",
+                "algorithmic_bytes": 2.0 * (2 * cfg["d_ffn"] * cfg["d_model"] + chunk * cfg["d_model"]
+                                            + chunk * cfg["d_ffn"])}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
