@@ -57,10 +57,10 @@ struct Shape {
     static constexpr int WAVES = WM * WN;
     static constexpr int ROWS = G_BM + 32 * NB;     // LDS rows per stage: A rows then W rows
     static constexpr int STAGE_BYTES = ROWS * 64;
-    static constexpr int SRW = ROWS / 4 / WAVES;    // 256-byte super-rows (4 rows) each wave loads per stage
-    static constexpr int LPW = (SRW + 3) / 4;       // wave-wide load instructions per wave and stage (the last
-                                                    // one may have only some of its four 16-lane groups active)
-    static_assert(NB % WN == 0 && 8 % WM == 0 && (ROWS / 4) % WAVES == 0, "tile does not split evenly over the waves");
+    static constexpr int NL = ROWS / 16;            // 1 KB load units (16 rows) per stage, dealt round-robin to the waves
+    static constexpr int LPW = (NL + WAVES - 1) / WAVES;  // load instructions per stage of the waves that have the most
+    static constexpr int REM = NL % WAVES;          // waves below REM issue LPW loads, the others LPW - 1 (0: all LPW)
+    static_assert(NB % WN == 0 && 8 % WM == 0, "tile does not split evenly over the waves");
     // as many ring slots as LDS holds (at most 8: the in-flight count must fit the 6-bit vmcnt)
     static constexpr int STAGES = kLdsBudget / STAGE_BYTES > 8 ? 8 : kLdsBudget / STAGE_BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
@@ -74,6 +74,16 @@ __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 #else
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 #endif
+}
+
+// Tells the compiler that p is the same in every lane (it is: built from kernel arguments, the workgroup id
+// and the wave number).  Kept opaque so that "uniform base + 32-bit lane offset" survives to instruction
+// selection and the pointer arithmetic of a load stays on the scalar unit.
+__device__ inline const char* uniform_ptr(const char* p) {
+    const unsigned long long v = (unsigned long long)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return (const char*)(((unsigned long long)hi << 32) | lo);
 }
 
 // s_waitcnt with only the vector-memory counter constrained.
@@ -142,42 +152,38 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
     const int KT = a.kt_per_split;
 
     // ---- global -> LDS load slots of this wave --------------------------------------------------------
-    // A stage is ROWS/4 super-rows of 256 bytes (4 rows of 64 bytes), A rows first, then W rows; wave w
-    // copies super-rows [w SRW, (w+1) SRW).  One load instruction moves four super-rows: its 16-lane group g
-    // copies one, lane i of the group 16 bytes of it, and lands at byte 16*(16g + i) of the instruction's
-    // 1 KB.  Both operands are pre-tiled, so a super-row is 256 consecutive bytes of a 2 KB block.
-    const u16* gp[S::LPW];
-    bool gact[S::LPW];
+    // A stage is ROWS/4 super-rows of 256 bytes (4 rows of 64 bytes), A rows first, then W rows.  One load
+    // instruction moves four super-rows: lane i's 16 bytes land at byte 16 i of the instruction's 1 KB.
+    // Unit j of a stage = rows [16j, 16j+16) of the LDS image = 1 KB that is contiguous in the tiled operand
+    // too (half a 2 KB block), so one load instruction is a wave-uniform base plus 16 bytes per lane.  Unit
+    // j = q * WAVES + wave belongs to this wave; HAS_LAST says whether its unit q = LPW-1 exists.
+    const char* ubase[S::LPW];
     const int kt_total = a.K / G_BK;
+    const unsigned lane16 = lane * 16;
 #pragma unroll
     for (int q = 0; q < S::LPW; ++q) {
-        const int local = 4 * q + (lane >> 4);
-        gact[q] = local < S::SRW;
-        const int sr = wave * S::SRW + min(local, S::SRW - 1);
+        const int j = min(q * S::WAVES + wave, S::NL - 1);
         const u16* base;
-        int blk, within;
-        if (sr < G_BM / 4) {
-            blk = min(m0 / 32 + (sr >> 3), (a.M + 31) / 32 - 1);  // blocks past M repeat the last one
-            within = sr & 7;
+        int blk;
+        if (j < G_BM / 16) {
+            blk = min(m0 / 32 + (j >> 1), (a.M + 31) / 32 - 1);  // blocks past M repeat the last one
             base = a.A;
         } else {
-            const int srw = sr - G_BM / 4;
-            blk = min(n0 / 32 + (srw >> 3), a.N / 32 - 1);  // blocks past N repeat the last one
-            within = srw & 7;
+            blk = min(n0 / 32 + ((j - G_BM / 16) >> 1), a.N / 32 - 1);  // blocks past N repeat the last one
             base = a.W;
         }
-        gp[q] = base + ((size_t)blk * kt_total + (size_t)split * KT) * 1024 + within * 128 + (lane & 15) * 8;
+        ubase[q] = uniform_ptr((const char*)(base + ((size_t)blk * kt_total + (size_t)split * KT) * 1024 + (j & 1) * 512));
     }
-    const int ldst0 = wave * S::SRW * 256;
-    auto issue = [&](int stage, int kt) {
+    auto issue_one = [&](int q, int stage, int kt) {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(uniform_ptr(ubase[q] + (size_t)kt * 2048) + lane16),
+            (__attribute__((address_space(3))) void*)(smem + stage * S::STAGE_BYTES + (q * S::WAVES + wave) * 1024),
+            16, 0, 0);
+    };
+    auto issue = [&](auto has_last, int stage, int kt) {
+        constexpr int CNT = S::REM == 0 || decltype(has_last)::value ? S::LPW : S::LPW - 1;
 #pragma unroll
-        for (int q = 0; q < S::LPW; ++q) {
-            if (4 * q + 4 <= S::SRW || gact[q])
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(gp[q] + (size_t)kt * 1024),
-                    (__attribute__((address_space(3))) void*)(smem + stage * S::STAGE_BYTES + ldst0 + q * 1024), 16,
-                    0, 0);
-        }
+        for (int q = 0; q < CNT; ++q) issue_one(q, stage, kt);
     };
 
     // ---- LDS -> register fragment addresses -------------------------------------------------------------
@@ -189,6 +195,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
     for (int ks = 0; ks < 2; ++ks)
         lane_off[ks] = (c >> 2) * 256 + ((((c & 3) << 2) + 2 * ks + hh) ^ ((c >> 2) & 3)) * 16;
     const int a_base = wm * MBW * 2048, b_base = G_BM * 64 + wn * NBW * 2048;
+    // Read number t of a sub-step, in the order the MFMAs need them: a[0], b[0], the other a, the other b.
+    auto load_frag_one = [&](Frags<MBW, NBW>& f, int stage, int ks, int t) {
+        const unsigned char* sb = smem + stage * S::STAGE_BYTES + lane_off[ks];
+        if (t == 0) f.a[0] = *(const bf16x8*)(sb + a_base);
+        else if (t == 1) f.b[0] = *(const bf16x8*)(sb + b_base);
+        else if (t < MBW + 1) f.a[t - 1] = *(const bf16x8*)(sb + a_base + (t - 1) * 2048);
+        else f.b[t - MBW] = *(const bf16x8*)(sb + b_base + (t - MBW) * 2048);
+    };
     auto load_frags = [&](Frags<MBW, NBW>& f, int stage, int ks) {
         const unsigned char* sb = smem + stage * S::STAGE_BYTES + lane_off[ks];
 #pragma unroll
@@ -214,23 +228,32 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
 
     // ---- prologue: fill all but one slot of the ring, fetch the first fragments -----------------------------
     constexpr int ST = S::STAGES;
+    Frags<MBW, NBW> f0, f1;
+#if GEMM_TIMELINE
+    unsigned long long tl_vm = 0, tl_bar = 0, tl_n = 0, tl_first = 0, tl_last = 0;
+    const unsigned long long tl_start = __builtin_amdgcn_s_memtime();
+    const unsigned long long tl_rstart = __builtin_amdgcn_s_memrealtime();
+#endif
+    // The whole K loop exists once per load count (waves with and without the last load unit), so that no
+    // load sits under a condition: a branch inside the loop would also cut it into scheduling regions.
+    auto k_loop = [&](auto has_last) {
+    constexpr int CNT = S::REM == 0 || decltype(has_last)::value ? S::LPW : S::LPW - 1;  // loads per stage
 #pragma unroll
     for (int s = 0; s < ST - 1; ++s)
-        if (s < KT) issue(s, s);
-    if (KT >= ST - 1) wait_vmcnt<(ST - 2) * S::LPW>();  // stage 0 landed, the others may be in flight
+        if (s < KT) issue(has_last, s, s);
+    if (KT >= ST - 1) wait_vmcnt<(ST - 2) * CNT>();  // stage 0 landed, the others may be in flight
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    Frags<MBW, NBW> f0, f1;
     load_frags(f0, 0, 0);
     wait_lgkmcnt0();
 
     // Waits until at most g of this wave's load groups (one group = one stage) are still in flight.
     auto wait_groups = [&](int g) {
-        if (g >= ST - 3) wait_vmcnt<(ST - 3) * S::LPW>();
-        else if (g == 4) wait_vmcnt<(ST > 7 ? 4 : 0) * S::LPW>();
-        else if (g == 3) wait_vmcnt<(ST > 6 ? 3 : 0) * S::LPW>();
-        else if (g == 2) wait_vmcnt<(ST > 5 ? 2 : 0) * S::LPW>();
-        else if (g == 1) wait_vmcnt<1 * S::LPW>();
+        if (g >= ST - 3) wait_vmcnt<(ST - 3) * CNT>();
+        else if (g == 4) wait_vmcnt<(ST > 7 ? 4 : 0) * CNT>();
+        else if (g == 3) wait_vmcnt<(ST > 6 ? 3 : 0) * CNT>();
+        else if (g == 2) wait_vmcnt<(ST > 5 ? 2 : 0) * CNT>();
+        else if (g == 1) wait_vmcnt<1 * CNT>();
         else wait_vmcnt<0>();
     };
 
@@ -243,17 +266,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
     // STEADY stages (kt + ST - 1 < KT) have no conditions at all; the main loop runs ST of them per trip
     // with the ring slots as compile-time constants, so a trip is one straight run of instructions (taken
     // branches starve the MFMA pipe: the instruction buffer refills while nothing issues).
-#if GEMM_TIMELINE
-    unsigned long long tl_vm = 0, tl_bar = 0, tl_n = 0, tl_first = 0, tl_last = 0;
-    const unsigned long long tl_start = __builtin_amdgcn_s_memtime();
-    const unsigned long long tl_rstart = __builtin_amdgcn_s_memrealtime();
-#endif
     auto do_stage = [&](auto steady, int kt, int stage, int pstage, int nstage) {
         constexpr bool STEADY = decltype(steady)::value;
         if (STEADY) {
 #if GEMM_TIMELINE
             const unsigned long long t0 = __builtin_amdgcn_s_memtime();
-            wait_vmcnt<(ST - 3) * S::LPW>();
+            wait_vmcnt<(ST - 3) * CNT>();
             const unsigned long long t1 = __builtin_amdgcn_s_memtime();
             __builtin_amdgcn_s_barrier();
             const unsigned long long t2 = __builtin_amdgcn_s_memtime();
@@ -261,22 +279,49 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
             if (tl_first == 0) tl_first = t0;
             tl_last = t2;
 #else
-            wait_vmcnt<(ST - 3) * S::LPW>();
+            wait_vmcnt<(ST - 3) * CNT>();
             if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
 #endif
-            if (!(GEMM_EXPERIMENT & 1)) issue(pstage, kt + ST - 1);
         } else if (kt + 1 < KT) {
             wait_groups(KT - 1 - (kt + 1));  // stages issued after kt+1 may stay in flight
             if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
-            if (!(GEMM_EXPERIMENT & 1) && kt + ST - 1 < KT) issue(pstage, kt + ST - 1);
+            if (!(GEMM_EXPERIMENT & 1) && kt + ST - 1 < KT) issue(has_last, pstage, kt + ST - 1);
         }
-        if (!(GEMM_EXPERIMENT & 4) || kt == 0) load_frags(f1, stage, 1);
-        mma(f0, 0, NBW);
-        if (!(GEMM_EXPERIMENT & 4) && (STEADY || kt + 1 < KT)) load_frags(f0, nstage, 0);
-        mma(f1, 0, NBW);
         if (STEADY && GEMM_EXPERIMENT == 0) {
-            sched_half<MBW * NBW, MBW + NBW, (S::LPW + 1) / 2>();
-            sched_half<MBW * NBW, MBW + NBW, S::LPW / 2>();
+            // Memory instructions are dealt out behind the MFMAs, one or two after each, and the compiler's
+            // scheduler is fenced at every step: a burst of LDS reads or global->LDS loads would hold the
+            // wave's issue port while the matrix pipe runs dry.
+            constexpr int NM = MBW * NBW, RD = MBW + NBW;
+            constexpr int V1 = (CNT + 1) / 2, V2 = CNT - V1;
+            auto half = [&]<int... M>(std::integer_sequence<int, M...>, auto second) {
+                constexpr bool SECOND = decltype(second)::value;
+                constexpr int TOT = RD + (SECOND ? V2 : V1);
+                auto step = [&](auto mi) {
+                    constexpr int m = decltype(mi)::value;
+                    const Frags<MBW, NBW>& use = SECOND ? f1 : f0;
+                    acc[m % MBW][m / MBW] = mfma32(use.a[m % MBW], use.b[m / MBW], acc[m % MBW][m / MBW]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int t = TOT * m / NM; t < TOT * (m + 1) / NM; ++t) {
+                        if (t < RD) {
+                            if (SECOND) load_frag_one(f0, nstage, 0, t);
+                            else load_frag_one(f1, stage, 1, t);
+                        } else {
+                            issue_one((SECOND ? V1 : 0) + t - RD, pstage, kt + ST - 1);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                (step(std::integral_constant<int, M>{}), ...);
+            };
+            half(std::make_integer_sequence<int, NM>{}, std::false_type{});
+            half(std::make_integer_sequence<int, NM>{}, std::true_type{});
+        } else {
+            if (STEADY && !(GEMM_EXPERIMENT & 1)) issue(has_last, pstage, kt + ST - 1);
+            if (!(GEMM_EXPERIMENT & 4) || kt == 0) load_frags(f1, stage, 1);
+            mma(f0, 0, NBW);
+            if (!(GEMM_EXPERIMENT & 4) && (STEADY || kt + 1 < KT)) load_frags(f0, nstage, 0);
+            mma(f1, 0, NBW);
         }
         // f0 (next stage) has had the last MFMAs to arrive; waiting here keeps the next stage's reads out of
         // the wait and leaves no LDS read of this wave outstanding at the barrier.
@@ -293,6 +338,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
         const int pstage = stage == 0 ? ST - 1 : stage - 1;
         do_stage(std::false_type{}, kt, stage, pstage, nstage);
         stage = nstage;
+    }
+    };
+    if constexpr (S::REM == 0) {
+        k_loop(std::true_type{});
+    } else {
+        if (wave < S::REM) k_loop(std::true_type{});
+        else k_loop(std::false_type{});
     }
 
 #if GEMM_TIMELINE
