@@ -46,23 +46,27 @@ __global__ void rope_table(float2* __restrict__ tab, int n, int pos0, float thet
     tab[gid] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
-// One 256-thread block per row; the row (d <= 8192) stays in registers between the two passes.
+// One block per row, IT float4 per thread (the row stays in registers between the two passes).  A row has
+// few bytes and there are few rows, so the block is wide (d/8 threads when that is a whole number of waves):
+// every load of a thread is independent and enough of them must be in flight per CU to cover HBM latency.
 //   v    = (hidden_in ? bf16 row of hidden_in : x32 row) + sum over splits of the partial rows
 //   x32 <- v                              (when anything was added or the row came from hidden_in)
 //   xn  <- bf16(v * rsqrt(mean v^2 + eps) * g)   (when g != NULL)
 //   out <- bf16(v)                        (when out != NULL)
-__global__ __launch_bounds__(256) void reduce_norm(float* __restrict__ x32, const u16* __restrict__ hidden_in,
-                                                   const float* __restrict__ partial, int splits, size_t split_stride,
-                                                   const u16* __restrict__ g, u16* __restrict__ xn,
-                                                   u16* __restrict__ out, int d, float eps) {
-    __shared__ float part[4];
+template <int IT>
+__global__ __launch_bounds__(1024) void reduce_norm(float* __restrict__ x32, const u16* __restrict__ hidden_in,
+                                                    const float* __restrict__ partial, int splits, size_t split_stride,
+                                                    const u16* __restrict__ g, u16* __restrict__ xn,
+                                                    u16* __restrict__ out, int d, float eps) {
+    __shared__ float part[16];
     const size_t row = blockIdx.x;
     const int nvec = d >> 2;  // float4 per row
-    float4 v[8];
+    const int nthr = blockDim.x;
+    float4 v[IT];
     float ss = 0.f;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int idx = threadIdx.x + it * 256;
+    for (int it = 0; it < IT; ++it) {
+        const int idx = threadIdx.x + it * nthr;
         if (idx < nvec) {
             float4 x;
             if (hidden_in) {
@@ -72,10 +76,13 @@ __global__ __launch_bounds__(256) void reduce_norm(float* __restrict__ x32, cons
             } else {
                 x = *(const float4*)(x32 + row * d + idx * 4);
             }
-            for (int s = 0; s < splits; ++s) {
-                const float4 p = *(const float4*)(partial + s * split_stride + row * d + idx * 4);
-                x.x += p.x; x.y += p.y; x.z += p.z; x.w += p.w;
-            }
+            float4 p[8];  // all loads first (at most 8 splits), then the sum in split order
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                if (s < splits) p[s] = *(const float4*)(partial + s * split_stride + row * d + idx * 4);
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                if (s < splits) { x.x += p[s].x; x.y += p[s].y; x.z += p[s].z; x.w += p[s].w; }
             if (hidden_in || splits > 0) *(float4*)(x32 + row * d + idx * 4) = x;
             if (out) {
                 u32x2 o;
@@ -91,10 +98,12 @@ __global__ __launch_bounds__(256) void reduce_norm(float* __restrict__ x32, cons
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float inv = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)d + eps);
+    float tot = 0.f;
+    for (int w = 0; w < (nthr >> 6); ++w) tot += part[w];  // same order in every thread
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int idx = threadIdx.x + it * 256;
+    for (int it = 0; it < IT; ++it) {
+        const int idx = threadIdx.x + it * nthr;
         if (idx < nvec) {
             const u32x2 gg = *(const u32x2*)(g + idx * 4);
             u32x2 o;
@@ -125,8 +134,12 @@ void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s)
 }
 void launch_reduce_norm(float* x32, const u16* hidden_in, const float* partial, int splits, size_t split_stride,
                         const u16* g, u16* xn, u16* out, int n, int d, float eps, hipStream_t s) {
-    hipLaunchKernelGGL(reduce_norm, dim3(n), dim3(256), 0, s, x32, hidden_in, partial, splits, split_stride, g, xn, out,
-                       d, eps);
+    if (d % 512 == 0 && d / 8 <= 1024)
+        hipLaunchKernelGGL(reduce_norm<2>, dim3(n), dim3(d / 8), 0, s, x32, hidden_in, partial, splits, split_stride, g,
+                           xn, out, d, eps);
+    else
+        hipLaunchKernelGGL(reduce_norm<8>, dim3(n), dim3(256), 0, s, x32, hidden_in, partial, splits, split_stride, g,
+                           xn, out, d, eps);
 }
 
 }  // namespace jup
