@@ -3,8 +3,10 @@
 //
 // One workgroup = QB*32 queries of one head, 4 waves.  The waves split the key range: wave w takes the
 // 32-key tiles w, w+4, ... of the keys this query block can see.  Each wave runs a private two-slot
-// LDS pipeline filled by direct global->LDS loads, so the main loop has no workgroup barrier.  Each
-// wave computes the TRANSPOSED products
+// LDS pipeline filled by direct global->LDS loads, so the main loop has no workgroup barrier, and it is
+// software-pipelined: the K fragments of the next tile are fetched from LDS under the P V products of
+// this one, the V^T fragments under the K Q^T products, and a slot is refilled (two tiles ahead) as soon
+// as its last fragment has been read.  Each wave computes the TRANSPOSED products
 //     S^T[key][query] = K Q^T        (A = K tile rows, B = Q)
 //     O^T[dh][query] += V^T P^T      (A = V^T, read from the row-major V tile with the transposing LDS
 //                                     load; B = P^T taken straight from the S^T accumulators)
@@ -42,6 +44,12 @@ constexpr int kKT = 32;                 // keys per tile
 constexpr int kTileBytes = kKT * 256;   // one K or V tile: 32 rows of 128 bf16
 constexpr int kSlotBytes = 2 * kTileBytes;
 constexpr int kWaveLds = 2 * kSlotBytes;  // two slots (K + V each) per wave = 32 KB
+// dynamic LDS: the merge at the end needs four fp32 [64][132] regions plus the statistics
+constexpr int kStatOffset = 4 * 64 * 132 * 4;               // softmax statistics of the four waves (past the tile slots)
+constexpr int kQOffset = kStatOffset + 2 * 4 * 64 * 4;      // the block's queries follow: [64 rows][256 B], K-tile layout
+static_assert(kStatOffset >= 4 * kWaveLds, "the statistics are written while other waves still read their slots");
+constexpr int kAttLds = kQOffset + 64 * 256;
+static_assert(kAttLds >= 4 * kWaveLds && kAttLds <= 160 * 1024, "LDS budget");
 
 // LDS tile layouts (rows of 256 bytes = 16 chunks of 16 bytes):
 //   K: chunk ch of row r at position ch ^ (r & 15)            (16 consecutive rows, same chunk: 16 banksets)
@@ -49,6 +57,28 @@ constexpr int kWaveLds = 2 * kSlotBytes;  // two slots (K + V each) per wave = 3
 //      their 64-byte groups over the four 64-byte bank groups for the transposing reads)
 __device__ inline int k_pos(int r, int ch) { return ch ^ (r & 15); }
 __device__ inline int v_pos(int r, int ch) { return (((ch >> 2) ^ (r & 3)) << 2) | (ch & 3); }
+
+// LDS byte address of a pointer into the workgroup's dynamic LDS.
+__device__ inline unsigned lds_addr(const void* p) {
+    return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+// Transposing 8-byte LDS read, issued as text so that the compiler's wait-count pass does not treat it as a
+// read that may alias the global->LDS loads in flight (it would drain them all before every read, which
+// undoes the prefetch).  The compiler does not know that a result is pending either: every use of the
+// results is preceded by wait_tr_reads() on the registers concerned.
+template <int OFF>
+__device__ inline u32x2 ds_read_tr16(unsigned addr) {
+    u32x2 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+// Waits until at most N LDS reads issued after the ones that fill v are still in flight; v is named as
+// an operand so that no use of it can be moved above the wait.
+template <int N>
+__device__ inline void wait_tr_reads(u32x4& v) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(v) : "n"(N));
+}
 
 template <int QB>
 __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restrict__ q, u16* __restrict__ o, int n,
@@ -72,16 +102,6 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
     const size_t plane_k = ((size_t)layer * 2 + 0) * n_heads + head;
     const size_t plane_v = ((size_t)layer * 2 + 1) * n_heads + head;
 
-    // Q fragments (B operand of S^T): lane = query column, 8 consecutive dh per k-step.
-    bf16x8 qf[QB][8];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int qrow = min(q0 + qb * 32 + c, n - 1);
-        const u16* qp = q + (size_t)qrow * d_model + head * 128 + 8 * hh;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[qb][ks] = *(const bf16x8*)(qp + 16 * ks);
-    }
-
     f32x16 oacc[QB][4];
     float m_run[QB], l_run[QB];
 #pragma unroll
@@ -95,64 +115,122 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
     }
 
     // Tile fill: 8 wave-wide loads for K and 8 for V.  Load j covers rows 4j..4j+3 (1 KB of LDS); lane i
-    // lands at row 4j + (i >> 4), position i & 15, and fetches the chunk that belongs there.
+    // lands at row 4j + (i >> 4), position i & 15, and fetches the chunk that belongs there.  A tile that
+    // lies inside one cache segment and below the last visible key (all but two or three) is a wave-uniform
+    // base plus a per-lane constant; the others compute every row's address.
     const int lrow = lane >> 4, lp = lane & 15;
     // plane bases of the two cache segments (the parent's is never dereferenced when nothing is shared)
     const u16* k_own = (const u16*)kv.own + plane_k * (size_t)kv.own_cap * 128;
     const u16* v_own = (const u16*)kv.own + plane_v * (size_t)kv.own_cap * 128;
     const u16* k_par = (const u16*)kv.parent + plane_k * (size_t)kv.parent_cap * 128;
     const u16* v_par = (const u16*)kv.parent + plane_v * (size_t)kv.parent_cap * 128;
+    unsigned gk[4];  // byte offset inside the tile of this lane's K chunk for loads j = t (mod 4)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) gk[t] = lrow * 256 + (lp ^ (4 * t + lrow)) * 16;
+    const unsigned gv = lrow * 256 + ((((lp >> 2) ^ lrow) << 2) | (lp & 3)) * 16;
     auto fill = [&](int tile, int slot) {
         unsigned char* kd = my + slot * kSlotBytes;
         unsigned char* vd = kd + kTileBytes;
+        const int key0 = tile * kKT;
+        if (key0 + kKT - 1 <= last_key && (key0 >= kv.n_shared || key0 + kKT <= kv.n_shared)) {
+            const bool shared = key0 < kv.n_shared;
+            const size_t row0 = (size_t)(shared ? key0 : key0 - kv.n_shared) * 128;
+            const char* kb = uniform_ptr((const char*)((shared ? k_par : k_own) + row0));
+            const char* vb = uniform_ptr((const char*)((shared ? v_par : v_own) + row0));
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int r = 4 * j + lrow;
-            const int key = min(tile * kKT + r, last_key);
-            const bool shared = key < kv.n_shared;
-            const unsigned row_off = (unsigned)(shared ? key : key - kv.n_shared) * 128u;  // elements, < 2^31
-            const u16* kr = (shared ? k_par : k_own) + row_off + (lp ^ (r & 15)) * 8;
-            const u16* vr = (shared ? v_par : v_own) + row_off + ((((lp >> 2) ^ (r & 3)) << 2) | (lp & 3)) * 8;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)kr,
-                                             (__attribute__((address_space(3))) void*)(kd + j * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vr,
-                                             (__attribute__((address_space(3))) void*)(vd + j * 1024), 16, 0, 0);
+            for (int j = 0; j < 8; ++j) {
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kb + j * 1024 + gk[j & 3]),
+                                                 (__attribute__((address_space(3))) void*)(kd + j * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vb + j * 1024 + gv),
+                                                 (__attribute__((address_space(3))) void*)(vd + j * 1024), 16, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = 4 * j + lrow;
+                const int key = min(key0 + r, last_key);
+                const bool shared = key < kv.n_shared;
+                const unsigned row_off = (unsigned)(shared ? key : key - kv.n_shared) * 128u;  // elements, < 2^31
+                const u16* kr = (shared ? k_par : k_own) + row_off + (lp ^ (r & 15)) * 8;
+                const u16* vr = (shared ? v_par : v_own) + row_off + ((((lp >> 2) ^ (r & 3)) << 2) | (lp & 3)) * 8;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)kr,
+                                                 (__attribute__((address_space(3))) void*)(kd + j * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vr,
+                                                 (__attribute__((address_space(3))) void*)(vd + j * 1024), 16, 0, 0);
+            }
         }
     };
 
     // Per-lane LDS read offsets.
-    //   K fragment (ks): row c, chunk 2ks + hh.
+    //   K fragment ks: row c, chunk 2ks + hh, stored at position (2ks + hh) ^ (c & 15): the ks term is an
+    //   XOR with 32 ks on the byte offset.
     //   V^T fragment (db, ks, part): transposing read; lane = 16*G + s supplies the address of
-    //   V[key = 16ks + 8*part + 4*(G>>1) + (s>>2)][dh = 32db + 16*(G&1) + 4*(s&3) .. +3].
+    //   V[key = 16ks + 8*part + 4*(G>>1) + (s>>2)][dh = 32db + 16*(G&1) + 4*(s&3) .. +3]: the row's low two
+    //   bits are s >> 2, so the db term is an XOR on the 64-byte group index and (ks, part) an immediate.
+    const unsigned k_lane = c * 256 + ((hh ^ (c & 15)) * 16);
     const int G = lane >> 4, s = lane & 15;
-    const int vt_row = 4 * (G >> 1) + (s >> 2);         // + 16ks + 8part
-    const int vt_dh = 16 * (G & 1) + 4 * (s & 3);       // + 32db   (in elements)
+    const int vt_row = 4 * (G >> 1) + (s >> 2);
+    unsigned v_lane[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+        v_lane[db] = vt_row * 256 + ((db ^ (vt_row & 3)) << 6) + (2 * (G & 1) + ((s & 3) >> 1)) * 16 + 8 * (s & 1);
 
-    int tile = wave;
-    int slot = 0;
-    if (tile < n_tiles) fill(tile, 0);
-    for (; tile < n_tiles; tile += 4) {
-        wait_vmcnt<0>();  // this tile has landed (only this wave reads it)
-        if (tile + 4 < n_tiles) fill(tile + 4, slot ^ 1);
-        const unsigned char* ks_base = my + slot * kSlotBytes;
-        const unsigned char* vs_base = ks_base + kTileBytes;
+    // This wave's tiles are wave, wave + 4, ...; tile number i of them lives in slot i & 1.  Two tiles are
+    // put in flight before the queries are fetched, and everything is waited for once: inside the loop the
+    // only vector-memory operations outstanding are the refills.
+    const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
+    if (cnt > 0) fill(wave, 0);
+    if (cnt > 1) fill(wave + 4, 1);
 
-        // S^T = K Q^T for the 32 keys of the tile.
+    // The block's queries go to LDS in the K-tile layout (they are the B operand of S^T: lane = query
+    // column, 8 consecutive dh per k-step); wave w fetches rows 16w .. 16w+15.  Keeping them in registers
+    // instead costs 64 VGPRs per lane, which the softmax needs.
+    unsigned char* q_lds = lds + kQOffset;
+    if (wave < QB * 2) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = 16 * wave + 4 * j + lrow;
+            const int qrow = min(q0 + r, n - 1);
+            const u16* qp = q + (size_t)qrow * d_model + head * 128 + (lp ^ (r & 15)) * 8;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)qp,
+                                             (__attribute__((address_space(3))) void*)(q_lds + (16 * wave + 4 * j) * 256),
+                                             16, 0, 0);
+        }
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    // A tile is processed in two parts.  front: scores, softmax statistics, probabilities; it reports whether
+    // any lane moved its reference maximum, in which case the accumulators must be rescaled before back:
+    // P V products, slot refill.  The rescaling code is kept out of the loop that runs the common case (its
+    // mere presence there makes the compiler copy 64 accumulator registers per tile ahead of the branch).
+    bf16x8 pf[QB][2];
+    float alpha[QB];
+    auto front = [&](auto masked, int i) -> bool {
+        constexpr bool MASKED = decltype(masked)::value;
+        const int tile = wave + 4 * i, slot = i & 1;
+        const unsigned char* k_base = my + slot * kSlotBytes;
+
+        // ---- S^T = K Q^T for the 32 keys of the tile ------------------------------------------------------------
+        bf16x8 kf[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kf[ks] = *(const bf16x8*)(k_base + (k_lane ^ (32 * ks)));
         f32x16 sacc[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 kf = *(const bf16x8*)(ks_base + c * 256 + k_pos(c, 2 * ks + hh) * 16);
+        for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) sacc[qb] = mfma32(kf, qf[qb][ks], sacc[qb]);
-        }
+            for (int qb = 0; qb < QB; ++qb) {
+                const bf16x8 qf = *(const bf16x8*)(q_lds + qb * 8192 + (k_lane ^ (32 * ks)));
+                sacc[qb] = mfma32(kf[ks], qf, sacc[qb]);
+            }
 
+        // ---- online softmax; a lane owns one query column of each query block -------------------------------
         const int key0 = tile * kKT;
-        const bool need_mask = tile >= first_masked_tile;
-        bf16x8 pf[QB][2];
+        bool any_rescale = false;
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const int q_abs = pos0 + q0 + qb * 32 + c;  // absolute position of this lane's query
@@ -160,65 +238,107 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
             float mt = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                sv[r] = sacc[qb][r] * scale_log2e;
-                if (need_mask && key0 + acc_row(r, hh) > q_abs) sv[r] = -INFINITY;
+                sv[r] = sacc[qb][r];
+                if (MASKED && key0 + acc_row(r, hh) > q_abs) sv[r] = -INFINITY;
                 mt = fmaxf(mt, sv[r]);
             }
-            mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-            const float m_new = fmaxf(m_run[qb], mt);
+            mt = fmaxf(mt, __shfl_xor(mt, 32, 64)) * scale_log2e;  // the scale is positive
+            // The reference maximum follows the running maximum lazily: it moves only when a tile exceeds it
+            // by more than 2^8, so the accumulators are rescaled a few times per query instead of at every
+            // tile whose maximum creeps up.  Probabilities then reach 2^8 at most, which bf16 and the fp32
+            // sums hold as well as values below 1; the final division by the sum removes the factor.
+            const bool grow = mt > m_run[qb] + 8.0f;  // also the first finite maximum (m_run = -inf)
+            const float m_new = grow ? mt : m_run[qb];
             const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_safe);
+            alpha[qb] = grow ? __builtin_amdgcn_exp2f(m_run[qb] - m_safe) : 1.0f;
+            any_rescale |= grow && m_run[qb] != -INFINITY;  // nothing accumulated yet otherwise
             float ps = 0.f;
             float pv[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                pv[r] = __builtin_amdgcn_exp2f(sv[r] - m_safe);
+                pv[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], scale_log2e, -m_safe));
                 ps += pv[r];
             }
-            l_run[qb] = l_run[qb] * alpha + ps;
+            l_run[qb] = l_run[qb] * alpha[qb] + ps;
             m_run[qb] = m_new;
-            if (__any(alpha != 1.0f)) {
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
-            }
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pf[qb][ks][e] = (__bf16)pv[8 * ks + e];
         }
-
-        // O^T += V^T P^T.
+        return __any(any_rescale);
+    };
+    auto rescale_all = [&]() {
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                s16x4 part[2];
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt) {
-                    const int r = 16 * ks + 8 * pt + vt_row;
-                    const int el = 32 * db + vt_dh;  // element index in the row; chunk = el >> 3, +8 bytes if el & 4
-                    const unsigned char* ap = vs_base + r * 256 + v_pos(r, el >> 3) * 16 + (el & 4) * 2;
-                    part[pt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)ap);
+                for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha[qb];
+    };
+    auto back = [&](int i) {
+        const int tile = wave + 4 * i, slot = i & 1;
+        const unsigned v_base = lds_addr(my + slot * kSlotBytes + kTileBytes);
+        // ---- O^T += V^T P^T ----------------------------------------------------------------------------------------
+        // All eight V^T fragments (two 8-byte transposing reads each) are requested at once and consumed in
+        // order as they arrive; when the last has arrived the slot is free and is refilled two tiles ahead.
+        u32x4 vf[8];
+        [&]<int... F>(std::integer_sequence<int, F...>) {
+            (([&] {
+                 constexpr int db = F / 2, ks = F % 2;
+                 const u32x2 lo = ds_read_tr16<(16 * ks) * 256>(v_base + v_lane[db]);
+                 const u32x2 hi = ds_read_tr16<(16 * ks + 8) * 256>(v_base + v_lane[db]);
+                 // the two 8-byte results are the low and high halves of the 16-byte operand
+                 vf[F] = (u32x4){lo[0], lo[1], hi[0], hi[1]};
+             }()),
+             ...);
+        }(std::make_integer_sequence<int, 8>{});
+        [&]<int... F>(std::integer_sequence<int, F...>) {
+            (([&] {
+                 wait_tr_reads<14 - 2 * F>(vf[F]);
+                 if (F == 7 && i + 2 < cnt) fill(tile + 8, slot);
+#pragma unroll
+                 for (int qb = 0; qb < QB; ++qb)
+                     oacc[qb][F / 2] = mfma32(__builtin_bit_cast(bf16x8, vf[F]), pf[qb][F % 2], oacc[qb][F / 2]);
+             }()),
+             ...);
+        }(std::make_integer_sequence<int, 8>{});
+        if (i + 1 < cnt) {  // the next tile has landed; the refill just issued may be in flight
+            if (i + 2 < cnt) wait_vmcnt<16>();
+            else wait_vmcnt<0>();
+        }
+    };
+    // Tiles below first_masked_tile lie under every query's diagonal and skip the mask arithmetic.
+    const int cnt_plain = min(cnt, first_masked_tile > wave ? (first_masked_tile - wave + 3) / 4 : 0);
+    int it = 0;
+    auto run = [&](auto masked, int end) {
+        while (it < end) {
+            bool slow = false;
+            for (; it < end; ++it) {
+                if (front(masked, it)) {
+                    slow = true;
+                    break;
                 }
-                // the two 8-byte results are the low and high halves of the 16-byte operand
-                const u32x2 lo = __builtin_bit_cast(u32x2, part[0]), hi = __builtin_bit_cast(u32x2, part[1]);
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, (u32x4){lo[0], lo[1], hi[0], hi[1]});
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) oacc[qb][db] = mfma32(vf, pf[qb][ks], oacc[qb][db]);
+                back(it);
+            }
+            if (slow) {
+                rescale_all();
+                back(it);
+                ++it;
             }
         }
-        slot ^= 1;
-    }
-    wait_vmcnt<0>();
+    };
+    run(std::false_type{}, cnt_plain);
+    run(std::true_type{}, cnt);
 
     // ---- merge the four waves' partial results --------------------------------------------------------
-    __syncthreads();  // every wave is done with its tile slots; LDS is reused below
-    float* stat_m = (float*)lds;                  // [4][QB*32]
-    float* stat_l = stat_m + 4 * QB * 32;         // [4][QB*32]
-    float* obuf = stat_l + 4 * QB * 32;           // [QB*32][132] fp32 (padded rows)
-    constexpr int kORow = 132;
+    // Statistics live past the tile slots; the fp32 output regions (one per wave) overlap other waves' slots
+    // and are written only after the barrier.
+    constexpr int kORow = 132;                              // padded fp32 row
+    constexpr int kRegion = QB * 32 * kORow;                // floats per wave
+    float* obuf = (float*)lds;                              // [4][QB*32][132]
+    float* stat_m = (float*)(lds + kStatOffset);            // [4][QB*32]
+    float* stat_l = stat_m + 4 * QB * 32;                   // [4][QB*32]
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
@@ -227,8 +347,8 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
             stat_l[wave * QB * 32 + qb * 32 + c] = l_tot;
         }
     }
-    __syncthreads();
-    float wscale[QB];
+    __syncthreads();  // statistics visible; every wave is done with its tile slots
+    float* mine = obuf + wave * kRegion;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         float m_all = -INFINITY;
@@ -240,38 +360,35 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
             const float mw = stat_m[w * QB * 32 + qb * 32 + c];
             l_all += mw == -INFINITY ? 0.f : stat_l[w * QB * 32 + qb * 32 + c] * exp2f(mw - m_all);
         }
-        wscale[qb] = m_run[qb] == -INFINITY ? 0.f : exp2f(m_run[qb] - m_all) / l_all;
+        const float wscale = m_run[qb] == -INFINITY ? 0.f : exp2f(m_run[qb] - m_all) / l_all;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                // registers 4g..4g+3 are dh = db*32 + 8g + 4hh + {0..3}: one 16-byte vector
+                *(float4*)(mine + (qb * 32 + c) * kORow + db * 32 + 8 * g + 4 * hh) =
+                    make_float4(oacc[qb][db][4 * g] * wscale, oacc[qb][db][4 * g + 1] * wscale,
+                                oacc[qb][db][4 * g + 2] * wscale, oacc[qb][db][4 * g + 3] * wscale);
+            }
     }
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        // registers 4g..4g+3 are dh = db*32 + 8g + 4hh + {0..3}: one 16-byte vector
-                        float4* p = (float4*)(obuf + (qb * 32 + c) * kORow + db * 32 + 8 * g + 4 * hh);
-                        float4 v = make_float4(oacc[qb][db][4 * g] * wscale[qb], oacc[qb][db][4 * g + 1] * wscale[qb],
-                                               oacc[qb][db][4 * g + 2] * wscale[qb], oacc[qb][db][4 * g + 3] * wscale[qb]);
-                        if (w > 0) {
-                            const float4 old = *p;
-                            v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
-                        }
-                        *p = v;
-                    }
-        }
-        __syncthreads();
-    }
-    // Write out in the GEMM operand layout: thread handles 8 consecutive dh of one query per step.
+    __syncthreads();
+    // Sum the four regions (fixed order) and write out in the GEMM operand layout: a thread handles 8
+    // consecutive dh of one query per step.
     for (int idx = tid; idx < QB * 32 * 16; idx += 256) {
         const int qr = idx >> 4, ch = idx & 15;
         const int qrow = q0 + qr;
         if (qrow >= n) continue;
         const float* src = obuf + qr * kORow + ch * 8;
-        u32x4 out;
+        float4 a = *(const float4*)src, b = *(const float4*)(src + 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) out[e] = pack_bf16x2(src[2 * e], src[2 * e + 1]);
+        for (int w = 1; w < 4; ++w) {
+            const float4 a2 = *(const float4*)(src + w * kRegion), b2 = *(const float4*)(src + w * kRegion + 4);
+            a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
+            b.x += b2.x; b.y += b2.y; b.z += b2.z; b.w += b2.w;
+        }
+        u32x4 out;
+        out[0] = pack_bf16x2(a.x, a.y); out[1] = pack_bf16x2(a.z, a.w);
+        out[2] = pack_bf16x2(b.x, b.y); out[3] = pack_bf16x2(b.z, b.w);
         *(u32x4*)(o + tiled_offset(qrow, head * 16 + ch, d_model >> 5)) = out;
     }
 }
@@ -280,20 +397,20 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
 
 hipError_t attention_configure() {
     hipError_t e = hipFuncSetAttribute((const void*)chunk_attention_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       4 * kWaveLds);
+                                       kAttLds);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute((const void*)chunk_attention_bf16<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               4 * kWaveLds);
+                               kAttLds);
 }
 
 void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
                             int layer, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
     if (n <= 32)
-        hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3((n + 31) / 32 * n_heads), dim3(256), 4 * kWaveLds, s, q, o, n,
+        hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3((n + 31) / 32 * n_heads), dim3(256), kAttLds, s, q, o, n,
                            d_model, n_heads, pos0, kv, layer, scale_log2e);
     else
-        hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(256), 4 * kWaveLds, s, q, o, n,
+        hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(256), kAttLds, s, q, o, n,
                            d_model, n_heads, pos0, kv, layer, scale_log2e);
 }
 

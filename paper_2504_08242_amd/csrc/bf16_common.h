@@ -19,6 +19,16 @@ __device__ inline u16 f2bf(float f) {
 __device__ inline float bf2f(u16 b) { return __uint_as_float((unsigned)b << 16); }
 __device__ inline unsigned pack_bf16x2(float lo, float hi) { return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16); }
 
+// Tells the compiler that p is the same in every lane (it is: built from kernel arguments, the workgroup id
+// and the wave number).  Kept opaque so that "uniform base + 32-bit lane offset" survives to instruction
+// selection and the pointer arithmetic of a load stays on the scalar unit.
+__device__ inline const char* uniform_ptr(const char* p) {
+    const unsigned long long v = (unsigned long long)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return (const char*)(((unsigned long long)hi << 32) | lo);
+}
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);

@@ -76,16 +76,6 @@ __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 #endif
 }
 
-// Tells the compiler that p is the same in every lane (it is: built from kernel arguments, the workgroup id
-// and the wave number).  Kept opaque so that "uniform base + 32-bit lane offset" survives to instruction
-// selection and the pointer arithmetic of a load stays on the scalar unit.
-__device__ inline const char* uniform_ptr(const char* p) {
-    const unsigned long long v = (unsigned long long)p;
-    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
-    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
-    return (const char*)(((unsigned long long)hi << 32) | lo);
-}
-
 // s_waitcnt with only the vector-memory counter constrained.
 template <int N>
 __device__ inline void wait_vmcnt() {
