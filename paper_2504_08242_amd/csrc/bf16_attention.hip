@@ -24,13 +24,35 @@
 // (r < 4) element (i & 3) of the 8 bytes addressed by lane 4r + (i >> 2) of the group.
 #include "bf16_common.h"
 
+// 1 = timing experiments only (the output is then overwritten with cycle counters): wave 0 of every
+// workgroup accumulates the cycles it spends in the parts of the tile loop.
+#ifndef ATT_TIMELINE
+#define ATT_TIMELINE 0
+#endif
+// Timing experiments only (results are garbage): bit 0 = the query fragments are not read (the key
+// fragment stands in), bit 1 = no MFMA, bit 2 = no exponentials, bit 3 = V^T fragments are not read,
+// bit 4 = slots are not refilled inside the loop.
+#ifndef ATT_EXPERIMENT
+#define ATT_EXPERIMENT 0
+#endif
+#if ATT_TIMELINE
+#define ATT_T(var) const unsigned long long var = __builtin_amdgcn_s_memtime()
+#else
+#define ATT_T(var)
+#endif
+
 namespace jup {
 namespace {
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+#if ATT_EXPERIMENT & 2
+    c[0] += (float)a[0] * (float)b[0];
+    return c;
+#else
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+#endif
 }
 // Row of D held in accumulator register i by a lane of half hh.
 __device__ inline int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i & 3); }
@@ -128,7 +150,7 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
 #pragma unroll
     for (int t = 0; t < 4; ++t) gk[t] = lrow * 256 + (lp ^ (4 * t + lrow)) * 16;
     const unsigned gv = lrow * 256 + ((((lp >> 2) ^ lrow) << 2) | (lp & 3)) * 16;
-    auto fill = [&](int tile, int slot) {
+    auto fill = [&](int tile, int slot) __attribute__((always_inline)) {
         unsigned char* kd = my + slot * kSlotBytes;
         unsigned char* vd = kd + kTileBytes;
         const int key0 = tile * kKT;
@@ -159,6 +181,34 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
                                                  (__attribute__((address_space(3))) void*)(vd + j * 1024), 16, 0, 0);
             }
         }
+    };
+
+    // In the loop a refill is split: the K half of a slot is free once the tile's scores are done and is
+    // reloaded under the P V products, the V half follows under the next tile's first LDS reads.  That form
+    // exists for uniform tiles only (tile_is_uniform); the others are reloaded whole by fill().
+    auto tile_is_uniform = [&](int tile) __attribute__((always_inline)) {
+        const int key0 = tile * kKT;
+        return key0 + kKT - 1 <= last_key && (key0 >= kv.n_shared || key0 + kKT <= kv.n_shared);
+    };
+    auto tile_base = [&](int tile, const u16* par, const u16* own) __attribute__((always_inline)) {
+        const int key0 = tile * kKT;
+        const bool shared = key0 < kv.n_shared;
+        return uniform_ptr((const char*)((shared ? par : own) + (size_t)(shared ? key0 : key0 - kv.n_shared) * 128));
+    };
+    auto load_k_unit = [&](const char* kb, int slot, int j) __attribute__((always_inline)) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kb + j * 1024 + gk[j & 3]),
+                                         (__attribute__((address_space(3))) void*)(my + slot * kSlotBytes + j * 1024), 16,
+                                         0, 0);
+    };
+    const char* pend_vb = nullptr;  // V half still to be reloaded (at the start of the next tile), or null
+    int pend_slot = 0;
+    auto load_pending_v = [&]() __attribute__((always_inline)) {
+        unsigned char* vd = my + pend_slot * kSlotBytes + kTileBytes;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pend_vb + j * 1024 + gv),
+                                             (__attribute__((address_space(3))) void*)(vd + j * 1024), 16, 0, 0);
+        pend_vb = nullptr;
     };
 
     // Per-lane LDS read offsets.
@@ -206,29 +256,50 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
     // mere presence there makes the compiler copy 64 accumulator registers per tile ahead of the branch).
     bf16x8 pf[QB][2];
     float alpha[QB];
-    auto front = [&](auto masked, int i) -> bool {
+#if ATT_TIMELINE
+    unsigned long long tl[6] = {0, 0, 0, 0, 0, 0};
+    const unsigned long long tl_begin = __builtin_amdgcn_s_memtime();
+#endif
+    auto front = [&](auto masked, int i) __attribute__((always_inline)) -> bool {
         constexpr bool MASKED = decltype(masked)::value;
         const int tile = wave + 4 * i, slot = i & 1;
         const unsigned char* k_base = my + slot * kSlotBytes;
 
         // ---- S^T = K Q^T for the 32 keys of the tile ------------------------------------------------------------
-        bf16x8 kf[8];
+        ATT_T(t0);
+        // Fragment reads run two k-steps ahead of the MFMAs that use them; the scheduler is fenced so that it
+        // keeps that distance (it otherwise sinks every read to just before its use and each k-step then
+        // waits out a full LDS latency).
+        bf16x8 kf[8], qf[QB][8];
+        auto read_step = [&](int ks) __attribute__((always_inline)) {
+            kf[ks] = *(const bf16x8*)(k_base + (k_lane ^ (32 * ks)));
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kf[ks] = *(const bf16x8*)(k_base + (k_lane ^ (32 * ks)));
+            for (int qb = 0; qb < QB; ++qb)
+                qf[qb][ks] = (ATT_EXPERIMENT & 1) ? kf[ks] : *(const bf16x8*)(q_lds + qb * 8192 + (k_lane ^ (32 * ks)));
+        };
+        read_step(0);
+        read_step(1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (pend_vb) load_pending_v();
         f32x16 sacc[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+        for (int ks = 0; ks < 8; ++ks) {
+            if (ks + 2 < 8) read_step(ks + 2);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                const bf16x8 qf = *(const bf16x8*)(q_lds + qb * 8192 + (k_lane ^ (32 * ks)));
-                sacc[qb] = mfma32(kf[ks], qf, sacc[qb]);
-            }
+            for (int qb = 0; qb < QB; ++qb) sacc[qb] = mfma32(kf[ks], qf[qb][ks], sacc[qb]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 
         // ---- online softmax; a lane owns one query column of each query block -------------------------------
+#if ATT_TIMELINE
+        asm volatile("s_nop 0" : "+v"(sacc[0]), "+v"(sacc[1]));  // the scores are complete here
+#endif
+        ATT_T(t1);
         const int key0 = tile * kKT;
         bool any_rescale = false;
 #pragma unroll
@@ -256,7 +327,8 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
             float pv[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                pv[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], scale_log2e, -m_safe));
+                pv[r] = (ATT_EXPERIMENT & 4) ? __builtin_fmaf(sv[r], scale_log2e, -m_safe)
+                                             : __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], scale_log2e, -m_safe));
                 ps += pv[r];
             }
             l_run[qb] = l_run[qb] * alpha[qb] + ps;
@@ -266,9 +338,14 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pf[qb][ks][e] = (__bf16)pv[8 * ks + e];
         }
+#if ATT_TIMELINE
+        asm volatile("s_nop 0" : "+v"(pf[0][0]), "+v"(pf[0][1]), "+v"(pf[1][0]), "+v"(pf[1][1]));
+        ATT_T(t2);
+        tl[0] += t1 - t0; tl[1] += t2 - t1; tl[5] += 1;
+#endif
         return __any(any_rescale);
     };
-    auto rescale_all = [&]() {
+    auto rescale_all = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -276,42 +353,77 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha[qb];
     };
-    auto back = [&](int i) {
-        const int tile = wave + 4 * i, slot = i & 1;
+    auto back_impl = [&](auto split_refill, int i, const char* kb2) __attribute__((always_inline)) {
+        constexpr bool SPLIT = decltype(split_refill)::value;  // reload the K half of the slot under the MFMAs
+        const int slot = i & 1;
         const unsigned v_base = lds_addr(my + slot * kSlotBytes + kTileBytes);
         // ---- O^T += V^T P^T ----------------------------------------------------------------------------------------
         // All eight V^T fragments (two 8-byte transposing reads each) are requested at once and consumed in
-        // order as they arrive; when the last has arrived the slot is free and is refilled two tiles ahead.
+        // order as they arrive.
         u32x4 vf[8];
         [&]<int... F>(std::integer_sequence<int, F...>) {
             (([&] {
                  constexpr int db = F / 2, ks = F % 2;
-                 const u32x2 lo = ds_read_tr16<(16 * ks) * 256>(v_base + v_lane[db]);
-                 const u32x2 hi = ds_read_tr16<(16 * ks + 8) * 256>(v_base + v_lane[db]);
-                 // the two 8-byte results are the low and high halves of the 16-byte operand
-                 vf[F] = (u32x4){lo[0], lo[1], hi[0], hi[1]};
+                 if (ATT_EXPERIMENT & 8) {
+                     vf[F] = (u32x4){v_base, v_lane[db], (unsigned)ks, 0u};
+                 } else {
+                     const u32x2 lo = ds_read_tr16<(16 * ks) * 256>(v_base + v_lane[db]);
+                     const u32x2 hi = ds_read_tr16<(16 * ks + 8) * 256>(v_base + v_lane[db]);
+                     // the two 8-byte results are the low and high halves of the 16-byte operand
+                     vf[F] = (u32x4){lo[0], lo[1], hi[0], hi[1]};
+                 }
              }()),
              ...);
         }(std::make_integer_sequence<int, 8>{});
         [&]<int... F>(std::integer_sequence<int, F...>) {
             (([&] {
                  wait_tr_reads<14 - 2 * F>(vf[F]);
-                 if (F == 7 && i + 2 < cnt) fill(tile + 8, slot);
+                 if (SPLIT && F < 4) {
+                     load_k_unit(kb2, slot, 2 * F);
+                     load_k_unit(kb2, slot, 2 * F + 1);
+                 }
 #pragma unroll
                  for (int qb = 0; qb < QB; ++qb)
                      oacc[qb][F / 2] = mfma32(__builtin_bit_cast(bf16x8, vf[F]), pf[qb][F % 2], oacc[qb][F / 2]);
              }()),
              ...);
         }(std::make_integer_sequence<int, 8>{});
-        if (i + 1 < cnt) {  // the next tile has landed; the refill just issued may be in flight
-            if (i + 2 < cnt) wait_vmcnt<16>();
-            else wait_vmcnt<0>();
+#if ATT_TIMELINE
+        asm volatile("s_nop 0" : "+v"(oacc[0][3]), "+v"(oacc[1][3]));
+#endif
+    };
+    auto back = [&](int i) __attribute__((always_inline)) {
+        const int tile = wave + 4 * i, slot = i & 1;
+        const bool refill = !(ATT_EXPERIMENT & 16) && i + 2 < cnt;
+        ATT_T(t3);
+        if (refill && tile_is_uniform(tile + 8)) {
+            back_impl(std::true_type{}, i, tile_base(tile + 8, k_par, k_own));
+            pend_vb = tile_base(tile + 8, v_par, v_own);
+            pend_slot = slot;
+            ATT_T(t4);
+            wait_vmcnt<8>();  // the next tile has landed; the K half just requested may be in flight
+#if ATT_TIMELINE
+            ATT_T(t5);
+            tl[2] += t4 - t3; tl[3] += t5 - t4;
+#endif
+        } else {
+            back_impl(std::false_type{}, i, nullptr);
+            if (refill) fill(tile + 8, slot);  // every V^T fragment has arrived: the slot is free
+            ATT_T(t4);
+            if (i + 1 < cnt) {
+                if (refill) wait_vmcnt<16>();
+                else wait_vmcnt<0>();
+            }
+#if ATT_TIMELINE
+            ATT_T(t5);
+            tl[2] += t4 - t3; tl[3] += t5 - t4;
+#endif
         }
     };
     // Tiles below first_masked_tile lie under every query's diagonal and skip the mask arithmetic.
     const int cnt_plain = min(cnt, first_masked_tile > wave ? (first_masked_tile - wave + 3) / 4 : 0);
     int it = 0;
-    auto run = [&](auto masked, int end) {
+    auto run = [&](auto masked, int end) __attribute__((always_inline)) {
         while (it < end) {
             bool slow = false;
             for (; it < end; ++it) {
@@ -330,6 +442,9 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
     };
     run(std::false_type{}, cnt_plain);
     run(std::true_type{}, cnt);
+#if ATT_TIMELINE
+    const unsigned long long tl_loop_end = __builtin_amdgcn_s_memtime();
+#endif
 
     // ---- merge the four waves' partial results --------------------------------------------------------
     // Statistics live past the tile slots; the fp32 output regions (one per wave) overlap other waves' slots
@@ -391,6 +506,14 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
         out[2] = pack_bf16x2(b.x, b.y); out[3] = pack_bf16x2(b.z, b.w);
         *(u32x4*)(o + tiled_offset(qrow, head * 16 + ch, d_model >> 5)) = out;
     }
+#if ATT_TIMELINE
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long* t = (unsigned long long*)o + (size_t)blockIdx.x * 8;
+        t[0] = tl[0]; t[1] = tl[1]; t[2] = tl[2]; t[3] = tl[3]; t[4] = tl_loop_end - tl_begin; t[5] = tl[5];
+        t[6] = __builtin_amdgcn_s_memtime() - tl_begin; t[7] = 0x1234;
+    }
+#endif
 }
 
 }  // namespace
