@@ -34,7 +34,8 @@
 #include "bf16_common.h"
 
 // 0 = product code.  Timing experiments only (results are garbage): bit 0 = no refills of the LDS ring,
-// bit 1 = no MFMA, bit 2 = no fragment reads in the loop, bit 3 = no barrier in the loop.
+// bit 1 = no MFMA, bit 2 = no fragment reads in the loop, bit 3 = no barrier in the loop, bit 4 = no rotary
+// table loads in the QKV epilogue.
 #ifndef GEMM_EXPERIMENT
 #define GEMM_EXPERIMENT 0
 #endif
@@ -48,6 +49,7 @@ namespace jup {
 namespace {
 
 constexpr int G_BM = 256, G_BK = 32;
+
 constexpr int kLdsBudget = 160 * 1024;
 
 template <int NB, int WM, int WN>
@@ -209,12 +211,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
 
-    auto mma = [&](const Frags<MBW, NBW>& f, int nb_lo, int nb_hi) {
-#pragma unroll
-        for (int nb = nb_lo; nb < nb_hi; ++nb)
-#pragma unroll
-            for (int mb = 0; mb < MBW; ++mb) acc[mb][nb] = mfma32(f.a[mb], f.b[nb], acc[mb][nb]);
-    };
 
     // ---- prologue: fill all but one slot of the ring, fetch the first fragments -----------------------------
     constexpr int ST = S::STAGES;
@@ -236,6 +232,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
     __builtin_amdgcn_s_barrier();
     load_frags(f0, 0, 0);
     wait_lgkmcnt0();
+    if (GEMM_EXPERIMENT & 4) f1 = f0;
 
     // Waits until at most g of this wave's load groups (one group = one stage) are still in flight.
     auto wait_groups = [&](int g) {
@@ -256,9 +253,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
     // STEADY stages (kt + ST - 1 < KT) have no conditions at all; the main loop runs ST of them per trip
     // with the ring slots as compile-time constants, so a trip is one straight run of instructions (taken
     // branches starve the MFMA pipe: the instruction buffer refills while nothing issues).
-    auto do_stage = [&](auto steady, int kt, int stage, int pstage, int nstage) {
-        constexpr bool STEADY = decltype(steady)::value;
-        if (STEADY) {
+    // REFILL: the slot behind (pstage) is reloaded with stage kt+ST-1.  LAST: no stage follows (nothing is
+    // prefetched and nothing waited for at the top).
+    auto do_stage = [&](auto refill, auto last, int kt, int stage, int pstage, int nstage) {
+        constexpr bool REFILL = decltype(refill)::value, LAST = decltype(last)::value;
+        if (REFILL) {
 #if GEMM_TIMELINE
             const unsigned long long t0 = __builtin_amdgcn_s_memtime();
             wait_vmcnt<(ST - 3) * CNT>();
@@ -272,63 +271,66 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
             wait_vmcnt<(ST - 3) * CNT>();
             if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
 #endif
-        } else if (kt + 1 < KT) {
+        } else if (!LAST) {
             wait_groups(KT - 1 - (kt + 1));  // stages issued after kt+1 may stay in flight
             if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
-            if (!(GEMM_EXPERIMENT & 1) && kt + ST - 1 < KT) issue(has_last, pstage, kt + ST - 1);
         }
-        if (STEADY && GEMM_EXPERIMENT == 0) {
-            // Memory instructions are dealt out behind the MFMAs, one or two after each, and the compiler's
-            // scheduler is fenced at every step: a burst of LDS reads or global->LDS loads would hold the
-            // wave's issue port while the matrix pipe runs dry.
-            constexpr int NM = MBW * NBW, RD = MBW + NBW;
-            constexpr int V1 = (CNT + 1) / 2, V2 = CNT - V1;
-            auto half = [&]<int... M>(std::integer_sequence<int, M...>, auto second) {
-                constexpr bool SECOND = decltype(second)::value;
-                constexpr int TOT = RD + (SECOND ? V2 : V1);
-                auto step = [&](auto mi) {
-                    constexpr int m = decltype(mi)::value;
-                    const Frags<MBW, NBW>& use = SECOND ? f1 : f0;
+        // Memory instructions are dealt out between the MFMAs, and the compiler's scheduler is fenced at
+        // every step: a burst of LDS reads or global->LDS loads would hold the wave's issue port while the
+        // matrix pipe runs dry.  Fragment reads come first in a half, the global->LDS loads after them
+        // (spreading the loads among the reads, or keeping the last MFMAs free of both, measured slower).
+        constexpr int NM = MBW * NBW;
+        constexpr int V1 = REFILL && !(GEMM_EXPERIMENT & 1) ? (CNT + 1) / 2 : 0;
+        constexpr int V2 = REFILL && !(GEMM_EXPERIMENT & 1) ? CNT - V1 : 0;
+        auto half = [&]<int... M>(std::integer_sequence<int, M...>, auto second) {
+            constexpr bool SECOND = decltype(second)::value;
+            constexpr int RD = (GEMM_EXPERIMENT & 4) || (SECOND && LAST) ? 0 : MBW + NBW;
+            constexpr int V = SECOND ? V2 : V1;
+            constexpr int TOT = RD + V;
+            auto step = [&](auto mi) {
+                constexpr int m = decltype(mi)::value;
+                const Frags<MBW, NBW>& use = SECOND ? f1 : f0;
+                if (!(GEMM_EXPERIMENT & 2))
                     acc[m % MBW][m / MBW] = mfma32(use.a[m % MBW], use.b[m / MBW], acc[m % MBW][m / MBW]);
-                    __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (TOT > 0) {
 #pragma unroll
                     for (int t = TOT * m / NM; t < TOT * (m + 1) / NM; ++t) {
-                        if (t < RD) {
+                        if (t >= RD) {
+                            issue_one((SECOND ? V1 : 0) + t - RD, pstage, kt + ST - 1);
+                        } else {
                             if (SECOND) load_frag_one(f0, nstage, 0, t);
                             else load_frag_one(f1, stage, 1, t);
-                        } else {
-                            issue_one((SECOND ? V1 : 0) + t - RD, pstage, kt + ST - 1);
                         }
                     }
-                    __builtin_amdgcn_sched_barrier(0);
-                };
-                (step(std::integral_constant<int, M>{}), ...);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             };
-            half(std::make_integer_sequence<int, NM>{}, std::false_type{});
-            half(std::make_integer_sequence<int, NM>{}, std::true_type{});
-        } else {
-            if (STEADY && !(GEMM_EXPERIMENT & 1)) issue(has_last, pstage, kt + ST - 1);
-            if (!(GEMM_EXPERIMENT & 4) || kt == 0) load_frags(f1, stage, 1);
-            mma(f0, 0, NBW);
-            if (!(GEMM_EXPERIMENT & 4) && (STEADY || kt + 1 < KT)) load_frags(f0, nstage, 0);
-            mma(f1, 0, NBW);
-        }
+            (step(std::integral_constant<int, M>{}), ...);
+        };
+        half(std::make_integer_sequence<int, NM>{}, std::false_type{});
+        half(std::make_integer_sequence<int, NM>{}, std::true_type{});
         // f0 (next stage) has had the last MFMAs to arrive; waiting here keeps the next stage's reads out of
         // the wait and leaves no LDS read of this wave outstanding at the barrier.
         wait_lgkmcnt0();
     };
     int kt = 0;
-    for (; kt + 2 * ST - 1 <= KT; kt += ST) {  // every stage of the trip is steady
+    for (; kt + 2 * ST - 1 <= KT; kt += ST) {  // ST refilling stages per trip, slots as compile-time constants
         [&]<int... I>(std::integer_sequence<int, I...>) {
-            (do_stage(std::true_type{}, kt + I, I, (I + ST - 1) % ST, (I + 1) % ST), ...);
+            (do_stage(std::true_type{}, std::false_type{}, kt + I, I, (I + ST - 1) % ST, (I + 1) % ST), ...);
         }(std::make_integer_sequence<int, ST>{});
     }
-    for (int stage = 0; kt < KT; ++kt) {  // the last few stages, with the tail conditions
-        const int nstage = stage + 1 == ST ? 0 : stage + 1;
-        const int pstage = stage == 0 ? ST - 1 : stage - 1;
-        do_stage(std::false_type{}, kt, stage, pstage, nstage);
-        stage = nstage;
-    }
+    // The rest, with the slots as run-time values: the remaining refilling stages, the stages that only drain
+    // the ring, and the last one.  One loop per kind (a single loop that branches between them makes the
+    // compiler shuffle all accumulators at every merge).
+    int stage = 0;
+    auto next_slot = [&](int sl) { return sl + 1 == ST ? 0 : sl + 1; };
+    auto prev_slot = [&](int sl) { return sl == 0 ? ST - 1 : sl - 1; };
+    for (; kt + ST - 1 < KT; ++kt, stage = next_slot(stage))
+        do_stage(std::true_type{}, std::false_type{}, kt, stage, prev_slot(stage), next_slot(stage));
+    for (; kt + 1 < KT; ++kt, stage = next_slot(stage))
+        do_stage(std::false_type{}, std::false_type{}, kt, stage, prev_slot(stage), next_slot(stage));
+    if (kt < KT) do_stage(std::false_type{}, std::true_type{}, kt, stage, prev_slot(stage), next_slot(stage));
     };
     if constexpr (S::REM == 0) {
         k_loop(std::true_type{});
@@ -452,7 +454,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
                     const float4* rp = (const float4*)(a.rope + (size_t)m * 64 + i_lo);  // 8 (cos, sin) pairs
 #pragma unroll
                     for (int e2 = 0; e2 < 4; ++e2) {
-                        const float4 cs = rp[e2];  // (cos, sin) of indices 2*e2 and 2*e2 + 1
+                        const float4 cs = (GEMM_EXPERIMENT & 16) ? make_float4(1.f, 0.f, 1.f, 0.f) : rp[e2];  // (cos, sin) of indices 2*e2, 2*e2 + 1
                         // lo' = lo cos - hi sin ; hi' = hi cos + lo sin
                         v[2 * e2] = hi ? hv[2 * e2] * cs.x + lo[2 * e2] * cs.y : lo[2 * e2] * cs.x - hv[2 * e2] * cs.y;
                         v[2 * e2 + 1] = hi ? hv[2 * e2 + 1] * cs.z + lo[2 * e2 + 1] * cs.w
