@@ -102,6 +102,13 @@ __device__ inline void wait_tr_reads(u32x4& v) {
     asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(v) : "n"(N));
 }
 
+// max over the two 32-lane halves (lanes i and i ^ 32 get the same result) on the vector ALU: the swap
+// leaves {x.lo, x.lo} in one register and {x.hi, x.hi} in the other.
+__device__ inline float max_across_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 template <int QB>
 __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restrict__ q, u16* __restrict__ o, int n,
                                                             int d_model, int n_heads, int pos0, KvView kv, int layer,
@@ -313,7 +320,7 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
                 if (MASKED && key0 + acc_row(r, hh) > q_abs) sv[r] = -INFINITY;
                 mt = fmaxf(mt, sv[r]);
             }
-            mt = fmaxf(mt, __shfl_xor(mt, 32, 64)) * scale_log2e;  // the scale is positive
+            mt = max_across_halves(mt) * scale_log2e;  // the scale is positive
             // The reference maximum follows the running maximum lazily: it moves only when a tile exceeds it
             // by more than 2^8, so the accumulators are rescaled a few times per query instead of at every
             // tile whose maximum creeps up.  Probabilities then reach 2^8 at most, which bf16 and the fp32
