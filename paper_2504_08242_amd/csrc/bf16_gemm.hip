@@ -48,21 +48,24 @@
 namespace jup {
 namespace {
 
-constexpr int G_BM = 256, G_BK = 32;
+constexpr int G_BK = 32;
 
 constexpr int kLdsBudget = 160 * 1024;
 
-template <int NB, int WM, int WN>
+template <int BMB, int NB, int WM, int WN>
 struct Shape {
+    static constexpr int BM = 32 * BMB;             // rows of the tile: 256 for prefill-sized chunks, 128 or 64 for
+                                                    // short ones (a short chunk is bound by streaming the weights:
+                                                    // MFMAs on rows that do not exist would only slow that down)
     static constexpr int NBW = NB / WN;             // column blocks per wave
-    static constexpr int MBW = 8 / WM;              // row blocks per wave (the tile has 8)
+    static constexpr int MBW = BMB / WM;            // row blocks per wave
     static constexpr int WAVES = WM * WN;
-    static constexpr int ROWS = G_BM + 32 * NB;     // LDS rows per stage: A rows then W rows
+    static constexpr int ROWS = BM + 32 * NB;       // LDS rows per stage: A rows then W rows
     static constexpr int STAGE_BYTES = ROWS * 64;
     static constexpr int NL = ROWS / 16;            // 1 KB load units (16 rows) per stage, dealt round-robin to the waves
     static constexpr int LPW = (NL + WAVES - 1) / WAVES;  // load instructions per stage of the waves that have the most
     static constexpr int REM = NL % WAVES;          // waves below REM issue LPW loads, the others LPW - 1 (0: all LPW)
-    static_assert(NB % WN == 0 && 8 % WM == 0, "tile does not split evenly over the waves");
+    static_assert(NB % WN == 0 && BMB % WM == 0, "tile does not split evenly over the waves");
     // as many ring slots as LDS holds (at most 8: the in-flight count must fit the 6-bit vmcnt)
     static constexpr int STAGES = kLdsBudget / STAGE_BYTES > 8 ? 8 : kLdsBudget / STAGE_BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
@@ -118,9 +121,10 @@ struct Frags {
     bf16x8 b[NB];
 };
 
-template <int NB, int WM, int WN, int EPI>
+template <int BMB, int NB, int WM, int WN, int EPI>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
-    using S = Shape<NB, WM, WN>;
+    using S = Shape<BMB, NB, WM, WN>;
+    constexpr int G_BM = S::BM;
     constexpr int NBW = S::NBW, MBW = S::MBW;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -484,46 +488,53 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
 
 constexpr int kCUs = 256;
 
-template <int NB, int WM, int WN, int EPI>
-hipError_t launch(const GemmArgs& a, hipStream_t s) {
+int div_up(int x, int y) { return (x + y - 1) / y; }
+
+// Row blocks of the tile for a chunk of M tokens.
+int pick_row_blocks(int M) { return M > 128 ? 8 : M > 64 ? 4 : 2; }
+
+template <int BMB, int NB, int WM, int WN, int EPI>
+hipError_t launch(GemmArgs a, hipStream_t s) {
+    a.n_stride = 32 * NB;
+    a.n_tiles = div_up(a.N, a.n_stride);
+    a.m_tiles = div_up(a.M, 32 * BMB);
+    a.kt_per_split = a.K / G_BK / a.splits;
     const int grid = a.m_tiles * a.n_tiles * a.splits;
-    constexpr size_t lds_bytes = Shape<NB, WM, WN>::LDS_BYTES;
-    hipLaunchKernelGGL((gemm_bf16<NB, WM, WN, EPI>), dim3(grid), dim3(64 * WM * WN), lds_bytes, s, a);
+    constexpr size_t lds_bytes = Shape<BMB, NB, WM, WN>::LDS_BYTES;
+    hipLaunchKernelGGL((gemm_bf16<BMB, NB, WM, WN, EPI>), dim3(grid), dim3(64 * WM * WN), lds_bytes, s, a);
     return hipGetLastError();
 }
 
-template <int NB, int WM, int WN, int EPI>
+template <int BMB, int NB, int WM, int WN, int EPI>
 hipError_t configure_one() {
-    return hipFuncSetAttribute((const void*)gemm_bf16<NB, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               Shape<NB, WM, WN>::LDS_BYTES);
+    return hipFuncSetAttribute((const void*)gemm_bf16<BMB, NB, WM, WN, EPI>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, Shape<BMB, NB, WM, WN>::LDS_BYTES);
 }
-
-void finish_plan(GemmArgs& a) {
-    a.m_tiles = (a.M + G_BM - 1) / G_BM;
-    a.kt_per_split = a.K / G_BK / a.splits;
-}
-
-int div_up(int x, int y) { return (x + y - 1) / y; }
 
 }  // namespace
+
+// Instantiations: (row blocks, column blocks, wave grid) per epilogue.  256-row tiles for prefill-sized
+// chunks; 128- and 64-row tiles with narrow N for short chunks, where the grid must be wide enough to keep
+// every CU streaming weights.
+#define JUP_GEMM_SHAPES(X)                                                          \
+    X(8, 1, 4, 1, EPI_QKV) X(8, 2, 4, 1, EPI_QKV) X(8, 3, 4, 1, EPI_QKV)            \
+    X(4, 2, 4, 1, EPI_QKV) X(2, 2, 2, 2, EPI_QKV)                                   \
+    X(8, 2, 4, 1, EPI_SWIGLU) X(8, 3, 4, 1, EPI_SWIGLU) X(8, 4, 4, 2, EPI_SWIGLU) X(8, 6, 4, 2, EPI_SWIGLU) \
+    X(4, 4, 4, 1, EPI_SWIGLU) X(2, 4, 2, 2, EPI_SWIGLU)                             \
+    X(8, 4, 4, 2, EPI_PARTIAL) X(4, 4, 4, 1, EPI_PARTIAL) X(2, 4, 2, 2, EPI_PARTIAL)
 
 hipError_t gemm_configure() {
     hipError_t e = hipSuccess;
     auto acc = [&](hipError_t r) { if (e == hipSuccess) e = r; };
-    acc(configure_one<1, 4, 1, EPI_QKV>());
-    acc(configure_one<2, 4, 1, EPI_QKV>());
-    acc(configure_one<3, 4, 1, EPI_QKV>());
-    acc(configure_one<2, 4, 1, EPI_SWIGLU>());
-    acc(configure_one<3, 4, 1, EPI_SWIGLU>());
-    acc(configure_one<4, 4, 2, EPI_SWIGLU>());
-    acc(configure_one<6, 4, 2, EPI_SWIGLU>());
-    acc(configure_one<4, 4, 2, EPI_PARTIAL>());
+#define X(BMB, NB, WM, WN, EPI) acc(configure_one<BMB, NB, WM, WN, EPI>());
+    JUP_GEMM_SHAPES(X)
+#undef X
     return e;
 }
 
 // K splits for the projections whose N (= d_model) alone cannot fill the chip.
 int gemm_plan_splits(int M, int N, int K) {
-    const int m_tiles = (M + G_BM - 1) / G_BM;
+    const int m_tiles = div_up(M, 32 * pick_row_blocks(M));
     const int n_tiles = div_up(N, 128);
     int splits = 1;
     // double while it keeps the grid within one wave of workgroups and the K stages divide evenly
@@ -532,10 +543,10 @@ int gemm_plan_splits(int M, int N, int K) {
 }
 
 namespace {
-// Among the instantiated widths (in 32-column blocks), the one with the least work on the busiest CU:
-// rounds of workgroups x rows streamed per tile.  Ties go to the wider tile (fewer re-reads of A).
+// Among the instantiated widths (in 32-column blocks) of the 256-row tile, the one with the least work on the
+// busiest CU: rounds of workgroups x rows streamed per tile.  Ties go to the wider tile (fewer re-reads of A).
 int pick_blocks(int M, int N, const int* cands, int n_cands) {
-    const int m_tiles = (M + G_BM - 1) / G_BM;
+    const int m_tiles = div_up(M, 256);
     int best = cands[0];
     long best_cost = -1;
     for (int i = 0; i < n_cands; ++i) {
@@ -549,36 +560,36 @@ int pick_blocks(int M, int N, const int* cands, int n_cands) {
 }  // namespace
 
 hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s) {
+    a.splits = 1;
+    const int bmb = pick_row_blocks(a.M);
+    if (bmb == 2) return launch<2, 2, 2, 2, EPI_QKV>(a, s);
+    if (bmb == 4) return launch<4, 2, 4, 1, EPI_QKV>(a, s);
     static const int cands[] = {1, 2, 3};
     const int nb = pick_blocks(a.M, a.N, cands, 3);
-    a.splits = 1;
-    a.n_stride = 32 * nb;
-    a.n_tiles = div_up(a.N, a.n_stride);
-    finish_plan(a);
-    if (nb == 3) return launch<3, 4, 1, EPI_QKV>(a, s);
-    if (nb == 2) return launch<2, 4, 1, EPI_QKV>(a, s);
-    return launch<1, 4, 1, EPI_QKV>(a, s);
+    if (nb == 3) return launch<8, 3, 4, 1, EPI_QKV>(a, s);
+    if (nb == 2) return launch<8, 2, 4, 1, EPI_QKV>(a, s);
+    return launch<8, 1, 4, 1, EPI_QKV>(a, s);
 }
 
 hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
+    a.splits = 1;
+    const int bmb = pick_row_blocks(a.M);
+    if (bmb == 2) return launch<2, 4, 2, 2, EPI_SWIGLU>(a, s);
+    if (bmb == 4) return launch<4, 4, 4, 1, EPI_SWIGLU>(a, s);
     static const int cands[] = {2, 3, 4, 6};
     const int nb = pick_blocks(a.M, a.N, cands, 4);
-    a.splits = 1;
-    a.n_stride = 32 * nb;
-    a.n_tiles = div_up(a.N, a.n_stride);
-    finish_plan(a);
-    if (nb == 6) return launch<6, 4, 2, EPI_SWIGLU>(a, s);
-    if (nb == 4) return launch<4, 4, 2, EPI_SWIGLU>(a, s);
-    if (nb == 3) return launch<3, 4, 1, EPI_SWIGLU>(a, s);
-    return launch<2, 4, 1, EPI_SWIGLU>(a, s);
+    if (nb == 6) return launch<8, 6, 4, 2, EPI_SWIGLU>(a, s);
+    if (nb == 4) return launch<8, 4, 4, 2, EPI_SWIGLU>(a, s);
+    if (nb == 3) return launch<8, 3, 4, 1, EPI_SWIGLU>(a, s);
+    return launch<8, 2, 4, 1, EPI_SWIGLU>(a, s);
 }
 
 hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
     a.splits = gemm_plan_splits(a.M, a.N, a.K);
-    a.n_stride = 128;
-    a.n_tiles = div_up(a.N, 128);
-    finish_plan(a);
-    return launch<4, 4, 2, EPI_PARTIAL>(a, s);
+    const int bmb = pick_row_blocks(a.M);
+    if (bmb == 2) return launch<2, 4, 2, 2, EPI_PARTIAL>(a, s);
+    if (bmb == 4) return launch<4, 4, 4, 1, EPI_PARTIAL>(a, s);
+    return launch<8, 4, 4, 2, EPI_PARTIAL>(a, s);
 }
 
 }  // namespace jup
