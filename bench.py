@@ -1,14 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the stage kernel: prefill tokens/s of one pipeline stage on one MI355X.
 
-A step is one pass of the whole hot path over one prompt: the 8-layer Llama-2-7B-shaped bf16 stage
-processes a 2048-token prompt chunk by chunk (default 4 chunks of 512), every chunk attending to the
-cached prefix of the earlier ones.  Inputs are seeded synthetic tensors (hidden ~ N(0,1), weights
-~ N(0, 0.02^2)) already resident in HBM when the timed region starts.
+Default workload (the one the headline metric is quoted on): the 8-layer Llama-2-7B-shaped bf16 stage
+processes a 2048-token prompt chunk by chunk (4 chunks of 512), every chunk attending to the cached prefix
+of the earlier ones.  A step is one pass of the whole hot path over that prompt.  Inputs are seeded synthetic
+tensors (hidden ~ N(0,1), weights ~ N(0, 0.02^2)) already resident in HBM when the timed region starts.
 
 Prints ONE JSON line.  `roofline` is for the dominant kernel (the gate/up GEMM with the SwiGLU epilogue),
 timed in place with HIP events in a second pass over the same steps; `cpu_baseline` is the CPU oracle
 timed on this machine's host cores on a bounded sample of the same workload.
+
+--workload selects the other benchmark configurations (same JSON line; they are reporting runs, the
+default is the metric):
+  c3  (default) 7B-shaped stage, 2048-token prompt, --chunk 128|256|512|2048
+  c2  7B-shaped stage, 512-token prompt in 8 chunks of 64            (bound by streaming the weights)
+  c4  13B-shaped 10-layer stage, 1024-token prompt in 8 chunks of 128 (bound by streaming the weights)
+  c5  7B-shaped stage, 8 branches sharing a 512-token prefix, 64 private tokens each; a step is one
+      5-token chunk at position 576 on every branch                  (decode-sized, bound by the weights)
 """
 import argparse
 import json
@@ -21,10 +29,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
-# HBM bytes per launch of the dominant kernel at chunk 512, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
-# script scaled by a 256 MiB copy (--calibrate-copy); the summary of those runs lies under profiles/.
-GATE_UP_TRAFFIC_BYTES = {512: (106863.5 * 2.0 + 11046.2 * 1.0) * 1024}
-PROMPT_TOKENS = 2048
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+# HBM bytes per launch of the dominant kernel of the default workload (chunk 512), from rocprofv3 FETCH_SIZE /
+# WRITE_SIZE runs of this script scaled by a 256 MiB copy (--calibrate-copy); the summary of those runs lies
+# under profiles/.
+GATE_UP_TRAFFIC_BYTES = {("c3", 512): (106863.5 * 2.0 + 11046.2 * 1.0) * 1024}
 
 
 def flops_per_call(cfg, n, p):
@@ -35,12 +44,22 @@ def flops_per_call(cfg, n, p):
     return L * (gemm + attn)
 
 
+def bytes_per_call(cfg, n, p):
+    """Algorithmic HBM bytes of one chunk call: weights once, cached prefix read, new K/V written, hidden in/out."""
+    d, f, L = cfg["d_model"], cfg["d_ffn"], cfg["n_layers"]
+    weights = 2.0 * L * (4 * d * d + 3 * d * f)
+    kv_read = L * 2.0 * (p + n) * d * 2
+    kv_write = L * 2.0 * n * d * 2
+    return weights + kv_read + kv_write + 2.0 * n * d * 2
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--chunk", type=int, default=512, help="chunk size (128, 256, 512 or 2048)")
+    ap.add_argument("--workload", choices=("c2", "c3", "c4", "c5"), default="c3")
+    ap.add_argument("--chunk", type=int, default=512, help="chunk size of workload c3 (128, 256, 512 or 2048)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024,
                     help="the oracle is timed on the first this-many tokens of the prompt, fed in the same chunks")
@@ -50,8 +69,6 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build covers one GPU (one stage of the pipeline); run with --gpus 1")
-    if PROMPT_TOKENS % args.chunk:
-        sys.exit("bench.py: --chunk must divide 2048")
 
     import numpy as np
     import torch
@@ -60,26 +77,66 @@ def main():
     from paper_2504_08242_amd import synth_inputs as si
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
-    cfg = si.LLAMA7B_STAGE
-    chunk = args.chunk
-    n_chunks = PROMPT_TOKENS // chunk
-    seed = 30
+    wl = args.workload
+    if wl == "c3":
+        cfg, prompt, chunk, seed = si.LLAMA7B_STAGE, 2048, args.chunk, 30
+        if prompt % chunk:
+            sys.exit("bench.py: --chunk must divide 2048")
+        what = (f"configs[2]: 8-layer stage of Llama-2-7B shape (d 4096, 32 heads x 128, FFN 11008), "
+                f"{prompt}-token prompt as {prompt // chunk} chunks of {chunk}")
+    elif wl == "c2":
+        cfg, prompt, chunk, seed = si.LLAMA7B_STAGE, 512, 64, 20
+        what = "configs[1]: 8-layer stage of Llama-2-7B shape, 512-token prompt as 8 chunks of 64"
+    elif wl == "c4":
+        cfg, prompt, chunk, seed = si.LLAMA13B_STAGE, 1024, 128, 40
+        what = ("configs[3]: 10-layer stage of Llama-2-13B shape (d 5120, 40 heads x 128, FFN 13824), "
+                "1024-token prompt as 8 chunks of 128")
+    else:
+        cfg, prompt, chunk, seed = si.LLAMA7B_STAGE, 512, 128, 50
+        what = ("configs[4]: 8-layer stage of Llama-2-7B shape, 8 branches sharing a 512-token prefix with 64 "
+                "private tokens each; a step = one 5-token chunk at position 576 on every branch")
+    n_chunks = prompt // chunk
 
     t0 = time.time()
     layers_np = si.make_layers(cfg, seed, bf16=True, n_threads=16)
-    hidden_np = si.make_hidden(cfg, seed, PROMPT_TOKENS, bf16=True)
+    hidden_np = si.make_hidden(cfg, seed, prompt, bf16=True)
     stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers_np, "bf16"), chunk)
-    kv = jb.KvCache(cfg, "bf16", PROMPT_TOKENS)
+    kv = jb.KvCache(cfg, "bf16", prompt)
     hidden = torch.from_numpy(hidden_np).to("cuda:0", torch.bfloat16)
     out = torch.empty_like(hidden)
+
+    if wl == "c5":
+        # Untimed set-up: the shared prefix, then 64 private tokens per branch.
+        n_branches, n_private, n_step, p_step = 8, 64, 5, 576
+        for c in range(n_chunks):
+            stage.prefill_chunk(hidden[c * chunk:(c + 1) * chunk], c * chunk, kv)
+        branches = [kv.fork(prompt, prompt + n_private + n_step) for _ in range(n_branches)]
+
+        def dev(n, tag):
+            return torch.from_numpy(si.make_hidden(cfg, seed, n, tag=tag, bf16=True)).to("cuda:0", torch.bfloat16)
+
+        priv = [dev(n_private, 100 + b) for b in range(n_branches)]
+        step_in = [dev(n_step, 200 + b) for b in range(n_branches)]
+        step_out = [torch.empty_like(x) for x in step_in]
+        for b in range(n_branches):
+            stage.prefill_chunk(priv[b], prompt, branches[b])
+        calls = [(n_step, p_step)] * n_branches
+        tokens_per_step = n_branches * n_step
+
+        def step():
+            for b in range(n_branches):  # pos_offset below the length = drop what the last step appended
+                stage.prefill_chunk(step_in[b], p_step, branches[b], hidden_out=step_out[b])
+    else:
+        calls = [(chunk, c * chunk) for c in range(n_chunks)]
+        tokens_per_step = prompt
+
+        def step():
+            kv.reset()
+            for c in range(n_chunks):
+                lo = c * chunk
+                stage.prefill_chunk(hidden[lo:lo + chunk], lo, kv, hidden_out=out[lo:lo + chunk])
     torch.cuda.synchronize()
     print(f"[bench] inputs ready in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
-
-    def step():
-        kv.reset()
-        for c in range(n_chunks):
-            lo = c * chunk
-            stage.prefill_chunk(hidden[lo:lo + chunk], lo, kv, hidden_out=out[lo:lo + chunk])
 
     if args.calibrate_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda:0")
@@ -98,14 +155,16 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
-    tokens_per_s = PROMPT_TOKENS * args.steps / elapsed
-    step_flops = sum(flops_per_call(cfg, chunk, c * chunk) for c in range(n_chunks))
+    tokens_per_s = tokens_per_step * args.steps / elapsed
+    step_flops = sum(flops_per_call(cfg, n, p) for n, p in calls)
+    step_bytes = sum(bytes_per_call(cfg, n, p) for n, p in calls)
     step_tflops = step_flops / (ms_per_step * 1e-3) / 1e12
+    step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # Second pass: the same steps with an event pair around every launch of the dominant kernel.
+    # Second pass: the same steps with an event pair around every launch of one kernel class at a time.
     per_kernel = {}
     for name in ("gemm_gate_up", "gemm_qkv", "gemm_down", "gemm_o", "attention", "rmsnorm"):
-        stage.trace(jb.KERNEL_IDS[name], max_launches=4 * cfg["n_layers"] * n_chunks * max(args.steps, 1))
+        stage.trace(jb.KERNEL_IDS[name], max_launches=4 * cfg["n_layers"] * len(calls) * max(args.steps, 1))
         reps = args.steps if name == "gemm_gate_up" else min(args.steps, 3)
         for _ in range(reps):
             step()
@@ -115,19 +174,28 @@ def main():
                             "dropped": dropped}
     stage.trace(-1)
     dom = per_kernel["gemm_gate_up"]
-    dom_flops = 2.0 * chunk * (2 * cfg["d_ffn"]) * cfg["d_model"]  # one launch: [chunk, d] x [2f, d]^T
-    achieved = dom_flops / (dom["avg_us"] * 1e-6) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_nt<gate_up+swiglu>", "achieved": round(achieved, 1),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "avg_launch_us": round(dom["avg_us"], 2), "flop_per_launch": dom_flops, "traffic": GATE_UP_TRAFFIC_BYTES.get(chunk),
-                "traffic_unit": "bytes per launch (offline rocprofv3 counters)",
-                "algorithmic_bytes": 2.0 * (2 * cfg["d_ffn"] * cfg["d_model"] + chunk * cfg["d_model"]
-                                            + chunk * cfg["d_ffn"])}
+    n_call = calls[0][0]
+    d, f = cfg["d_model"], cfg["d_ffn"]
+    dom_flops = 2.0 * n_call * (2 * f) * d  # one launch: [n, d] x [2f, d]^T
+    dom_bytes = 2.0 * (2 * f * d + n_call * d + n_call * f)  # weights + activations in + activations out
+    dom_s = dom["avg_us"] * 1e-6
+    # which roof the dominant kernel sits under: the ridge of the chip is peak flop/s over peak byte/s
+    if dom_flops / dom_bytes >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        achieved = dom_flops / dom_s / 1e12
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16<gate_up+swiglu>", "achieved": round(achieved, 1),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4)}
+    else:
+        achieved = dom_bytes / dom_s / 1e9
+        roofline = {"bound": "hbm", "kernel": "gemm_bf16<gate_up+swiglu>", "achieved": round(achieved, 1),
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4)}
+    roofline.update({"avg_launch_us": round(dom["avg_us"], 2), "flop_per_launch": dom_flops,
+                     "algorithmic_bytes": dom_bytes, "traffic": GATE_UP_TRAFFIC_BYTES.get((wl, chunk)),
+                     "traffic_unit": "bytes per launch (offline rocprofv3 counters)"})
 
     cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and wl != "c5":
         import oracle
-        ns = min(max(args.cpu_sample_tokens, 1), PROMPT_TOKENS)
+        ns = min(max(args.cpu_sample_tokens, 1), prompt)
         ora = oracle.OracleStage(cfg, layers_np, ns)
         ref = np.empty((ns, cfg["d_model"]), np.float32)
         t0 = time.perf_counter()
@@ -138,7 +206,7 @@ def main():
         got = out[:ns].float().cpu().numpy().astype(np.float64)
         cpu_baseline = {"value": round(ns / dt, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
                         "kind": "oracle", "seconds": round(dt, 2),
-                        "sample": f"first {ns} of the {PROMPT_TOKENS} prompt tokens in chunks of {chunk}, all "
+                        "sample": f"first {ns} of the {prompt} prompt tokens in chunks of {chunk}, all "
                                   f"{cfg['n_layers']} layers",
                         "gpu_vs_oracle_rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref.astype(np.float64)))}
 
@@ -155,11 +223,11 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"configs[2]: 8-layer stage of Llama-2-7B shape (d 4096, 32 heads x 128, FFN 11008), "
-                               f"{PROMPT_TOKENS}-token prompt as {n_chunks} chunks of {chunk}",
-                   "prompt_tokens": PROMPT_TOKENS, "chunk_tokens": chunk},
+        "config": {"workload": what, "tokens_per_step": tokens_per_step, "chunk_tokens": n_call},
         "tflops": round(step_tflops, 1),
         "frac_of_bf16_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
+        "algorithmic_gb_per_s": round(step_gbs, 1),
+        "frac_of_hbm_peak": round(step_gbs / PEAK_HBM_GBS, 4),
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in per_kernel.items()},
