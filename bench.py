@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel of the default workload (chunk 512), from rocprofv3 FETCH_SIZE /
 # WRITE_SIZE runs of this script scaled by a 256 MiB copy (--calibrate-copy); the summary of those runs lies
 # under profiles/.
-GATE_UP_TRAFFIC_BYTES = {("c3", 512): (106863.5 * 2.0 + 11046.2 * 1.0) * 1024}
+GATE_UP_TRAFFIC_BYTES = {("c3", 512): (106897.5 * 2.0 + 11050.6 * 1.0) * 1024}
 
 
 def flops_per_call(cfg, n, p):
