@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", choices=("c2", "c3", "c4", "c5"), default="c3")
     ap.add_argument("--chunk", type=int, default=512, help="chunk size of workload c3 (128, 256, 512 or 2048)")
+    ap.add_argument("--batched", action="store_true",
+                    help="workload c5: all 8 branches in one jup_stage_prefill_branches call per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024,
                     help="the oracle is timed on the first this-many tokens of the prompt, fed in the same chunks")
@@ -122,10 +124,17 @@ def main():
             stage.prefill_chunk(priv[b], prompt, branches[b])
         calls = [(n_step, p_step)] * n_branches
         tokens_per_step = n_branches * n_step
+        if args.batched:
+            what += "; all branches in one batched call (the weights are streamed once per step, not once per branch)"
+            all_in = torch.cat(step_in)
+            all_out = torch.empty_like(all_in)
 
-        def step():
-            for b in range(n_branches):  # pos_offset below the length = drop what the last step appended
-                stage.prefill_chunk(step_in[b], p_step, branches[b], hidden_out=step_out[b])
+            def step():  # pos_offset below the length = drop what the last step appended
+                stage.prefill_branches(all_in, n_step, [p_step] * n_branches, branches, hidden_out=all_out)
+        else:
+            def step():
+                for b in range(n_branches):
+                    stage.prefill_chunk(step_in[b], p_step, branches[b], hidden_out=step_out[b])
     else:
         calls = [(chunk, c * chunk) for c in range(n_chunks)]
         tokens_per_step = prompt
@@ -158,6 +167,9 @@ def main():
     tokens_per_s = tokens_per_step * args.steps / elapsed
     step_flops = sum(flops_per_call(cfg, n, p) for n, p in calls)
     step_bytes = sum(bytes_per_call(cfg, n, p) for n, p in calls)
+    if wl == "c5" and args.batched:  # one pass over the weights serves every branch
+        d_, f_, L_ = cfg["d_model"], cfg["d_ffn"], cfg["n_layers"]
+        step_bytes -= (len(calls) - 1) * 2.0 * L_ * (4 * d_ * d_ + 3 * d_ * f_)
     step_tflops = step_flops / (ms_per_step * 1e-3) / 1e12
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
@@ -174,7 +186,7 @@ def main():
                             "dropped": dropped}
     stage.trace(-1)
     dom = per_kernel["gemm_gate_up"]
-    n_call = calls[0][0]
+    n_call = calls[0][0] * (len(calls) if wl == "c5" and args.batched else 1)  # rows of one GEMM launch
     d, f = cfg["d_model"], cfg["d_ffn"]
     dom_flops = 2.0 * n_call * (2 * f) * d  # one launch: [n, d] x [2f, d]^T
     dom_bytes = 2.0 * (2 * f * d + n_call * d + n_call * f)  # weights + activations in + activations out

@@ -202,6 +202,32 @@ JUP_API jup_status_t jup_kv_destroy(jup_kv_t *kv);
 JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hidden_in, int32_t n_tokens,
                                      int32_t pos_offset, jup_kv_t *kv, void *hidden_out, void *stream);
 
+/*
+ * The same stage forward for several branches at once.  In outline-based pipeline parallel decoding the
+ * branches of one request are independent sub-sequences over a shared prompt cache (Sec. V-B, Fig. 11),
+ * each advanced by a few tokens per step (Sec. V-A: one token plus speculative candidates).  The paper
+ * staggers the branches over the stages of the pipeline; inside ONE stage this call goes further and pushes
+ * the chunks of all branches through the layers together, so that the stage's weights, whose streaming from
+ * HBM bounds a decode-sized chunk, are read once per step instead of once per branch.  This batching is an
+ * optimisation of this library, not a mechanism of the paper.
+ *   n_branches   1 .. JUP_MAX_BRANCHES
+ *   hidden_in    [n_branches * n_tokens, d_model], stage dtype: rows b*n_tokens .. (b+1)*n_tokens-1 are
+ *                the chunk of branch b
+ *   n_tokens     tokens per branch (the same for all); n_branches * n_tokens <= the stage's max_chunk_tokens
+ *   pos_offsets  HOST array [n_branches]: pos_offset of every branch's chunk (rules of jup_kv_check_append)
+ *   kvs          HOST array [n_branches] of caches, all different, none the parent of another in the list
+ *   hidden_out   [n_branches * n_tokens, d_model]; may be the same buffer as hidden_in
+ * The result equals n_branches calls of jup_stage_prefill_chunk(), one per branch, bit for bit in the
+ * JUP_BF16 path's caches and outputs (rows do not interact outside attention, and every row meets the same
+ * arithmetic in the same order either way).  On success every cache b has length pos_offsets[b] + n_tokens.
+ * Errors: as jup_stage_prefill_chunk(); all branches are validated before anything is enqueued, and on error
+ * no cache changes.
+ */
+#define JUP_MAX_BRANCHES 16
+JUP_API jup_status_t jup_stage_prefill_branches(jup_stage_t *stage, int32_t n_branches, const void *hidden_in,
+                                        int32_t n_tokens, const int32_t *pos_offsets, jup_kv_t *const *kvs,
+                                        void *hidden_out, void *stream);
+
 /* ---- per-kernel timing (benchmarks) ----------------------------------------------------------- */
 
 /*

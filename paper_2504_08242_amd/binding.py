@@ -64,6 +64,7 @@ def lib():
             "jup_kv_check_append": (i32, [vp, i32, i32]),
             "jup_kv_destroy": (i32, [vp]),
             "jup_stage_prefill_chunk": (i32, [vp, vp, i32, i32, vp, vp, vp]),
+            "jup_stage_prefill_branches": (i32, [vp, i32, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), vp, vp]),
             "jup_stage_trace": (i32, [vp, i32, i32]),
             "jup_stage_trace_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32),
                                            ctypes.POINTER(i32)]),
@@ -204,6 +205,21 @@ class Stage:
         _check(lib().jup_stage_prefill_chunk(self.handle, ctypes.c_void_p(hidden_in.data_ptr()), n, int(pos_offset),
                                              kv.handle, ctypes.c_void_p(hidden_out.data_ptr()),
                                              _stream_handle(stream)))
+        return hidden_out
+
+    def prefill_branches(self, hidden_in, n_tokens, pos_offsets, kvs, hidden_out=None, stream=None):
+        """hidden_in: [len(kvs) * n_tokens, d_model]; rows b*n_tokens.. belong to branch b. Returns hidden_out."""
+        import torch
+        nb = len(kvs)
+        assert len(pos_offsets) == nb and hidden_in.shape[0] == nb * n_tokens
+        assert hidden_in.is_contiguous() and hidden_in.dtype == _torch_dtype(self.dtype)
+        if hidden_out is None:
+            hidden_out = torch.empty_like(hidden_in)
+        pos = (ctypes.c_int32 * nb)(*[int(p) for p in pos_offsets])
+        handles = (ctypes.c_void_p * nb)(*[k.handle for k in kvs])
+        _check(lib().jup_stage_prefill_branches(self.handle, nb, ctypes.c_void_p(hidden_in.data_ptr()), int(n_tokens),
+                                                pos, handles, ctypes.c_void_p(hidden_out.data_ptr()),
+                                                _stream_handle(stream)))
         return hidden_out
 
     def trace(self, kernel_id, max_launches=4096):

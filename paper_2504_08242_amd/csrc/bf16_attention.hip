@@ -111,16 +111,26 @@ __device__ inline float max_across_halves(float x) {
 
 template <int QB>
 __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restrict__ q, u16* __restrict__ o, int n,
-                                                            int d_model, int n_heads, int pos0, KvView kv, int layer,
-                                                            float scale_log2e) {
+                                                            int d_model, int n_heads, int pos0_arg, KvView kv_arg,
+                                                            int layer, float scale_log2e,
+                                                            const BranchTable* __restrict__ branches) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31, hh = lane >> 5;
     // Workgroup b runs on XCD b % 8: heads vary fastest so that every query block of a head reads that
     // head's keys and values through the same L2; the longest query blocks (most visible keys) start first.
+    // A batched-branch launch runs the grid of one chunk once per branch: rows [branch * n, +n) of q and o,
+    // that branch's cache and starting position.
     const int head = blockIdx.x % n_heads;
-    const int q0 = ((int)(gridDim.x / n_heads) - 1 - (int)(blockIdx.x / n_heads)) * (QB * 32);
+    const int q_blocks = (n + QB * 32 - 1) / (QB * 32);
+    const int bq = blockIdx.x / n_heads;
+    const int branch = bq / q_blocks;  // 0 without a branch table
+    const int q0 = (q_blocks - 1 - bq % q_blocks) * (QB * 32);
+    const int row0 = branch * n;       // first row of this chunk in q and o
+    const int pos0 = branches ? branches->pos0[branch] : pos0_arg;
+    const KvView kv = branches ? branches->kv[branch] : kv_arg;
+    q += (size_t)row0 * d_model;
     const int q_last = min(q0 + QB * 32, n) - 1;  // last real query of this block
     const int n_keys = pos0 + q_last + 1;         // keys 0 .. n_keys-1 are visible to the block
     const int n_tiles = (n_keys + kKT - 1) / kKT;
@@ -511,7 +521,7 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
         u32x4 out;
         out[0] = pack_bf16x2(a.x, a.y); out[1] = pack_bf16x2(a.z, a.w);
         out[2] = pack_bf16x2(b.x, b.y); out[3] = pack_bf16x2(b.z, b.w);
-        *(u32x4*)(o + tiled_offset(qrow, head * 16 + ch, d_model >> 5)) = out;
+        *(u32x4*)(o + tiled_offset(row0 + qrow, head * 16 + ch, d_model >> 5)) = out;
     }
 #if ATT_TIMELINE
     __syncthreads();
@@ -538,10 +548,22 @@ void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_head
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
     if (n <= 32)
         hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3((n + 31) / 32 * n_heads), dim3(256), kAttLds, s, q, o, n,
-                           d_model, n_heads, pos0, kv, layer, scale_log2e);
+                           d_model, n_heads, pos0, kv, layer, scale_log2e, (const BranchTable*)nullptr);
     else
         hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(256), kAttLds, s, q, o, n,
-                           d_model, n_heads, pos0, kv, layer, scale_log2e);
+                           d_model, n_heads, pos0, kv, layer, scale_log2e, (const BranchTable*)nullptr);
+}
+
+void launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_model, int n_heads,
+                             const BranchTable* branches, int layer, hipStream_t s) {
+    const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
+    const KvView none{};
+    if (n <= 32)
+        hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3(n_branches * ((n + 31) / 32) * n_heads), dim3(256), kAttLds, s,
+                           q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches);
+    else
+        hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3(n_branches * ((n + 63) / 64) * n_heads), dim3(256), kAttLds, s,
+                           q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches);
 }
 
 }  // namespace jup

@@ -71,6 +71,7 @@ struct GemmArgs {
     const float2* rope;  // [M, 64] (cos, sin)
     KvView kv;
     int layer, n_heads, d_model, pos0;
+    const BranchTable* branches;  // non-null: row m belongs to branch m / n_tok (kv and pos0 above are unused)
     // EPI_PARTIAL
     float* partial;  // [splits][M][N] fp32
     // EPI_SWIGLU
@@ -93,12 +94,17 @@ hipError_t gemm_configure();  // raises the dynamic-LDS limit of every instantia
 hipError_t attention_configure();  // raises the dynamic-LDS limit (once per process)
 void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
                             int layer, hipStream_t s);
+// n_branches chunks of n tokens each (rows b*n .. b*n+n-1 of q and o), every one against its own cache
+void launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_model, int n_heads,
+                             const BranchTable* branches, int layer, hipStream_t s);
 
 // ---- packing, rotary table, reduce + norm (bf16_misc.hip) -------------------------------------------
 void launch_pack_qkv(u16* dst, const u16* wq, const u16* wk, const u16* wv, int d, hipStream_t s);
 void launch_pack_gate_up(u16* dst, const u16* wg, const u16* wu, int d, int f, hipStream_t s);
 void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s);
 void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s);
+void launch_rope_table_branches(float2* tab, int n_rows, const BranchTable* branches, float theta, hipStream_t s);
+void launch_write_branch_table(const BranchTable& host_table, BranchTable* dst, hipStream_t s);
 // x32 <- (hidden_in ? hidden_in : x32) + sum_s partial[s];  xn <- rmsnorm(x32) * g (if g), tiled layout;
 // out <- bf16(x32) (if out), row-major
 void launch_reduce_norm(float* x32, const u16* hidden_in, const float* partial, int splits, size_t split_stride,

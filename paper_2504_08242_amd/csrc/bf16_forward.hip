@@ -31,8 +31,13 @@ hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* lay
     return hipGetLastError();
 }
 
+// bt == nullptr: one chunk of n tokens at position pos of cache kv.
+// bt != nullptr: bt->n_branches chunks of bt->n_tok tokens each, n = their total number of rows; the rows of
+// branch b are appended to and attend over cache bt->kv[b] from position bt->pos0[b] (pos and kv are unused).
+// Everything that is not attention or cache traffic sees one [n, d] activation matrix either way, so the
+// stage's weights are streamed once for all branches.
 hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int pos, const KvView& kv,
-                        void* hidden_out, hipStream_t s) {
+                        void* hidden_out, hipStream_t s, const BranchTable* bt) {
     const jup_stage_config_t& c = st.cfg;
     const int d = c.d_model, f = c.d_ffn, H = c.n_heads;
     char* ws = (char*)st.workspace;
@@ -46,7 +51,14 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
     const size_t split_stride = (size_t)n * d;
 
     if (c.n_layers == 0) return hipMemcpyAsync(hidden_out, hidden_in, (size_t)n * d * 2, hipMemcpyDeviceToDevice, s);
-    launch_rope_table(rope, n, pos, c.rope_theta, s);
+    const BranchTable* bt_dev = nullptr;
+    if (bt) {
+        bt_dev = (const BranchTable*)(ws + st.wl.branches);
+        launch_write_branch_table(*bt, (BranchTable*)(ws + st.wl.branches), s);
+        launch_rope_table_branches(rope, n, bt_dev, c.rope_theta, s);
+    } else {
+        launch_rope_table(rope, n, pos, c.rope_theta, s);
+    }
 
     const int splits_o = gemm_plan_splits(n, d, d), splits_down = gemm_plan_splits(n, d, f);
     hipError_t e = hipSuccess;
@@ -67,11 +79,13 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
             GemmArgs a{};
             a.A = xn; a.W = (const u16*)(wb + st.pl.wqkv); a.M = n; a.N = 3 * d; a.K = d;
             a.q_out = q; a.rope = rope; a.kv = kv; a.layer = l; a.n_heads = H; a.d_model = d; a.pos0 = pos;
+            a.branches = bt_dev;
             e = launch_gemm_qkv(a, s);
         }
         {
             TraceScope ts(st, JUP_K_ATTENTION, s);
-            launch_chunk_attention(q, o, n, d, H, pos, kv, l, s);
+            if (bt) launch_branch_attention(q, o, bt->n_tok, bt->n_branches, d, H, bt_dev, l, s);
+            else launch_chunk_attention(q, o, n, d, H, pos, kv, l, s);
         }
         {
             TraceScope ts(st, JUP_K_GEMM_O, s);

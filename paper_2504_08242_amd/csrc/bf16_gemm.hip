@@ -431,19 +431,30 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
             const int hi = sub >> 1, i_lo = 16 * j + 8 * (sub & 1);
             u16* dst;
             size_t stride;
+            const int in_row = which == 2 ? 32 * j + 8 * sub : i_lo + 64 * hi;  // first of the lane's 8 columns
             if (which == 0) {
-                dst = a.q_out + head * 128 + i_lo + 64 * hi;
+                dst = a.q_out + head * 128 + in_row;
                 stride = a.d_model;
-            } else {
-                dst = kv_slot_bf16(a.kv, a.layer, which - 1, head, a.n_heads, a.pos0) +
-                      (which == 2 ? 32 * j + 8 * sub : i_lo + 64 * hi);
+            } else if (!a.branches) {
+                dst = kv_slot_bf16(a.kv, a.layer, which - 1, head, a.n_heads, a.pos0) + in_row;
                 stride = 128;
+            } else {
+                dst = nullptr;  // per row below
+                stride = 0;
             }
 #pragma unroll
             for (int p = 0; p < WROWS / 16; ++p) {
                 const int rl = p * 16 + rl0;
                 const int m = m0 + wm * WROWS + rl;
                 if (m >= a.M) continue;
+                u16* out_ptr;
+                if (which != 0 && a.branches) {  // row m is token t of branch b: that branch's cache and position
+                    const int b = m / a.branches->n_tok, t = m - b * a.branches->n_tok;
+                    out_ptr = kv_slot_bf16(a.branches->kv[b], a.layer, which - 1, head, a.n_heads,
+                                           a.branches->pos0[b] + t) + in_row;
+                } else {
+                    out_ptr = dst + (size_t)m * stride;
+                }
                 const float* sp = strip + rl * SW + nb * 32;
                 float v[8];
                 if (which == 2) {
@@ -468,7 +479,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
                 u32x4 out;
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2) out[e2] = pack_bf16x2(v[2 * e2], v[2 * e2 + 1]);
-                *(u32x4*)(dst + (size_t)m * stride) = out;
+                *(u32x4*)out_ptr = out;
             }
         }
     }

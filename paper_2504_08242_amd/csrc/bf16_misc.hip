@@ -46,6 +46,23 @@ __global__ void rope_table(float2* __restrict__ tab, int n, int pos0, float thet
     tab[gid] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
+// Batched-branch call: row r is token r % n_tok of branch r / n_tok.
+__global__ void rope_table_branches(float2* __restrict__ tab, int n_rows, const BranchTable* __restrict__ bt,
+                                    float theta) {
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= n_rows * 64) return;
+    const int i = gid & 63, r = gid >> 6;
+    const int b = r / bt->n_tok, t = r - b * bt->n_tok;
+    const double ang = (double)(bt->pos0[b] + t) * pow((double)theta, -(double)i / 64.0);
+    tab[gid] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+// The table of a batched-branch call travels as a kernel argument and is parked in the workspace, where the
+// kernels of the call find it (no host-to-device copy on the hot path).
+__global__ void write_branch_table(const BranchTable t, BranchTable* __restrict__ dst) {
+    if (threadIdx.x == 0) *dst = t;
+}
+
 // One block per row, IT float4 per thread (the row stays in registers between the two passes).  A row has
 // few bytes and there are few rows, so the block is wide (d/8 threads when that is a whole number of waves):
 // every load of a thread is independent and enough of them must be in flight per CU to cover HBM latency.
@@ -131,6 +148,13 @@ void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s)
 }
 void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s) {
     hipLaunchKernelGGL(rope_table, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, theta);
+}
+void launch_rope_table_branches(float2* tab, int n_rows, const BranchTable* branches, float theta, hipStream_t s) {
+    hipLaunchKernelGGL(rope_table_branches, dim3((n_rows * 64 + 255) / 256), dim3(256), 0, s, tab, n_rows, branches,
+                       theta);
+}
+void launch_write_branch_table(const BranchTable& host_table, BranchTable* dst, hipStream_t s) {
+    hipLaunchKernelGGL(write_branch_table, dim3(1), dim3(64), 0, s, host_table, dst);
 }
 void launch_reduce_norm(float* x32, const u16* hidden_in, const float* partial, int splits, size_t split_stride,
                         const u16* g, u16* xn, u16* out, int n, int d, float eps, hipStream_t s) {

@@ -85,6 +85,7 @@ WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T) {
     w.act = off;  off += align_up(t * f * e);
     w.rope = off; off += align_up(t * (size_t)(c.head_dim / 2) * 8);
     w.partial = off; off += f32 ? 0 : align_up(8 * t * d * 4);
+    w.branches = off; off += f32 ? 0 : align_up(sizeof(BranchTable));
     w.total = off;
     return w;
 }
@@ -358,6 +359,21 @@ jup_status_t jup_kv_destroy(jup_kv_t* kv) {
 }
 
 // ---- the hot path -----------------------------------------------------------------------------
+}  // extern "C"
+
+namespace {
+jup::KvView view_of(const jup_kv_t* kv) {
+    jup::KvView view{};
+    view.own = kv->buf;
+    view.parent = kv->parent ? kv->parent->buf : nullptr;
+    view.n_shared = kv->n_shared;
+    view.own_cap = kv->max_positions - kv->n_shared;
+    view.parent_cap = kv->parent ? kv->parent->max_positions : 0;
+    return view;
+}
+}  // namespace
+
+extern "C" {
 
 jup_status_t jup_stage_prefill_chunk(jup_stage_t* stage, const void* hidden_in, int32_t n_tokens,
                                      int32_t pos_offset, jup_kv_t* kv, void* hidden_out, void* stream) {
@@ -384,12 +400,7 @@ jup_status_t jup_stage_prefill_chunk(jup_stage_t* stage, const void* hidden_in, 
     if (!hidden_in || !hidden_out)
         return fail(JUP_EINVAL, "jup_stage_prefill_chunk: hidden_in and hidden_out must not be NULL");
 
-    jup::KvView view{};
-    view.own = kv->buf;
-    view.parent = kv->parent ? kv->parent->buf : nullptr;
-    view.n_shared = kv->n_shared;
-    view.own_cap = kv->max_positions - kv->n_shared;
-    view.parent_cap = kv->parent ? kv->parent->max_positions : 0;
+    const jup::KvView view = view_of(kv);
 
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
@@ -399,6 +410,72 @@ jup_status_t jup_stage_prefill_chunk(jup_stage_t* stage, const void* hidden_in, 
         e = jup::bf16_forward(*stage, hidden_in, n_tokens, pos_offset, view, hidden_out, s);
     if (e != hipSuccess) return fail(JUP_EDEVICE, "jup_stage_prefill_chunk: %s", hipGetErrorString(e));
     kv->len = pos_offset + n_tokens;
+    return JUP_OK;
+}
+
+jup_status_t jup_stage_prefill_branches(jup_stage_t* stage, int32_t n_branches, const void* hidden_in,
+                                        int32_t n_tokens, const int32_t* pos_offsets, jup_kv_t* const* kvs,
+                                        void* hidden_out, void* stream) {
+    const char* me = "jup_stage_prefill_branches";
+    if (!stage) return fail(JUP_EINVAL, "%s: stage is NULL", me);
+    if (n_branches < 1 || n_branches > JUP_MAX_BRANCHES)
+        return fail(JUP_EINVAL, "%s: n_branches=%d is outside 1..%d", me, n_branches, JUP_MAX_BRANCHES);
+    if (!pos_offsets || !kvs) return fail(JUP_EINVAL, "%s: pos_offsets and kvs must not be NULL", me);
+    if (n_tokens < 0) return fail(JUP_EINVAL, "%s: n_tokens=%d is negative", me, n_tokens);
+    for (int b = 0; b < n_branches; ++b) {  // the list itself first, then every branch's positions
+        jup_kv_t* kv = kvs[b];
+        if (!kv) return fail(JUP_EINVAL, "%s: kvs[%d] is NULL", me, b);
+        if (!same_shape(stage->cfg, kv->cfg))
+            return fail(JUP_EINVAL, "%s: kvs[%d] was made for another configuration", me, b);
+        for (int a = 0; a < b; ++a) {
+            if (kvs[a] == kv) return fail(JUP_EINVAL, "%s: kvs[%d] and kvs[%d] are the same cache", me, a, b);
+            if (kvs[a]->parent == kv || kv->parent == kvs[a])
+                return fail(JUP_EINVAL, "%s: kvs[%d] and kvs[%d] are parent and fork: one call would write positions "
+                            "the other reads", me, a, b);
+        }
+    }
+    for (int b = 0; b < n_branches; ++b) {
+        jup_kv_t* kv = kvs[b];
+        jup_status_t rc = jup_kv_check_append(kv, n_tokens, pos_offsets[b]);
+        if (rc != JUP_OK) {
+            char tmp[400];
+            snprintf(tmp, sizeof(tmp), "%s", g_err);
+            return fail(rc, "%s: branch %d: %s", me, b, tmp);
+        }
+        if (kv->parent && kv->parent->len < kv->n_shared)
+            return fail(JUP_EPOS, "%s: branch %d: the parent cache holds %d positions, fewer than the %d shared", me, b,
+                        kv->parent->len, kv->n_shared);
+    }
+    const long rows = (long)n_branches * n_tokens;
+    if (rows > stage->max_chunk_tokens)
+        return fail(JUP_ECAP, "%s: %d branches x %d tokens exceed the stage's max_chunk_tokens=%d", me, n_branches,
+                    n_tokens, stage->max_chunk_tokens);
+    if (n_tokens == 0) {
+        for (int b = 0; b < n_branches; ++b) kvs[b]->len = pos_offsets[b];
+        return JUP_OK;
+    }
+    if (!hidden_in || !hidden_out) return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must not be NULL", me);
+
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    if (stage->cfg.dtype == JUP_F32) {
+        // check mode: one branch after the other (it exists to be compared with, not to be fast)
+        const size_t row_elems = (size_t)n_tokens * stage->cfg.d_model;
+        for (int b = 0; b < n_branches && e == hipSuccess; ++b)
+            e = jup::f32_forward(*stage, (const float*)hidden_in + b * row_elems, n_tokens, pos_offsets[b],
+                                 view_of(kvs[b]), (float*)hidden_out + b * row_elems, s);
+    } else {
+        jup::BranchTable bt{};
+        bt.n_branches = n_branches;
+        bt.n_tok = n_tokens;
+        for (int b = 0; b < n_branches; ++b) {
+            bt.pos0[b] = pos_offsets[b];
+            bt.kv[b] = view_of(kvs[b]);
+        }
+        e = jup::bf16_forward(*stage, hidden_in, (int)rows, 0, jup::KvView{}, hidden_out, s, &bt);
+    }
+    if (e != hipSuccess) return fail(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
+    for (int b = 0; b < n_branches; ++b) kvs[b]->len = pos_offsets[b] + n_tokens;
     return JUP_OK;
 }
 

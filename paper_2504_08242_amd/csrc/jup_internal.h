@@ -36,6 +36,7 @@ struct WorkspaceLayout {
     size_t act;   // [T, f] silu(gate) * up
     size_t rope;  // [T, head_dim/2] float2 (cos, sin) of the chunk's positions
     size_t partial;  // bf16 only: [8][T, d] fp32 K-split partial sums of the O / down projections
+    size_t branches; // bf16 only: BranchTable of a batched-branch call
     size_t total;
 };
 WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T);
@@ -48,6 +49,15 @@ struct KvView {
     int32_t n_shared;
     int32_t own_cap;    // slots in the own buffer
     int32_t parent_cap; // slots in the parent's buffer (0 if none)
+};
+
+// Batched-branch call: rows [b * n_tok, (b + 1) * n_tok) of the activation matrices belong to branch b,
+// whose chunk starts at position pos0[b] of cache kv[b].
+constexpr int kMaxBranches = JUP_MAX_BRANCHES;
+struct BranchTable {
+    int32_t n_branches, n_tok;
+    int32_t pos0[kMaxBranches];
+    KvView kv[kMaxBranches];
 };
 
 }  // namespace jup
@@ -109,6 +119,6 @@ hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int p
 // ---- matrix-core (bf16) path: kernels_bf16.hip ----------------------------------------------------
 hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s);
 hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int pos, const KvView& kv,
-                        void* hidden_out, hipStream_t s);
+                        void* hidden_out, hipStream_t s, const BranchTable* branches = nullptr);
 
 }  // namespace jup

@@ -201,6 +201,77 @@ def run_fork_case(p, n_prefix, n_private, n_chunk, n_branches):
     p.kv.truncate(n_prefix - 1)
 
 
+def run_batched_branches_case(p, n_prefix, n_privates, n_chunk):
+    """All branches advance by n_chunk tokens in ONE call; the result must equal one call per branch bit for
+    bit (outputs and caches), and the oracle within tolerance."""
+    torch = torch_mod()
+    nb = len(n_privates)
+    prefix = p.hidden(n_prefix)
+    p.kv.reset()
+    p.oracle.reset()
+    step = p.stage.max_chunk_tokens
+    for pos in range(0, n_prefix, step):
+        n = min(step, n_prefix - pos)
+        p.gpu_chunk(prefix[pos:pos + n], pos)
+        p.oracle.prefill_chunk(prefix[pos:pos + n], pos)
+    oracle_prefix_kv = p.oracle.kv.copy()
+    cap = n_prefix + max(n_privates) + n_chunk
+    forks = [p.kv.fork(n_prefix, cap) for _ in range(nb)]
+    chunks = [p.hidden(n_chunk, tag=200 + b) for b in range(nb)]
+    seq_out, seq_kv, ora_out = [], [], []
+    for b, fk in enumerate(forks):
+        priv = p.hidden(n_privates[b], tag=100 + b)
+        p.oracle.kv[...] = oracle_prefix_kv
+        p.oracle.prefill_chunk(priv, n_prefix)
+        ora_out.append(p.oracle.prefill_chunk(chunks[b], n_prefix + n_privates[b]))
+        p.gpu_chunk(priv, n_prefix, kv=fk)
+        seq_out.append(p.gpu_chunk(chunks[b], n_prefix + n_privates[b], kv=fk))
+        seq_kv.append(kv_bits(fk).copy())
+    # again, all branches in one call; the chunk of the sequential pass is overwritten (pos_offset < length)
+    x = torch.from_numpy(np.concatenate(chunks)).to(device="cuda:0", dtype=p.td)
+    pos = [n_prefix + n for n in n_privates]
+    # poison the slots the batched call must rewrite, so that equality below proves they were written
+    for b, fk in enumerate(forks):
+        fk.view()[:, :, :, n_privates[b]:n_privates[b] + n_chunk, :] = 7.0
+    y = to_numpy(p.stage.prefill_branches(x, n_chunk, pos, forks))
+    torch.cuda.synchronize()
+    for b, fk in enumerate(forks):
+        got = y[b * n_chunk:(b + 1) * n_chunk]
+        assert np.array_equal(got, seq_out[b]), f"branch {b}: batched output differs from the per-branch call"
+        assert np.array_equal(kv_bits(fk), seq_kv[b]), f"branch {b}: batched cache differs"
+        p.check(got, ora_out[b], f"branch {b} chunk (batched)")
+        assert len(fk) == pos[b] + n_chunk
+    # validation happens before anything is enqueued and leaves every cache as it was
+    lens = [len(fk) for fk in forks]
+    for bad_kvs, bad_pos, status in (
+            ([forks[0], forks[0]], [pos[0], pos[0]], jb.JUP_EINVAL),          # the same cache twice
+            ([p.kv, forks[0]], [n_prefix, pos[0]], jb.JUP_EINVAL),           # parent and fork together
+            ([forks[0], forks[1]], [pos[0], lens[1] + 1], jb.JUP_EPOS),      # a hole in the second branch
+            ([forks[0], forks[1]], [pos[0], n_prefix - 1], jb.JUP_EPOS)):    # inside the shared prefix
+        with pytest.raises(jb.JupiterError) as e:
+            p.stage.prefill_branches(x[:2 * n_chunk], n_chunk, bad_pos, bad_kvs)
+        assert e.value.status == status
+        assert [len(fk) for fk in forks] == lens
+    with pytest.raises(jb.JupiterError) as e:  # more rows than the stage's workspace holds
+        big = torch.zeros((nb * (step // nb + 1), p.cfg["d_model"]), device="cuda:0", dtype=p.td)
+        p.stage.prefill_branches(big, step // nb + 1, pos, forks)
+    assert e.value.status == jb.JUP_ECAP
+    for fk in forks:
+        fk.destroy()
+
+
+def test_f32_batched_branches_equal_one_call_per_branch():
+    p = Pair(si.TINY, "f32", seed=8, max_positions=40, max_chunk_tokens=16, oracle_positions=64)
+    run_batched_branches_case(p, n_prefix=37, n_privates=[9, 4, 12], n_chunk=5)
+
+
+def test_bf16_batched_branches_equal_one_call_per_branch_bitwise():
+    """Outline branches advanced together (Sec. V-B): the weights are streamed once for all of them."""
+    cfg = dict(si.LLAMA7B_STAGE, n_layers=2)
+    p = Pair(cfg, "bf16", seed=9, max_positions=72, max_chunk_tokens=64, oracle_positions=128)
+    run_batched_branches_case(p, n_prefix=70, n_privates=[9, 33, 12, 1], n_chunk=5)
+
+
 def p_tensor(p, a):
     torch = torch_mod()
     return torch.from_numpy(a).to(device="cuda:0", dtype=p.td)
@@ -338,3 +409,10 @@ def test_c5_decode_sized_chunks_on_eight_branches_sharing_a_512_token_prefix():
     5-token chunk (1 token + 4 drafts) with a causal mask inside the chunk."""
     p = Pair(si.LLAMA7B_STAGE, "bf16", seed=50, max_positions=512, max_chunk_tokens=128, oracle_positions=581)
     run_fork_case(p, n_prefix=512, n_private=64, n_chunk=5, n_branches=8)
+
+
+@pytest.mark.slow
+def test_c5_all_eight_branches_in_one_call():
+    """Config 5 with the 8 branches batched: 40 rows through the stage at once."""
+    p = Pair(si.LLAMA7B_STAGE, "bf16", seed=50, max_positions=512, max_chunk_tokens=128, oracle_positions=581)
+    run_batched_branches_case(p, n_prefix=512, n_privates=[64] * 8, n_chunk=5)

@@ -139,6 +139,16 @@ def test_prefill_chunk_argument_errors_leave_the_cache_untouched():
     L.jup_kv_destroy(kv)
 
 
+def test_prefill_branches_without_a_stage_is_rejected():
+    L = jb.lib()
+    kv = make_kv(16)
+    pos = (ctypes.c_int32 * 1)(0)
+    kvs = (ctypes.c_void_p * 1)(kv)
+    assert L.jup_stage_prefill_branches(None, 1, FAKE, 4, pos, kvs, FAKE, None) == jb.JUP_EINVAL
+    assert L.jup_kv_len(kv) == 0
+    L.jup_kv_destroy(kv)
+
+
 def test_fork_rules():
     """Outline branches share the prompt's cache read-only (Sec. V-B)."""
     L = jb.lib()
