@@ -528,7 +528,7 @@ hipError_t configure_one() {
 // chunks; 128- and 64-row tiles with narrow N for short chunks, where the grid must be wide enough to keep
 // every CU streaming weights.
 #define JUP_GEMM_SHAPES(X)                                                          \
-    X(8, 1, 4, 1, EPI_QKV) X(8, 2, 4, 1, EPI_QKV) X(8, 3, 4, 1, EPI_QKV)            \
+    X(8, 1, 4, 1, EPI_QKV) X(8, 2, 4, 1, EPI_QKV) X(8, 3, 8, 1, EPI_QKV)            \
     X(4, 2, 4, 1, EPI_QKV) X(2, 2, 2, 2, EPI_QKV)                                   \
     X(8, 2, 4, 1, EPI_SWIGLU) X(8, 3, 4, 1, EPI_SWIGLU) X(8, 4, 4, 2, EPI_SWIGLU) X(8, 6, 4, 2, EPI_SWIGLU) \
     X(4, 4, 4, 1, EPI_SWIGLU) X(2, 4, 2, 2, EPI_SWIGLU)                             \
@@ -577,7 +577,7 @@ hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s) {
     if (bmb == 4) return launch<4, 2, 4, 1, EPI_QKV>(a, s);
     static const int cands[] = {1, 2, 3};
     const int nb = pick_blocks(a.M, a.N, cands, 3);
-    if (nb == 3) return launch<8, 3, 4, 1, EPI_QKV>(a, s);
+    if (nb == 3) return launch<8, 3, 8, 1, EPI_QKV>(a, s);  // 8 waves of 32 x 96: measured 1.3 % faster than 4 of 64 x 96
     if (nb == 2) return launch<8, 2, 4, 1, EPI_QKV>(a, s);
     return launch<8, 1, 4, 1, EPI_QKV>(a, s);
 }
