@@ -533,9 +533,290 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
 #endif
 }
 
+
+// ---------------------------------------------------------------------------------------------------------------
+// Second kernel: the same work split over twice the waves.  A workgroup is still NQ*32 queries of one head, but
+// every wave owns ONE block of 32 queries and one quarter of the keys: wave = 4*qb + g handles query block qb
+// against the tiles g, g+4, ...  The waves of a key quarter (one per query block) share that quarter's tiles
+// in LDS, each fetching half of every tile, and meet at one workgroup barrier per tile.  With 64 accumulator
+// registers per wave instead of 128, two waves fit a SIMD: while one waits for LDS or works through its
+// softmax on the vector ALU, the other has the matrix pipe.
+template <int NQ>
+__global__ __launch_bounds__(256 * NQ) void chunk_attention2_bf16(const u16* __restrict__ q, u16* __restrict__ o,
+                                                                  int n, int d_model, int n_heads, int pos0_arg,
+                                                                  KvView kv_arg, int layer, float scale_log2e,
+                                                                  const BranchTable* __restrict__ branches) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = wave & 3, qb = wave >> 2;  // key quarter, query block
+    const int c = lane & 31, hh = lane >> 5;
+    const int head = blockIdx.x % n_heads;
+    const int q_blocks = (n + NQ * 32 - 1) / (NQ * 32);
+    const int bq = blockIdx.x / n_heads;
+    const int branch = bq / q_blocks;  // 0 without a branch table
+    const int q0 = (q_blocks - 1 - bq % q_blocks) * (NQ * 32);
+    const int row0 = branch * n;
+    const int pos0 = branches ? branches->pos0[branch] : pos0_arg;
+    const KvView kv = branches ? branches->kv[branch] : kv_arg;
+    q += (size_t)row0 * d_model;
+    const int q_last = min(q0 + NQ * 32, n) - 1;  // last real query of this workgroup
+    const int n_keys = pos0 + q_last + 1;
+    const int n_tiles = (n_keys + kKT - 1) / kKT;
+    const int last_key = n_keys - 1;
+    const int first_masked_tile = (pos0 + q0 + 1) / kKT;
+
+    unsigned char* grp = lds + g * kWaveLds;  // this key quarter's two slots (K tile + V tile each)
+    const unsigned grp_addr = __builtin_amdgcn_readfirstlane(lds_byte_address(lds)) + g * kWaveLds;
+    const size_t plane_k = ((size_t)layer * 2 + 0) * n_heads + head;
+    const size_t plane_v = ((size_t)layer * 2 + 1) * n_heads + head;
+
+    // Q fragments (B operand of S^T) straight from global memory: lane = query column, 8 consecutive dh per k-step.
+    bf16x8 qf[8];
+    {
+        const int qrow = min(q0 + qb * 32 + c, n - 1);
+        const u16* qp = q + (size_t)qrow * d_model + head * 128 + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8*)(qp + 16 * ks);
+    }
+    f32x16 oacc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    // Tile fill.  With two query blocks the K half is fetched by the qb = 0 wave of the quarter and the V half
+    // by the qb = 1 wave; alone, a wave fetches both.  Load j covers rows 4j..4j+3 (1 KB of LDS); lane i lands at
+    // row 4j + (i >> 4), position i & 15, and fetches the chunk that belongs there.
+    const int lrow = lane >> 4, lp = lane & 15;
+    const u16* k_own = (const u16*)kv.own + plane_k * (size_t)kv.own_cap * 128;
+    const u16* v_own = (const u16*)kv.own + plane_v * (size_t)kv.own_cap * 128;
+    const u16* k_par = (const u16*)kv.parent + plane_k * (size_t)kv.parent_cap * 128;
+    const u16* v_par = (const u16*)kv.parent + plane_v * (size_t)kv.parent_cap * 128;
+    auto fill_part = [&](int tile, int slot, bool v_part) __attribute__((always_inline)) {
+        const unsigned dst = grp_addr + slot * kSlotBytes + (v_part ? kTileBytes : 0);
+        const u16* par = v_part ? v_par : k_par;
+        const u16* own = v_part ? v_own : k_own;
+        const int key0 = tile * kKT;
+        if (key0 + kKT - 1 <= last_key && (key0 >= kv.n_shared || key0 + kKT <= kv.n_shared)) {
+            const bool shared = key0 < kv.n_shared;
+            const char* base = uniform_ptr((const char*)((shared ? par : own) + (size_t)(shared ? key0 : key0 - kv.n_shared) * 128));
+            const unsigned vch = (((lp >> 2) ^ lrow) << 2) | (lp & 3);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                load_to_lds_16(base + j * 1024, lrow * 256 + (v_part ? vch : (lp ^ (4 * (j & 3) + lrow))) * 16,
+                               dst + j * 1024);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = 4 * j + lrow;
+                const int key = min(key0 + r, last_key);
+                const bool shared = key < kv.n_shared;
+                const unsigned row_off = (unsigned)(shared ? key : key - kv.n_shared) * 128u;  // elements, < 2^31
+                const unsigned ch = v_part ? ((((lp >> 2) ^ (r & 3)) << 2) | (lp & 3)) : (lp ^ (r & 15));
+                load_to_lds_16((shared ? par : own) + row_off + ch * 8, dst + j * 1024);
+            }
+        }
+    };
+    auto fill = [&](int tile, int slot) __attribute__((always_inline)) {
+        if (NQ == 1) {
+            fill_part(tile, slot, false);
+            fill_part(tile, slot, true);
+        } else {
+            fill_part(tile, slot, qb == 1);
+        }
+    };
+
+    const unsigned k_lane = c * 256 + ((hh ^ (c & 15)) * 16);
+    const int G = lane >> 4, s = lane & 15;
+    const int vt_row = 4 * (G >> 1) + (s >> 2);
+    unsigned v_lane[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+        v_lane[db] = vt_row * 256 + ((db ^ (vt_row & 3)) << 6) + (2 * (G & 1) + ((s & 3) >> 1)) * 16 + 8 * (s & 1);
+
+    const int cnt = n_tiles > g ? (n_tiles - g + 3) / 4 : 0;  // tiles of this key quarter
+    const int max_cnt = (n_tiles + 3) / 4;                    // of quarter 0: every wave runs that many rounds
+    if (cnt > 0) fill(g, 0);
+    const int q_abs = pos0 + q0 + qb * 32 + c;  // absolute position of this lane's query
+
+#if ATT_TIMELINE
+    unsigned long long tl[6] = {0, 0, 0, 0, 0, 0};
+    const unsigned long long tl_begin = __builtin_amdgcn_s_memtime();
+#endif
+    for (int it = 0; it < max_cnt; ++it) {
+        ATT_T(ta);
+        // The tile of this round has landed (this wave's half: the partner says the same at the barrier), and
+        // every wave of the quarter is done with the other slot, which is refilled right away.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        ATT_T(tb);
+        if (it + 1 < cnt) fill(g + 4 * (it + 1), (it + 1) & 1);
+        if (it >= cnt) continue;
+        ATT_T(t0);
+        const int tile = g + 4 * it, slot = it & 1;
+        const unsigned char* k_base = grp + slot * kSlotBytes;
+        const unsigned v_base = grp_addr + slot * kSlotBytes + kTileBytes;
+
+        // ---- S^T = K Q^T ---------------------------------------------------------------------------------------
+        f32x16 sacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+        bf16x8 kf[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kf[ks] = *(const bf16x8*)(k_base + (k_lane ^ (32 * ks)));
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) sacc = mfma32(kf[ks], qf[ks], sacc);
+
+        // ---- online softmax (a lane owns one query column) -------------------------------------------------------
+#if ATT_TIMELINE
+        asm volatile("s_nop 0" : "+v"(sacc));
+#endif
+        ATT_T(t1);
+        float sv[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sv[r] = sacc[r];
+        if (tile >= first_masked_tile) {  // the tile reaches some query's diagonal (a few tiles per workgroup)
+            asm volatile("");             // keeps this a branch: merged into selects it would run for every tile
+            const int key0 = tile * kKT;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (key0 + acc_row(r, hh) > q_abs) sv[r] = -INFINITY;
+        }
+        float mt = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mt = fmaxf(mt, sv[r]);
+        mt = max_across_halves(mt) * scale_log2e;  // the scale is positive
+        const bool grow = mt > m_run + 8.0f;       // lazy reference maximum, see the first kernel
+        const float m_new = grow ? mt : m_run;
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = grow ? __builtin_amdgcn_exp2f(m_run - m_safe) : 1.0f;
+        const bool rescale = grow && m_run != -INFINITY;
+        float ps = 0.f;
+        bf16x8 pf[2];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], scale_log2e, -m_safe));
+            ps += p;
+            pf[r >> 3][r & 7] = (__bf16)p;
+        }
+        l_run = l_run * alpha + ps;
+        m_run = m_new;
+        if (__any(rescale)) {
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+        }
+
+        // ---- O^T += V^T P^T ----------------------------------------------------------------------------------------
+#if ATT_TIMELINE
+        asm volatile("s_nop 0" : "+v"(pf[0]), "+v"(pf[1]));
+#endif
+        ATT_T(t2);
+        u32x4 vf[8];
+        [&]<int... F>(std::integer_sequence<int, F...>) {
+            (([&] {
+                 constexpr int db = F / 2, ks = F % 2;
+                 const u32x2 lo = ds_read_tr16<(16 * ks) * 256>(v_base + v_lane[db]);
+                 const u32x2 hi = ds_read_tr16<(16 * ks + 8) * 256>(v_base + v_lane[db]);
+                 vf[F] = (u32x4){lo[0], lo[1], hi[0], hi[1]};
+             }()),
+             ...);
+        }(std::make_integer_sequence<int, 8>{});
+        [&]<int... F>(std::integer_sequence<int, F...>) {
+            (([&] {
+                 wait_tr_reads<14 - 2 * F>(vf[F]);
+                 oacc[F / 2] = mfma32(__builtin_bit_cast(bf16x8, vf[F]), pf[F % 2], oacc[F / 2]);
+             }()),
+             ...);
+        }(std::make_integer_sequence<int, 8>{});
+#if ATT_TIMELINE
+        asm volatile("s_nop 0" : "+v"(oacc[3]));
+        ATT_T(t3);
+        tl[0] += t1 - t0; tl[1] += t2 - t1; tl[2] += t3 - t2; tl[3] += tb - ta; tl[4] += t0 - tb; tl[5] += 1;
+#endif
+    }
+#if ATT_TIMELINE
+    const unsigned long long tl_loop_end = __builtin_amdgcn_s_memtime();
+#endif
+
+    // ---- merge the four key quarters of every query block ----------------------------------------------------------
+    constexpr int kORow = 132;
+    constexpr int kRegion = 64 * kORow;                     // floats per key quarter: [64 queries][132]
+    float* obuf = (float*)lds;
+    float* stat_m = (float*)(lds + kStatOffset);            // [4][64]
+    float* stat_l = stat_m + 4 * 64;
+    {
+        const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+        if (hh == 0) {
+            stat_m[g * 64 + qb * 32 + c] = m_run;
+            stat_l[g * 64 + qb * 32 + c] = l_tot;
+        }
+    }
+    __syncthreads();  // statistics visible; every wave is done with the tile slots
+    {
+        float m_all = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m_all = fmaxf(m_all, stat_m[w * 64 + qb * 32 + c]);
+        float l_all = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float mw = stat_m[w * 64 + qb * 32 + c];
+            l_all += mw == -INFINITY ? 0.f : stat_l[w * 64 + qb * 32 + c] * exp2f(mw - m_all);
+        }
+        const float wscale = m_run == -INFINITY ? 0.f : exp2f(m_run - m_all) / l_all;
+        float* mine = obuf + g * kRegion + (qb * 32 + c) * kORow;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg)
+                *(float4*)(mine + db * 32 + 8 * gg + 4 * hh) =
+                    make_float4(oacc[db][4 * gg] * wscale, oacc[db][4 * gg + 1] * wscale,
+                                oacc[db][4 * gg + 2] * wscale, oacc[db][4 * gg + 3] * wscale);
+    }
+    __syncthreads();
+    for (int idx = tid; idx < NQ * 32 * 16; idx += 256 * NQ) {
+        const int qr = idx >> 4, ch = idx & 15;
+        const int qrow = q0 + qr;
+        if (qrow >= n) continue;
+        const float* src = obuf + qr * kORow + ch * 8;
+        float4 a = *(const float4*)src, b = *(const float4*)(src + 4);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const float4 a2 = *(const float4*)(src + w * kRegion), b2 = *(const float4*)(src + w * kRegion + 4);
+            a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
+            b.x += b2.x; b.y += b2.y; b.z += b2.z; b.w += b2.w;
+        }
+        u32x4 out;
+        out[0] = pack_bf16x2(a.x, a.y); out[1] = pack_bf16x2(a.z, a.w);
+        out[2] = pack_bf16x2(b.x, b.y); out[3] = pack_bf16x2(b.z, b.w);
+        *(u32x4*)(o + tiled_offset(row0 + qrow, head * 16 + ch, d_model >> 5)) = out;
+    }
+#if ATT_TIMELINE
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long* t = (unsigned long long*)o + (size_t)blockIdx.x * 8;
+        t[0] = tl[0]; t[1] = tl[1]; t[2] = tl[2]; t[3] = tl[3]; t[4] = tl_loop_end - tl_begin; t[5] = tl[5];
+        t[6] = tl[4]; t[7] = 0x1234;
+    }
+#endif
+}
+
 }  // namespace
 
+#ifndef JUP_ATTENTION_KERNEL
+#define JUP_ATTENTION_KERNEL 2
+#endif
+
 hipError_t attention_configure() {
+    hipError_t e2 = hipFuncSetAttribute((const void*)chunk_attention2_bf16<1>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kAttLds);
+    if (e2 == hipSuccess)
+        e2 = hipFuncSetAttribute((const void*)chunk_attention2_bf16<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 kAttLds);
+    if (e2 != hipSuccess) return e2;
     hipError_t e = hipFuncSetAttribute((const void*)chunk_attention_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        kAttLds);
     if (e != hipSuccess) return e;
@@ -546,24 +827,43 @@ hipError_t attention_configure() {
 void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
                             int layer, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
+    const BranchTable* none = nullptr;
+#if JUP_ATTENTION_KERNEL == 2
+    if (n <= 32)
+        hipLaunchKernelGGL(chunk_attention2_bf16<1>, dim3((n + 31) / 32 * n_heads), dim3(256), kAttLds, s, q, o, n,
+                           d_model, n_heads, pos0, kv, layer, scale_log2e, none);
+    else
+        hipLaunchKernelGGL(chunk_attention2_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(512), kAttLds, s, q, o, n,
+                           d_model, n_heads, pos0, kv, layer, scale_log2e, none);
+#else
     if (n <= 32)
         hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3((n + 31) / 32 * n_heads), dim3(256), kAttLds, s, q, o, n,
-                           d_model, n_heads, pos0, kv, layer, scale_log2e, (const BranchTable*)nullptr);
+                           d_model, n_heads, pos0, kv, layer, scale_log2e, none);
     else
         hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(256), kAttLds, s, q, o, n,
-                           d_model, n_heads, pos0, kv, layer, scale_log2e, (const BranchTable*)nullptr);
+                           d_model, n_heads, pos0, kv, layer, scale_log2e, none);
+#endif
 }
 
 void launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_model, int n_heads,
                              const BranchTable* branches, int layer, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
     const KvView none{};
+#if JUP_ATTENTION_KERNEL == 2
+    if (n <= 32)
+        hipLaunchKernelGGL(chunk_attention2_bf16<1>, dim3(n_branches * ((n + 31) / 32) * n_heads), dim3(256), kAttLds,
+                           s, q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches);
+    else
+        hipLaunchKernelGGL(chunk_attention2_bf16<2>, dim3(n_branches * ((n + 63) / 64) * n_heads), dim3(512), kAttLds,
+                           s, q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches);
+#else
     if (n <= 32)
         hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3(n_branches * ((n + 31) / 32) * n_heads), dim3(256), kAttLds, s,
                            q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches);
     else
         hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3(n_branches * ((n + 63) / 64) * n_heads), dim3(256), kAttLds, s,
                            q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches);
+#endif
 }
 
 }  // namespace jup

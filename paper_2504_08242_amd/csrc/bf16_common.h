@@ -29,6 +29,27 @@ __device__ inline const char* uniform_ptr(const char* p) {
     return (const char*)(((unsigned long long)hi << 32) | lo);
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane i's piece lands at lds_base + 16 i, where
+// lds_base (a wave-uniform LDS byte address) travels in M0.  Issued as text so that the caller controls every
+// wait itself: the hardware counts these loads in vmcnt only, and the caller orders them against LDS reads of
+// the same bytes with explicit vmcnt waits and barriers.  (The builtin form makes the compiler's wait-count
+// pass drain every load in flight before LDS reads it cannot tell apart, which undoes prefetching.)  The
+// "memory" clobber keeps the compiler from moving LDS accesses across the instruction.  First form: a 64-bit
+// address per lane; second form: a wave-uniform base plus a 32-bit byte offset per lane.
+__device__ inline void load_to_lds_16(const void* gptr, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+__device__ inline void load_to_lds_16(const void* uniform_base, unsigned lane_offset, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_offset), "s"(uniform_base), "s"(lds_base)
+                 : "memory", "m0");
+}
+// LDS byte address of a pointer into the workgroup's dynamic LDS.
+__device__ inline unsigned lds_byte_address(const void* p) {
+    return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
