@@ -535,21 +535,27 @@ __global__ __launch_bounds__(256) void chunk_attention_bf16(const u16* __restric
 
 
 // ---------------------------------------------------------------------------------------------------------------
-// Second kernel: the same work split over twice the waves.  A workgroup is still NQ*32 queries of one head, but
-// every wave owns ONE block of 32 queries and one quarter of the keys: wave = 4*qb + g handles query block qb
-// against the tiles g, g+4, ...  The waves of a key quarter (one per query block) share that quarter's tiles
-// in LDS, each fetching half of every tile, and meet at one workgroup barrier per tile.  With 64 accumulator
-// registers per wave instead of 128, two waves fit a SIMD: while one waits for LDS or works through its
-// softmax on the vector ALU, the other has the matrix pipe.
+// Second kernel: the same work split over twice the waves, plus four waves that only fetch.  A workgroup is
+// still NQ*32 queries of one head, but every computing wave owns ONE block of 32 queries and one quarter of the
+// keys: wave = 4*qb + g handles query block qb against the tiles g, g+4, ...  The waves of a key quarter (one
+// per query block) share that quarter's tiles in LDS; loader wave g keeps them one tile ahead, and all waves
+// meet at one workgroup barrier per round.  With 64 accumulator registers per wave instead of 128, three waves
+// fit a SIMD (two computing, one loading): while one waits for LDS or works through its softmax on the vector
+// ALU, the other has the matrix pipe, and no computing wave is held by the issue of a global->LDS load.
 template <int NQ>
-__global__ __launch_bounds__(256 * NQ) void chunk_attention2_bf16(const u16* __restrict__ q, u16* __restrict__ o,
+__global__ __launch_bounds__(256 * NQ + 256) void chunk_attention2_bf16(const u16* __restrict__ q, u16* __restrict__ o,
                                                                   int n, int d_model, int n_heads, int pos0_arg,
                                                                   KvView kv_arg, int layer, float scale_log2e,
                                                                   const BranchTable* __restrict__ branches) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g = wave & 3, qb = wave >> 2;  // key quarter, query block
+    // Waves 0 .. 4 NQ - 1 compute (key quarter g, query block qb); the last four waves only fetch tiles, one per
+    // key quarter.  A global->LDS load holds the issuing wave for about a hundred cycles (the address path of a
+    // CU takes 64 bytes per clock, and all quarters refill at the same moment): issued by the computing waves,
+    // the loads of a round cost them as much as the round's arithmetic.
+    const bool loader = wave >= 4 * NQ;
+    const int g = wave & 3, qb = loader ? 0 : wave >> 2;
     const int c = lane & 31, hh = lane >> 5;
     const int head = blockIdx.x % n_heads;
     const int q_blocks = (n + NQ * 32 - 1) / (NQ * 32);
@@ -571,6 +577,58 @@ __global__ __launch_bounds__(256 * NQ) void chunk_attention2_bf16(const u16* __r
     const size_t plane_k = ((size_t)layer * 2 + 0) * n_heads + head;
     const size_t plane_v = ((size_t)layer * 2 + 1) * n_heads + head;
 
+    const int cnt = n_tiles > g ? (n_tiles - g + 3) / 4 : 0;  // tiles of this key quarter
+    const int max_cnt = (n_tiles + 3) / 4;                    // of quarter 0: every wave runs that many rounds
+    if (loader) {
+        // The whole life of a loader wave: one tile ahead of the computing waves, the same barriers as they.
+        // Tile fill (loader waves).  Load j covers rows 4j..4j+3 (1 KB of LDS); lane i lands at
+        // row 4j + (i >> 4), position i & 15, and fetches the chunk that belongs there.
+        const int lrow = lane >> 4, lp = lane & 15;
+        const u16* k_own = (const u16*)kv.own + plane_k * (size_t)kv.own_cap * 128;
+        const u16* v_own = (const u16*)kv.own + plane_v * (size_t)kv.own_cap * 128;
+        const u16* k_par = (const u16*)kv.parent + plane_k * (size_t)kv.parent_cap * 128;
+        const u16* v_par = (const u16*)kv.parent + plane_v * (size_t)kv.parent_cap * 128;
+        auto fill_part = [&](int tile, int slot, bool v_part) __attribute__((always_inline)) {
+            const unsigned dst = grp_addr + slot * kSlotBytes + (v_part ? kTileBytes : 0);
+            const u16* par = v_part ? v_par : k_par;
+            const u16* own = v_part ? v_own : k_own;
+            const int key0 = tile * kKT;
+            if (key0 + kKT - 1 <= last_key && (key0 >= kv.n_shared || key0 + kKT <= kv.n_shared)) {
+                const bool shared = key0 < kv.n_shared;
+                const char* base = uniform_ptr((const char*)((shared ? par : own) + (size_t)(shared ? key0 : key0 - kv.n_shared) * 128));
+                const unsigned vch = (((lp >> 2) ^ lrow) << 2) | (lp & 3);
+    #pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    load_to_lds_16(base + j * 1024, lrow * 256 + (v_part ? vch : (lp ^ (4 * (j & 3) + lrow))) * 16,
+                                   dst + j * 1024);
+            } else {
+    #pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int r = 4 * j + lrow;
+                    const int key = min(key0 + r, last_key);
+                    const bool shared = key < kv.n_shared;
+                    const unsigned row_off = (unsigned)(shared ? key : key - kv.n_shared) * 128u;  // elements, < 2^31
+                    const unsigned ch = v_part ? ((((lp >> 2) ^ (r & 3)) << 2) | (lp & 3)) : (lp ^ (r & 15));
+                    load_to_lds_16((shared ? par : own) + row_off + ch * 8, dst + j * 1024);
+                }
+            }
+        };
+        auto fill = [&](int tile, int slot) __attribute__((always_inline)) {
+            fill_part(tile, slot, false);
+            fill_part(tile, slot, true);
+        };
+        if (cnt > 0) fill(g, 0);
+        for (int it = 0; it < max_cnt; ++it) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the tile of this round has landed
+            __builtin_amdgcn_s_barrier();                     // ... and the other slot is free
+            if (it + 1 < cnt) fill(g + 4 * (it + 1), (it + 1) & 1);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();  // the two barriers of the merge
+        __syncthreads();
+        return;
+    }
+
     // Q fragments (B operand of S^T) straight from global memory: lane = query column, 8 consecutive dh per k-step.
     bf16x8 qf[8];
     {
@@ -586,48 +644,6 @@ __global__ __launch_bounds__(256 * NQ) void chunk_attention2_bf16(const u16* __r
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // Tile fill.  With two query blocks the K half is fetched by the qb = 0 wave of the quarter and the V half
-    // by the qb = 1 wave; alone, a wave fetches both.  Load j covers rows 4j..4j+3 (1 KB of LDS); lane i lands at
-    // row 4j + (i >> 4), position i & 15, and fetches the chunk that belongs there.
-    const int lrow = lane >> 4, lp = lane & 15;
-    const u16* k_own = (const u16*)kv.own + plane_k * (size_t)kv.own_cap * 128;
-    const u16* v_own = (const u16*)kv.own + plane_v * (size_t)kv.own_cap * 128;
-    const u16* k_par = (const u16*)kv.parent + plane_k * (size_t)kv.parent_cap * 128;
-    const u16* v_par = (const u16*)kv.parent + plane_v * (size_t)kv.parent_cap * 128;
-    auto fill_part = [&](int tile, int slot, bool v_part) __attribute__((always_inline)) {
-        const unsigned dst = grp_addr + slot * kSlotBytes + (v_part ? kTileBytes : 0);
-        const u16* par = v_part ? v_par : k_par;
-        const u16* own = v_part ? v_own : k_own;
-        const int key0 = tile * kKT;
-        if (key0 + kKT - 1 <= last_key && (key0 >= kv.n_shared || key0 + kKT <= kv.n_shared)) {
-            const bool shared = key0 < kv.n_shared;
-            const char* base = uniform_ptr((const char*)((shared ? par : own) + (size_t)(shared ? key0 : key0 - kv.n_shared) * 128));
-            const unsigned vch = (((lp >> 2) ^ lrow) << 2) | (lp & 3);
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                load_to_lds_16(base + j * 1024, lrow * 256 + (v_part ? vch : (lp ^ (4 * (j & 3) + lrow))) * 16,
-                               dst + j * 1024);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int r = 4 * j + lrow;
-                const int key = min(key0 + r, last_key);
-                const bool shared = key < kv.n_shared;
-                const unsigned row_off = (unsigned)(shared ? key : key - kv.n_shared) * 128u;  // elements, < 2^31
-                const unsigned ch = v_part ? ((((lp >> 2) ^ (r & 3)) << 2) | (lp & 3)) : (lp ^ (r & 15));
-                load_to_lds_16((shared ? par : own) + row_off + ch * 8, dst + j * 1024);
-            }
-        }
-    };
-    auto fill = [&](int tile, int slot) __attribute__((always_inline)) {
-        if (NQ == 1) {
-            fill_part(tile, slot, false);
-            fill_part(tile, slot, true);
-        } else {
-            fill_part(tile, slot, qb == 1);
-        }
-    };
-
     const unsigned k_lane = c * 256 + ((hh ^ (c & 15)) * 16);
     const int G = lane >> 4, s = lane & 15;
     const int vt_row = 4 * (G >> 1) + (s >> 2);
@@ -636,9 +652,6 @@ __global__ __launch_bounds__(256 * NQ) void chunk_attention2_bf16(const u16* __r
     for (int db = 0; db < 4; ++db)
         v_lane[db] = vt_row * 256 + ((db ^ (vt_row & 3)) << 6) + (2 * (G & 1) + ((s & 3) >> 1)) * 16 + 8 * (s & 1);
 
-    const int cnt = n_tiles > g ? (n_tiles - g + 3) / 4 : 0;  // tiles of this key quarter
-    const int max_cnt = (n_tiles + 3) / 4;                    // of quarter 0: every wave runs that many rounds
-    if (cnt > 0) fill(g, 0);
     const int q_abs = pos0 + q0 + qb * 32 + c;  // absolute position of this lane's query
 
 #if ATT_TIMELINE
@@ -647,12 +660,10 @@ __global__ __launch_bounds__(256 * NQ) void chunk_attention2_bf16(const u16* __r
 #endif
     for (int it = 0; it < max_cnt; ++it) {
         ATT_T(ta);
-        // The tile of this round has landed (this wave's half: the partner says the same at the barrier), and
-        // every wave of the quarter is done with the other slot, which is refilled right away.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // One barrier per round: the loader arrives when the tile of this round has landed, the computing waves
+        // when they are done with the other slot, which the loader then refills.
         __builtin_amdgcn_s_barrier();
         ATT_T(tb);
-        if (it + 1 < cnt) fill(g + 4 * (it + 1), (it + 1) & 1);
         if (it >= cnt) continue;
         ATT_T(t0);
         const int tile = g + 4 * it, slot = it & 1;
@@ -663,11 +674,14 @@ __global__ __launch_bounds__(256 * NQ) void chunk_attention2_bf16(const u16* __r
         f32x16 sacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-        bf16x8 kf[8];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kf[ks] = *(const bf16x8*)(k_base + (k_lane ^ (32 * ks)));
+        for (int half = 0; half < 2; ++half) {  // four fragments at a time: 168 registers per wave is the budget
+            bf16x8 kf[4];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) sacc = mfma32(kf[ks], qf[ks], sacc);
+            for (int ks = 0; ks < 4; ++ks) kf[ks] = *(const bf16x8*)(k_base + (k_lane ^ (32 * (4 * half + ks))));
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sacc = mfma32(kf[ks], qf[4 * half + ks], sacc);
+        }
 
         // ---- online softmax (a lane owns one query column) -------------------------------------------------------
 #if ATT_TIMELINE
@@ -830,10 +844,10 @@ void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_head
     const BranchTable* none = nullptr;
 #if JUP_ATTENTION_KERNEL == 2
     if (n <= 32)
-        hipLaunchKernelGGL(chunk_attention2_bf16<1>, dim3((n + 31) / 32 * n_heads), dim3(256), kAttLds, s, q, o, n,
+        hipLaunchKernelGGL(chunk_attention2_bf16<1>, dim3((n + 31) / 32 * n_heads), dim3(512), kAttLds, s, q, o, n,
                            d_model, n_heads, pos0, kv, layer, scale_log2e, none);
     else
-        hipLaunchKernelGGL(chunk_attention2_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(512), kAttLds, s, q, o, n,
+        hipLaunchKernelGGL(chunk_attention2_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(768), kAttLds, s, q, o, n,
                            d_model, n_heads, pos0, kv, layer, scale_log2e, none);
 #else
     if (n <= 32)
@@ -851,10 +865,10 @@ void launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_
     const KvView none{};
 #if JUP_ATTENTION_KERNEL == 2
     if (n <= 32)
-        hipLaunchKernelGGL(chunk_attention2_bf16<1>, dim3(n_branches * ((n + 31) / 32) * n_heads), dim3(256), kAttLds,
+        hipLaunchKernelGGL(chunk_attention2_bf16<1>, dim3(n_branches * ((n + 31) / 32) * n_heads), dim3(512), kAttLds,
                            s, q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches);
     else
-        hipLaunchKernelGGL(chunk_attention2_bf16<2>, dim3(n_branches * ((n + 63) / 64) * n_heads), dim3(512), kAttLds,
+        hipLaunchKernelGGL(chunk_attention2_bf16<2>, dim3(n_branches * ((n + 63) / 64) * n_heads), dim3(768), kAttLds,
                            s, q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches);
 #else
     if (n <= 32)
