@@ -42,6 +42,10 @@ def lib():
         L.oracle_stage_prefill_chunk.argtypes = [
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
             ctypes.POINTER(fp), fp, ctypes.c_int, ctypes.c_int, fp, ctypes.c_int, fp]
+        L.oracle_stage_prefill_tree.restype = ctypes.c_int
+        L.oracle_stage_prefill_tree.argtypes = [
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
+            ctypes.POINTER(fp), fp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), fp, ctypes.c_int, fp]
         L.oracle_num_threads.restype = ctypes.c_int
         L.oracle_rmsnorm.restype = None
         L.oracle_rmsnorm.argtypes = [fp, fp, fp, ctypes.c_int, ctypes.c_int, ctypes.c_double]
@@ -87,7 +91,8 @@ class OracleStage:
     def reset(self):
         self.kv_len = 0
 
-    def prefill_chunk(self, hidden_in, pos_offset=None):
+    def prefill_chunk(self, hidden_in, pos_offset=None, parents=None):
+        """One sub-sequence; with ``parents`` (one index per token, -1 or an earlier token) a token tree."""
         c = self.cfg
         hin, hin_p = _f32(hidden_in)
         n = hin.shape[0]
@@ -95,15 +100,32 @@ class OracleStage:
         if pos_offset is None:
             pos_offset = self.kv_len
         out = np.empty_like(hin)
-        rc = lib().oracle_stage_prefill_chunk(
-            c["n_layers"], c["d_model"], c["n_heads"], c["head_dim"], c["d_ffn"], float(c["rms_eps"]),
-            float(c["rope_theta"]), self._ptrs, hin_p, n, int(pos_offset),
-            self.kv.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), self.max_positions,
-            out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+        head = (c["n_layers"], c["d_model"], c["n_heads"], c["head_dim"], c["d_ffn"], float(c["rms_eps"]),
+                float(c["rope_theta"]), self._ptrs, hin_p, n, int(pos_offset))
+        tail = (self.kv.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), self.max_positions,
+                out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+        if parents is None:
+            rc = lib().oracle_stage_prefill_chunk(*head, *tail)
+        else:
+            par = np.ascontiguousarray(parents, dtype=np.int32)
+            assert par.shape == (n,)
+            rc = lib().oracle_stage_prefill_tree(*head, par.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), *tail)
         if rc != 0:
-            raise RuntimeError(f"oracle_stage_prefill_chunk failed with {rc}")
+            raise RuntimeError(f"oracle stage forward failed with {rc}")
         self.kv_len = int(pos_offset) + n
         return out
+
+    def prefill_tree(self, hidden_in, parents, pos_offset=None):
+        return self.prefill_chunk(hidden_in, pos_offset, parents=parents)
+
+    def keep(self, base_len, slots):
+        """Sec. V-A, removal of the rejected candidates: the cache keeps positions below ``base_len`` and,
+        behind them, the entries at ``base_len + slots[j]`` (in this order); everything else is dropped."""
+        slots = [int(s) for s in slots]
+        assert all(0 <= s and base_len + s < self.kv_len for s in slots)
+        kept = self.kv[:, :, :, [base_len + s for s in slots], :].copy()
+        self.kv[:, :, :, base_len:base_len + len(slots), :] = kept
+        self.kv_len = base_len + len(slots)
 
 
 def rmsnorm(x, g, eps):

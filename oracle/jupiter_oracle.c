@@ -28,12 +28,22 @@
  *     element index = (((layer*2 + which)*n_heads + head)*max_positions
  *                      + position)*head_dim + i
  *
+ * Token-tree variant (Sec. V-A: the candidate tokens of a speculative step are
+ * verified in one forward pass; the paper evaluates with the token tree of
+ * Medusa): the sub-sequence is a forest given by parents[t] in {-1, 0..t-1};
+ * token t is stored at slot pos_offset + t, is rotated at position
+ * pos_offset + depth(t) and sees the earlier sub-sequences, its ancestors and
+ * itself.  A chain (parents[t] = t-1) is the ordinary sub-sequence.
+ *
  * Pins (tests/test_oracle_*.py): an independent library decoder (Hugging Face
  * Llama layers with a DynamicCache, fp64, CPU), torch's scaled-dot-product
  * attention / rms_norm / silu, closed forms (uniform softmax -> running mean,
  * one-hot softmax, position-0 RoPE identity, constant-vector RMSNorm), the
  * relative-position invariance of RoPE scores, and brute force over every
- * composition of a short prompt against oracle/bruteforce.py.
+ * composition of a short prompt against oracle/bruteforce.py.  Tree variant:
+ * the same library decoder driven with an explicit ancestor mask and depth
+ * positions, and the path property (a node's output is the last row of the
+ * ordinary call on its root-to-node path).
  */
 #include <math.h>
 #include <stddef.h>
@@ -114,7 +124,8 @@ int oracle_num_threads(void)
 }
 
 /*
- * One stage forward over one sub-sequence (Sec. IV-A.2).
+ * One stage forward over one sub-sequence (Sec. IV-A.2); with parents != NULL over the token
+ * tree of a speculative step (Sec. V-A), see oracle_stage_prefill_tree below.
  *
  *   weights     [n_layers * 9] host pointers, per layer in the order
  *               wq, wk, wv, wo ([d,d]), w_gate, w_up ([f,d]), w_down ([d,f]),
@@ -129,9 +140,9 @@ int oracle_num_threads(void)
  * Returns 0, or -1 for inconsistent sizes, -2 when the cache is too small,
  * -3 when memory for the intermediates cannot be obtained.
  */
-int oracle_stage_prefill_chunk(int n_layers, int d, int n_heads, int dh, int f, double rms_eps, double rope_theta,
-                               const float *const *weights, const float *hidden_in, int n_tokens, int pos_offset,
-                               float *kv, int max_positions, float *hidden_out)
+static int stage_forward(int n_layers, int d, int n_heads, int dh, int f, double rms_eps, double rope_theta,
+                         const float *const *weights, const float *hidden_in, int n_tokens, int pos_offset,
+                         const int32_t *parents, float *kv, int max_positions, float *hidden_out)
 {
     if (n_layers < 0 || d <= 0 || n_heads <= 0 || dh <= 0 || f <= 0 || d != n_heads * dh || (dh & 1) ||
         n_tokens < 0 || pos_offset < 0)
@@ -140,6 +151,10 @@ int oracle_stage_prefill_chunk(int n_layers, int d, int n_heads, int dh, int f, 
         return -2;
     if (n_tokens == 0)
         return 0;
+    if (parents)
+        for (int t = 0; t < n_tokens; ++t)
+            if (parents[t] < -1 || parents[t] >= t)
+                return -1;
 
     const int n = n_tokens;
     const size_t nd = (size_t)n * d, nf = (size_t)n * f;
@@ -153,12 +168,24 @@ int oracle_stage_prefill_chunk(int n_layers, int d, int n_heads, int dh, int f, 
     float *h = malloc(nd * sizeof(float));    /* residual stream after attention */
     float *gate = malloc(nf * sizeof(float));
     float *up = malloc(nf * sizeof(float));
+    /*
+     * depth[t]: number of ancestors of token t inside this sub-sequence (t itself for a chain).
+     * sees[t*n + j] = 1 when token t attends to token j of this sub-sequence: j is t or an ancestor of t.
+     */
+    int *depth = malloc((size_t)n * sizeof(int));
+    unsigned char *sees = calloc((size_t)n * n, 1);
     int rc = 0;
-    if (!x || !xn || !q || !k || !v || !o || !proj || !h || !gate || !up) {
+    if (!x || !xn || !q || !k || !v || !o || !proj || !h || !gate || !up || !depth || !sees) {
         rc = -3;
         goto done;
     }
     memcpy(x, hidden_in, nd * sizeof(float));
+    for (int t = 0; t < n; ++t) {
+        const int par = parents ? parents[t] : t - 1;
+        depth[t] = par < 0 ? 0 : depth[par] + 1;
+        for (int a = t; a >= 0; a = parents ? parents[a] : a - 1)
+            sees[(size_t)t * n + a] = 1;
+    }
 
     for (int l = 0; l < n_layers; ++l) {
         const float *const *w = weights + (size_t)l * W_PER_LAYER;
@@ -169,28 +196,39 @@ int oracle_stage_prefill_chunk(int n_layers, int d, int n_heads, int dh, int f, 
         linear_nt(xn, w[W_K], k, n, d, d);
         linear_nt(xn, w[W_V], v, n, d, d);
 
-        /* Rotary embedding at absolute positions, then store K and V in the cache. */
+        /*
+         * Rotary embedding at absolute positions (earlier tokens + own depth), then store K and V
+         * in the cache slot of the token (earlier tokens + own index).
+         */
 #pragma omp parallel for collapse(2) schedule(static)
         for (int t = 0; t < n; ++t)
             for (int hh = 0; hh < n_heads; ++hh) {
-                int64_t pos = (int64_t)pos_offset + t;
+                const int64_t pos = (int64_t)pos_offset + depth[t];
+                const int slot = pos_offset + t;
                 rope_head(q + (size_t)t * d + (size_t)hh * dh, dh, pos, rope_theta);
                 rope_head(k + (size_t)t * d + (size_t)hh * dh, dh, pos, rope_theta);
-                memcpy(kv + kv_index(l, 0, hh, (int)pos, n_heads, max_positions, dh),
+                memcpy(kv + kv_index(l, 0, hh, slot, n_heads, max_positions, dh),
                        k + (size_t)t * d + (size_t)hh * dh, (size_t)dh * sizeof(float));
-                memcpy(kv + kv_index(l, 1, hh, (int)pos, n_heads, max_positions, dh),
+                memcpy(kv + kv_index(l, 1, hh, slot, n_heads, max_positions, dh),
                        v + (size_t)t * d + (size_t)hh * dh, (size_t)dh * sizeof(float));
             }
 
         /*
-         * Masked attention: the query at absolute position P sees the cached
-         * keys 0..P (earlier sub-sequences, earlier tokens of this one, itself).
+         * Masked attention: a query sees every cached slot of the earlier sub-sequences and, of
+         * this sub-sequence, the slots of the tokens marked in `sees` (for a chain: slots 0..P of
+         * the query at absolute position P).
          */
         const double scale = 1.0 / sqrt((double)dh);
 #pragma omp parallel for collapse(2) schedule(dynamic, 4)
         for (int hh = 0; hh < n_heads; ++hh)
             for (int t = 0; t < n; ++t) {
-                const int n_keys = pos_offset + t + 1;
+                int *vis = malloc((size_t)(pos_offset + t + 1) * sizeof(int)); /* visible slots, ascending */
+                int n_keys = 0;
+                for (int j = 0; j < pos_offset; ++j)
+                    vis[n_keys++] = j;
+                for (int j = 0; j <= t; ++j)
+                    if (sees[(size_t)t * n + j])
+                        vis[n_keys++] = pos_offset + j;
                 const float *qv = q + (size_t)t * d + (size_t)hh * dh;
                 const float *kc = kv + kv_index(l, 0, hh, 0, n_heads, max_positions, dh);
                 const float *vc = kv + kv_index(l, 1, hh, 0, n_heads, max_positions, dh);
@@ -198,7 +236,7 @@ int oracle_stage_prefill_chunk(int n_layers, int d, int n_heads, int dh, int f, 
                 double *acc = calloc((size_t)dh, sizeof(double));
                 double m = -INFINITY, z = 0.0;
                 for (int j = 0; j < n_keys; ++j) {
-                    p[j] = dotd(qv, kc + (size_t)j * dh, dh) * scale;
+                    p[j] = dotd(qv, kc + (size_t)vis[j] * dh, dh) * scale;
                     if (p[j] > m)
                         m = p[j];
                 }
@@ -208,7 +246,7 @@ int oracle_stage_prefill_chunk(int n_layers, int d, int n_heads, int dh, int f, 
                 }
                 for (int j = 0; j < n_keys; ++j) {
                     const double wj = p[j] / z;
-                    const float *vj = vc + (size_t)j * dh;
+                    const float *vj = vc + (size_t)vis[j] * dh;
                     for (int i = 0; i < dh; ++i)
                         acc[i] += wj * (double)vj[i];
                 }
@@ -216,6 +254,7 @@ int oracle_stage_prefill_chunk(int n_layers, int d, int n_heads, int dh, int f, 
                     o[(size_t)t * d + (size_t)hh * dh + i] = (float)acc[i];
                 free(p);
                 free(acc);
+                free(vis);
             }
 
         /* Final linear layer of the attention block, residual. */
@@ -251,7 +290,34 @@ done:
     free(h);
     free(gate);
     free(up);
+    free(depth);
+    free(sees);
     return rc;
+}
+
+int oracle_stage_prefill_chunk(int n_layers, int d, int n_heads, int dh, int f, double rms_eps, double rope_theta,
+                               const float *const *weights, const float *hidden_in, int n_tokens, int pos_offset,
+                               float *kv, int max_positions, float *hidden_out)
+{
+    return stage_forward(n_layers, d, n_heads, dh, f, rms_eps, rope_theta, weights, hidden_in, n_tokens, pos_offset,
+                         NULL, kv, max_positions, hidden_out);
+}
+
+/*
+ * One stage forward over the candidate tokens of a speculative step (Sec. V-A), arranged as a
+ * token tree: parents[t] is the index of token t's parent inside this call, or -1 when t follows
+ * the last earlier token directly; parents[t] < t.  Slots, positions and visibility as described
+ * at the top of the file.  Returns as oracle_stage_prefill_chunk; -1 also for a parent index
+ * outside [-1, t).
+ */
+int oracle_stage_prefill_tree(int n_layers, int d, int n_heads, int dh, int f, double rms_eps, double rope_theta,
+                              const float *const *weights, const float *hidden_in, int n_tokens, int pos_offset,
+                              const int32_t *parents, float *kv, int max_positions, float *hidden_out)
+{
+    if (!parents)
+        return -1;
+    return stage_forward(n_layers, d, n_heads, dh, f, rms_eps, rope_theta, weights, hidden_in, n_tokens, pos_offset,
+                         parents, kv, max_positions, hidden_out);
 }
 
 /*

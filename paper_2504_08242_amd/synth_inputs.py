@@ -18,6 +18,12 @@ Recipe
   stream = HIDDEN_STREAM for hidden states (index = caller-chosen tag),
   drawn with ``standard_normal(dtype=float32)``; tensors are therefore
   independent of the order in which they are requested.
+* token trees (the candidates of a speculative step, Sec. V-A; the paper
+  evaluates with Medusa's tree, which has one root, at most 64 nodes and a
+  few levels, bushy near the root): ``make_token_tree`` draws, for every
+  node after the root, a parent among the earlier nodes of depth below
+  ``max_depth`` with probability proportional to 2**(-depth), from
+  ``default_rng([seed, TREE_STREAM, n_tokens])``.
 """
 from concurrent.futures import ThreadPoolExecutor
 
@@ -25,6 +31,7 @@ import numpy as np
 
 WEIGHT_NAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_mlp")
 HIDDEN_STREAM = 1_000_000
+TREE_STREAM = 2_000_000
 
 # Architectures of the five benchmark configurations.
 TINY = dict(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ffn=688, rms_eps=1e-5, rope_theta=1e4)
@@ -84,3 +91,16 @@ def make_hidden(cfg, seed, n_tokens, tag=0, bf16=False):
     rng = np.random.default_rng([seed, HIDDEN_STREAM, tag])
     h = rng.standard_normal((n_tokens, cfg["d_model"]), dtype=np.float32)
     return round_to_bf16(h) if bf16 else h
+
+
+def make_token_tree(n_tokens, seed, max_depth=4):
+    """parents[t] for a one-root tree of n_tokens nodes: -1 for the root, else the index of an earlier node."""
+    rng = np.random.default_rng([seed, TREE_STREAM, n_tokens])
+    parents = np.full(n_tokens, -1, dtype=np.int32)
+    depth = np.zeros(n_tokens, dtype=np.int64)
+    for t in range(1, n_tokens):
+        ok = np.flatnonzero(depth[:t] < max_depth)
+        w = 0.5 ** depth[ok]
+        parents[t] = ok[rng.choice(len(ok), p=w / w.sum())]
+        depth[t] = depth[parents[t]] + 1
+    return parents

@@ -377,3 +377,137 @@ def test_input_generator_is_seeded_and_bf16_rounding_is_nearest_even():
     r = np.random.default_rng(0).standard_normal(10000).astype(np.float32)
     assert np.array_equal(si.round_to_bf16(r), torch.from_numpy(r).to(torch.bfloat16).float().numpy())
     assert np.array_equal(si.bf16_bits_to_f32(si.bf16_bits(si.round_to_bf16(r))), si.round_to_bf16(r))
+
+
+# ----------------------------------------------------------------------------------------------
+# Token tree of a speculative step (Sec. V-A): candidates verified in one forward pass.
+# ----------------------------------------------------------------------------------------------
+def tree_depths_and_ancestors(parents):
+    n = len(parents)
+    depth = [0] * n
+    anc = [[] for _ in range(n)]
+    for t in range(n):
+        if parents[t] >= 0:
+            depth[t] = depth[parents[t]] + 1
+            anc[t] = anc[parents[t]] + [int(parents[t])]
+    return depth, anc
+
+
+def test_tree_oracle_matches_hf_llama_with_ancestor_mask_and_depth_positions():
+    """Independent pin: the library decoder, driven with an explicit 4-D mask (prefix + ancestors + self) and
+    position ids prefix + depth, on a cache that already holds the prefix."""
+    cfg = dict(SMALL, n_layers=3)
+    layers = si.make_layers(cfg, seed=11, weight_std=0.15)
+    p, n = 7, 13
+    parents = si.make_token_tree(n, seed=11)
+    hidden = si.make_hidden(cfg, seed=11, n_tokens=p + n)
+    st = oracle.OracleStage(cfg, layers, p + n)
+    st.prefill_chunk(hidden[:p])
+    out = st.prefill_tree(hidden[p:], parents)
+
+    depth, anc = tree_depths_and_ancestors(parents)
+    m = hf_model(cfg, layers)
+    from transformers import DynamicCache
+    cache = DynamicCache()
+    with torch.no_grad():
+        r = m(inputs_embeds=torch.from_numpy(hidden[:p].astype(np.float64))[None], past_key_values=cache,
+              use_cache=True)
+        cache = r.past_key_values
+        mask = torch.full((1, 1, n, p + n), float("-inf"), dtype=torch.float64)
+        mask[..., :p] = 0.0
+        for t in range(n):
+            for a in anc[t] + [t]:
+                mask[0, 0, t, p + a] = 0.0
+        pos = torch.tensor([[p + dpt for dpt in depth]])
+        r = m(inputs_embeds=torch.from_numpy(hidden[p:].astype(np.float64))[None], attention_mask=mask,
+              position_ids=pos, cache_position=torch.arange(p, p + n), past_key_values=cache, use_cache=True)
+    ref = r.last_hidden_state[0].numpy()
+    assert rel_l2(out, ref) < 2e-6
+    assert np.max(np.abs(out - ref)) < 2e-5
+    for l in range(cfg["n_layers"]):
+        k, v = hf_cache_kv(r.past_key_values, l)
+        assert rel_l2(st.kv[l, 0], k.numpy()) < 2e-6   # slot p + t holds node t, K rotated at p + depth(t)
+        assert rel_l2(st.kv[l, 1], v.numpy()) < 2e-6
+
+
+def test_tree_node_equals_last_row_of_the_ordinary_call_on_its_path():
+    """What verification relies on: a candidate's output is what the model gives after the tokens on its path."""
+    cfg = dict(SMALL, n_layers=2)
+    layers = si.make_layers(cfg, seed=12, weight_std=0.15)
+    p, n = 5, 16
+    parents = si.make_token_tree(n, seed=12)
+    hidden = si.make_hidden(cfg, seed=12, n_tokens=p + n)
+    st = oracle.OracleStage(cfg, layers, p + n)
+    st.prefill_chunk(hidden[:p])
+    out = st.prefill_tree(hidden[p:], parents)
+    _, anc = tree_depths_and_ancestors(parents)
+    assert max(len(a) for a in anc) >= 2 and len(set(parents.tolist())) > 3   # a real tree, not a chain or a star
+    for t in range(n):
+        path = anc[t] + [t]
+        chain = oracle.OracleStage(cfg, layers, p + len(path))
+        chain.prefill_chunk(hidden[:p])
+        ref = chain.prefill_chunk(hidden[p:][path])
+        np.testing.assert_array_equal(out[t], ref[-1])   # same keys in the same order: the same roundings
+        for j, a in enumerate(path):                      # and the same cache entries, slot p+a vs position p+j
+            np.testing.assert_array_equal(st.kv[:, :, :, p + a], chain.kv[:, :, :, p + j])
+
+
+def test_chain_shaped_tree_is_the_ordinary_sub_sequence():
+    cfg = dict(SMALL, n_layers=2)
+    layers = si.make_layers(cfg, seed=13, weight_std=0.15)
+    hidden = si.make_hidden(cfg, seed=13, n_tokens=14)
+    a = oracle.OracleStage(cfg, layers, 14)
+    b = oracle.OracleStage(cfg, layers, 14)
+    a.prefill_chunk(hidden[:4]); b.prefill_chunk(hidden[:4])
+    oa = a.prefill_chunk(hidden[4:])
+    ob = b.prefill_tree(hidden[4:], np.arange(-1, 9))
+    np.testing.assert_array_equal(oa, ob)
+    np.testing.assert_array_equal(a.kv, b.kv)
+
+
+def test_siblings_do_not_see_each_other():
+    """A star (every candidate follows the prefix directly) is n independent one-token calls at the same position."""
+    cfg = dict(SMALL, n_layers=2)
+    layers = si.make_layers(cfg, seed=14, weight_std=0.15)
+    p, n = 6, 5
+    hidden = si.make_hidden(cfg, seed=14, n_tokens=p + n)
+    st = oracle.OracleStage(cfg, layers, p + n)
+    st.prefill_chunk(hidden[:p])
+    out = st.prefill_tree(hidden[p:], [-1] * n)
+    for t in range(n):
+        one = oracle.OracleStage(cfg, layers, p + 1)
+        one.prefill_chunk(hidden[:p])
+        np.testing.assert_array_equal(out[t], one.prefill_chunk(hidden[p + t:p + t + 1])[0])
+
+
+def test_keep_leaves_the_cache_of_the_accepted_path():
+    """Sec. V-A step 5: after the rejected candidates are removed the cache is that of the accepted tokens alone."""
+    cfg = dict(SMALL, n_layers=2)
+    layers = si.make_layers(cfg, seed=15, weight_std=0.15)
+    p, n = 5, 16
+    parents = si.make_token_tree(n, seed=15)
+    hidden = si.make_hidden(cfg, seed=15, n_tokens=p + n + 3)
+    _, anc = tree_depths_and_ancestors(parents)
+    leaf = max(range(n), key=lambda t: len(anc[t]))
+    path = anc[leaf] + [leaf]
+    st = oracle.OracleStage(cfg, layers, p + n + 3)
+    st.prefill_chunk(hidden[:p])
+    st.prefill_tree(hidden[p:p + n], parents)
+    st.keep(p, path)
+    assert st.kv_len == p + len(path)
+    nxt = st.prefill_chunk(hidden[p + n:])
+    ref = oracle.OracleStage(cfg, layers, p + n + 3)
+    ref.prefill_chunk(hidden[:p])
+    ref.prefill_chunk(hidden[p:p + n][path])
+    np.testing.assert_array_equal(nxt, ref.prefill_chunk(hidden[p + n:]))
+    np.testing.assert_array_equal(st.kv[:, :, :, :st.kv_len], ref.kv[:, :, :, :ref.kv_len])
+
+
+def test_tree_oracle_rejects_a_parent_that_is_not_an_earlier_token():
+    cfg = dict(SMALL, n_layers=1)
+    layers = si.make_layers(cfg, seed=16)
+    st = oracle.OracleStage(cfg, layers, 8)
+    hidden = si.make_hidden(cfg, seed=16, n_tokens=3)
+    for bad in ([-1, 1, 0], [-1, 0, 2], [-2, 0, 0], [0, 0, 0]):
+        with pytest.raises(RuntimeError):
+            st.prefill_tree(hidden, bad)
