@@ -168,6 +168,21 @@ JUP_API jup_status_t jup_kv_reset(jup_kv_t *kv);
  */
 JUP_API jup_status_t jup_kv_truncate(jup_kv_t *kv, int32_t new_len);
 
+/*
+ * Removal of rejected candidates after a token-tree step (Sec. V-A step 5; see jup_stage_prefill_tree()):
+ * the cache keeps its first base_len entries and, behind them, the n_keep entries that sat at
+ * base_len + slots[0], base_len + slots[1], ... (moved to base_len, base_len + 1, ...); all others are
+ * dropped and the length becomes base_len + n_keep.  For the accepted root-to-node path of a tree
+ * (slots = the path's token indices) the moved keys are already rotated for their new positions, so the
+ * cache is then exactly the one an ordinary call on the accepted tokens would have left.
+ *   slots   HOST array [n_keep], strictly increasing, 0 <= slots[j], base_len + slots[j] < length;
+ *           0 <= n_keep <= JUP_MAX_TREE_TOKENS
+ *   stream  hipStream_t the copies are enqueued on (they must follow the call that wrote the entries)
+ * Errors: JUP_EINVAL (NULL, n_keep out of range, slots not increasing), JUP_EPOS (base_len or a slot outside
+ * the cache, inside a fork's shared prefix, or below the n_shared of a live fork), JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_kv_keep(jup_kv_t *kv, int32_t base_len, int32_t n_keep, const int32_t *slots, void *stream);
+
 JUP_API int32_t jup_kv_len(const jup_kv_t *kv);      /* positions currently valid; -1 for NULL */
 JUP_API int32_t jup_kv_capacity(const jup_kv_t *kv); /* max_positions; -1 for NULL */
 
@@ -227,6 +242,31 @@ JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hid
 JUP_API jup_status_t jup_stage_prefill_branches(jup_stage_t *stage, int32_t n_branches, const void *hidden_in,
                                         int32_t n_tokens, const int32_t *pos_offsets, jup_kv_t *const *kvs,
                                         void *hidden_out, void *stream);
+
+/*
+ * The same stage forward over the candidate tokens of one speculative decoding step (Sec. V-A, steps 3-5:
+ * all candidates go through the model in one forward pass, their intermediate results are stored in the
+ * KVCache, and the rejected ones are removed afterwards).  The candidates form a token tree, the drafting
+ * scheme the paper evaluates with (Medusa's): token t continues token parents[t] of the same call, or the
+ * cached sequence itself when parents[t] is -1.
+ *   parents     HOST array [n_tokens], parents[t] in {-1, 0 .. t-1}
+ *   n_tokens    0 .. JUP_MAX_TREE_TOKENS (and <= the stage's max_chunk_tokens)
+ *   others      as jup_stage_prefill_chunk()
+ * Token t
+ *   - is rotated at position pos_offset + depth(t)   (depth = number of ancestors inside the call),
+ *   - is stored in cache entry pos_offset + t,
+ *   - attends to the entries 0 .. pos_offset-1, to its ancestors' entries and to its own.
+ * Row t of hidden_out is therefore what an ordinary call on the tokens of t's root-to-node path would give
+ * for its last token; a chain (parents[t] = t-1) is exactly jup_stage_prefill_chunk().  On success the cache
+ * length is pos_offset + n_tokens; the caller then verifies the candidates and calls jup_kv_keep() with the
+ * accepted path (or jup_kv_truncate() to drop them all).
+ * Errors: as jup_stage_prefill_chunk(), plus JUP_EINVAL for n_tokens > JUP_MAX_TREE_TOKENS, parents == NULL
+ * or a parent index outside [-1, t).
+ */
+#define JUP_MAX_TREE_TOKENS 64
+JUP_API jup_status_t jup_stage_prefill_tree(jup_stage_t *stage, const void *hidden_in, int32_t n_tokens,
+                                    int32_t pos_offset, const int32_t *parents, jup_kv_t *kv, void *hidden_out,
+                                    void *stream);
 
 /* ---- per-kernel timing (benchmarks) ----------------------------------------------------------- */
 

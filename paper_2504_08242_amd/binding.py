@@ -59,12 +59,14 @@ def lib():
             "jup_kv_fork": (i32, [vp, i32, i32, vp, sz, ctypes.POINTER(vp)]),
             "jup_kv_reset": (i32, [vp]),
             "jup_kv_truncate": (i32, [vp, i32]),
+            "jup_kv_keep": (i32, [vp, i32, i32, ctypes.POINTER(i32), vp]),
             "jup_kv_len": (i32, [vp]),
             "jup_kv_capacity": (i32, [vp]),
             "jup_kv_check_append": (i32, [vp, i32, i32]),
             "jup_kv_destroy": (i32, [vp]),
             "jup_stage_prefill_chunk": (i32, [vp, vp, i32, i32, vp, vp, vp]),
             "jup_stage_prefill_branches": (i32, [vp, i32, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), vp, vp]),
+            "jup_stage_prefill_tree": (i32, [vp, vp, i32, i32, ctypes.POINTER(i32), vp, vp, vp]),
             "jup_stage_trace": (i32, [vp, i32, i32]),
             "jup_stage_trace_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32),
                                            ctypes.POINTER(i32)]),
@@ -149,6 +151,12 @@ class KvCache:
     def truncate(self, new_len):
         _check(lib().jup_kv_truncate(self.handle, int(new_len)))
 
+    def keep(self, base_len, slots, stream=None):
+        """Keeps the first base_len entries and, behind them, the entries base_len + slots[j] (a tree's accepted path)."""
+        k = len(slots)
+        arr = (ctypes.c_int32 * max(1, k))(*[int(x) for x in slots])
+        _check(lib().jup_kv_keep(self.handle, int(base_len), k, arr, _stream_handle(stream)))
+
     def check_append(self, n_tokens, pos_offset):
         return int(lib().jup_kv_check_append(self.handle, int(n_tokens), int(pos_offset)))
 
@@ -205,6 +213,20 @@ class Stage:
         _check(lib().jup_stage_prefill_chunk(self.handle, ctypes.c_void_p(hidden_in.data_ptr()), n, int(pos_offset),
                                              kv.handle, ctypes.c_void_p(hidden_out.data_ptr()),
                                              _stream_handle(stream)))
+        return hidden_out
+
+    def prefill_tree(self, hidden_in, pos_offset, parents, kv, hidden_out=None, stream=None):
+        """hidden_in: [n_tokens, d_model] candidate tokens of a token tree; parents[t] is -1 or an earlier row."""
+        import torch
+        n = int(hidden_in.shape[0])
+        assert len(parents) == n
+        assert hidden_in.is_contiguous() and hidden_in.dtype == _torch_dtype(self.dtype)
+        if hidden_out is None:
+            hidden_out = torch.empty_like(hidden_in)
+        par = (ctypes.c_int32 * max(1, n))(*[int(x) for x in parents])
+        _check(lib().jup_stage_prefill_tree(self.handle, ctypes.c_void_p(hidden_in.data_ptr()), n, int(pos_offset), par,
+                                            kv.handle, ctypes.c_void_p(hidden_out.data_ptr()),
+                                            _stream_handle(stream)))
         return hidden_out
 
     def prefill_branches(self, hidden_in, n_tokens, pos_offsets, kvs, hidden_out=None, stream=None):

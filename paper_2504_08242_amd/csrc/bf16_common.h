@@ -113,8 +113,9 @@ hipError_t gemm_configure();  // raises the dynamic-LDS limit of every instantia
 // ---- attention (bf16_attention.hip) ---------------------------------------------------------------
 // o is written in the tiled layout (it is the output projection's A operand)
 hipError_t attention_configure();  // raises the dynamic-LDS limit (once per process)
+// tree (device pointer, may be null): inside the chunk a query sees the tokens of its row of the table only
 void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
-                            int layer, hipStream_t s);
+                            int layer, hipStream_t s, const TreeTable* tree = nullptr);
 // n_branches chunks of n tokens each (rows b*n .. b*n+n-1 of q and o), every one against its own cache
 void launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_model, int n_heads,
                              const BranchTable* branches, int layer, hipStream_t s);
@@ -124,6 +125,7 @@ void launch_pack_qkv(u16* dst, const u16* wq, const u16* wk, const u16* wv, int 
 void launch_pack_gate_up(u16* dst, const u16* wg, const u16* wu, int d, int f, hipStream_t s);
 void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s);
 void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s);
+void launch_rope_table_tree(float2* tab, int n, int pos0, const TreeTable* tree, float theta, hipStream_t s);
 void launch_rope_table_branches(float2* tab, int n_rows, const BranchTable* branches, float theta, hipStream_t s);
 void launch_write_branch_table(const BranchTable& host_table, BranchTable* dst, hipStream_t s);
 // x32 <- (hidden_in ? hidden_in : x32) + sum_s partial[s];  xn <- rmsnorm(x32) * g (if g), tiled layout;

@@ -36,8 +36,10 @@ hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* lay
 // branch b are appended to and attend over cache bt->kv[b] from position bt->pos0[b] (pos and kv are unused).
 // Everything that is not attention or cache traffic sees one [n, d] activation matrix either way, so the
 // stage's weights are streamed once for all branches.
+// tree != nullptr (host table, bt == nullptr): the n tokens are a token tree; only the rotary positions
+// (pos + depth) and the mask inside the chunk differ from an ordinary chunk.
 hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int pos, const KvView& kv,
-                        void* hidden_out, hipStream_t s, const BranchTable* bt) {
+                        void* hidden_out, hipStream_t s, const BranchTable* bt, const TreeTable* tree) {
     const jup_stage_config_t& c = st.cfg;
     const int d = c.d_model, f = c.d_ffn, H = c.n_heads;
     char* ws = (char*)st.workspace;
@@ -52,10 +54,15 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
 
     if (c.n_layers == 0) return hipMemcpyAsync(hidden_out, hidden_in, (size_t)n * d * 2, hipMemcpyDeviceToDevice, s);
     const BranchTable* bt_dev = nullptr;
+    const TreeTable* tree_dev = nullptr;
     if (bt) {
         bt_dev = (const BranchTable*)(ws + st.wl.branches);
         launch_write_branch_table(*bt, (BranchTable*)(ws + st.wl.branches), s);
         launch_rope_table_branches(rope, n, bt_dev, c.rope_theta, s);
+    } else if (tree) {
+        tree_dev = (const TreeTable*)(ws + st.wl.tree);
+        launch_write_tree_table(*tree, (TreeTable*)(ws + st.wl.tree), s);
+        launch_rope_table_tree(rope, n, pos, tree_dev, c.rope_theta, s);
     } else {
         launch_rope_table(rope, n, pos, c.rope_theta, s);
     }
@@ -85,7 +92,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         {
             TraceScope ts(st, JUP_K_ATTENTION, s);
             if (bt) launch_branch_attention(q, o, bt->n_tok, bt->n_branches, d, H, bt_dev, l, s);
-            else launch_chunk_attention(q, o, n, d, H, pos, kv, l, s);
+            else launch_chunk_attention(q, o, n, d, H, pos, kv, l, s, tree_dev);
         }
         {
             TraceScope ts(st, JUP_K_GEMM_O, s);

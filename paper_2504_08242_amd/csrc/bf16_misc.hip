@@ -46,6 +46,16 @@ __global__ void rope_table(float2* __restrict__ tab, int n, int pos0, float thet
     tab[gid] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
+// Token-tree call: token t sits tree->depth[t] positions behind the cached sequence.
+__global__ void rope_table_tree(float2* __restrict__ tab, int n, int pos0, const TreeTable* __restrict__ tree,
+                                float theta) {
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= n * 64) return;
+    const int i = gid & 63, t = gid >> 6;
+    const double ang = (double)(pos0 + tree->depth[t]) * pow((double)theta, -(double)i / 64.0);
+    tab[gid] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
 // Batched-branch call: row r is token r % n_tok of branch r / n_tok.
 __global__ void rope_table_branches(float2* __restrict__ tab, int n_rows, const BranchTable* __restrict__ bt,
                                     float theta) {
@@ -148,6 +158,9 @@ void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s)
 }
 void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s) {
     hipLaunchKernelGGL(rope_table, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, theta);
+}
+void launch_rope_table_tree(float2* tab, int n, int pos0, const TreeTable* tree, float theta, hipStream_t s) {
+    hipLaunchKernelGGL(rope_table_tree, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, tree, theta);
 }
 void launch_rope_table_branches(float2* tab, int n_rows, const BranchTable* branches, float theta, hipStream_t s) {
     hipLaunchKernelGGL(rope_table_branches, dim3((n_rows * 64 + 255) / 256), dim3(256), 0, s, tab, n_rows, branches,

@@ -86,6 +86,7 @@ WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T) {
     w.rope = off; off += align_up(t * (size_t)(c.head_dim / 2) * 8);
     w.partial = off; off += f32 ? 0 : align_up(8 * t * d * 4);
     w.branches = off; off += f32 ? 0 : align_up(sizeof(BranchTable));
+    w.tree = off; off += align_up(sizeof(TreeTable));
     w.total = off;
     return w;
 }
@@ -327,6 +328,41 @@ jup_status_t jup_kv_truncate(jup_kv_t* kv, int32_t new_len) {
     return JUP_OK;
 }
 
+jup_status_t jup_kv_keep(jup_kv_t* kv, int32_t base_len, int32_t n_keep, const int32_t* slots, void* stream) {
+    const char* me = "jup_kv_keep";
+    if (!kv) return fail(JUP_EINVAL, "%s: kv is NULL", me);
+    if (n_keep < 0 || n_keep > JUP_MAX_TREE_TOKENS)
+        return fail(JUP_EINVAL, "%s: n_keep=%d is outside 0..%d", me, n_keep, JUP_MAX_TREE_TOKENS);
+    if (n_keep > 0 && !slots) return fail(JUP_EINVAL, "%s: slots is NULL", me);
+    if (base_len < 0 || base_len > kv->len)
+        return fail(JUP_EPOS, "%s: base_len=%d outside [0, %d]", me, base_len, kv->len);
+    if (base_len < kv->n_shared)
+        return fail(JUP_EPOS, "%s: base_len=%d cuts into the shared prefix of %d", me, base_len, kv->n_shared);
+    if (kv->n_children > 0 && base_len < kv->max_child_shared)
+        return fail(JUP_EPOS, "%s: live forks share the first %d positions", me, kv->max_child_shared);
+    jup::KeepList list{};
+    list.n = n_keep;
+    bool moves = false;
+    for (int j = 0; j < n_keep; ++j) {
+        if (slots[j] < 0 || (j > 0 && slots[j] <= slots[j - 1]))
+            return fail(JUP_EINVAL, "%s: slots must be non-negative and strictly increasing (slots[%d]=%d)", me, j,
+                        slots[j]);
+        if ((int64_t)base_len + slots[j] >= kv->len)
+            return fail(JUP_EPOS, "%s: slots[%d]=%d lies behind the %d cached positions", me, j, slots[j], kv->len);
+        list.slots[j] = slots[j];
+        moves |= slots[j] != j;
+    }
+    if (moves) {
+        const jup_stage_config_t& c = kv->cfg;
+        jup::launch_kv_keep(kv->buf, kv->max_positions - kv->n_shared, c.n_layers * 2 * c.n_heads,
+                            c.head_dim * (int)elem_size(c), base_len - kv->n_shared, list, (hipStream_t)stream);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
+    }
+    kv->len = base_len + n_keep;
+    return JUP_OK;
+}
+
 int32_t jup_kv_len(const jup_kv_t* kv) { return kv ? kv->len : -1; }
 int32_t jup_kv_capacity(const jup_kv_t* kv) { return kv ? kv->max_positions : -1; }
 
@@ -375,42 +411,74 @@ jup::KvView view_of(const jup_kv_t* kv) {
 
 extern "C" {
 
-jup_status_t jup_stage_prefill_chunk(jup_stage_t* stage, const void* hidden_in, int32_t n_tokens,
-                                     int32_t pos_offset, jup_kv_t* kv, void* hidden_out, void* stream) {
-    if (!stage) return fail(JUP_EINVAL, "jup_stage_prefill_chunk: stage is NULL");
-    if (!kv) return fail(JUP_EINVAL, "jup_stage_prefill_chunk: kv is NULL");
-    if (!same_shape(stage->cfg, kv->cfg))
-        return fail(JUP_EINVAL, "jup_stage_prefill_chunk: the cache was made for another configuration");
+}  // extern "C"
+
+namespace {
+// One chunk, ordinary (parents == NULL) or a token tree.
+jup_status_t prefill_one(const char* me, jup_stage_t* stage, const void* hidden_in, int32_t n_tokens,
+                         int32_t pos_offset, const int32_t* parents, bool is_tree, jup_kv_t* kv, void* hidden_out,
+                         void* stream) {
+    if (!stage) return fail(JUP_EINVAL, "%s: stage is NULL", me);
+    if (!kv) return fail(JUP_EINVAL, "%s: kv is NULL", me);
+    if (!same_shape(stage->cfg, kv->cfg)) return fail(JUP_EINVAL, "%s: the cache was made for another configuration", me);
     jup_status_t rc = jup_kv_check_append(kv, n_tokens, pos_offset);
     if (rc != JUP_OK) {
         char tmp[400];
         snprintf(tmp, sizeof(tmp), "%s", g_err);
-        return fail(rc, "jup_stage_prefill_chunk: %s", tmp);
+        return fail(rc, "%s: %s", me, tmp);
     }
     if (n_tokens > stage->max_chunk_tokens)
-        return fail(JUP_ECAP, "jup_stage_prefill_chunk: n_tokens=%d exceeds the stage's max_chunk_tokens=%d", n_tokens,
+        return fail(JUP_ECAP, "%s: n_tokens=%d exceeds the stage's max_chunk_tokens=%d", me, n_tokens,
                     stage->max_chunk_tokens);
+    jup::TreeTable tree{};
+    if (is_tree) {
+        if (n_tokens > JUP_MAX_TREE_TOKENS)
+            return fail(JUP_EINVAL, "%s: n_tokens=%d exceeds the %d tokens of a tree", me, n_tokens, JUP_MAX_TREE_TOKENS);
+        if (n_tokens > 0 && !parents) return fail(JUP_EINVAL, "%s: parents is NULL", me);
+        tree.n = n_tokens;
+        for (int t = 0; t < n_tokens; ++t) {
+            const int par = parents[t];
+            if (par < -1 || par >= t)
+                return fail(JUP_EINVAL, "%s: parents[%d]=%d is not -1 or an earlier token", me, t, par);
+            tree.depth[t] = par < 0 ? 0 : tree.depth[par] + 1;
+            tree.sees[t] = (par < 0 ? 0ull : tree.sees[par]) | (1ull << t);
+        }
+    }
     if (kv->parent && kv->parent->len < kv->n_shared)
-        return fail(JUP_EPOS, "jup_stage_prefill_chunk: the parent cache holds %d positions, fewer than the %d shared",
-                    kv->parent->len, kv->n_shared);
+        return fail(JUP_EPOS, "%s: the parent cache holds %d positions, fewer than the %d shared", me, kv->parent->len,
+                    kv->n_shared);
     if (n_tokens == 0) {
         kv->len = pos_offset;
         return JUP_OK;
     }
-    if (!hidden_in || !hidden_out)
-        return fail(JUP_EINVAL, "jup_stage_prefill_chunk: hidden_in and hidden_out must not be NULL");
+    if (!hidden_in || !hidden_out) return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must not be NULL", me);
 
     const jup::KvView view = view_of(kv);
-
+    const jup::TreeTable* tt = is_tree ? &tree : nullptr;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     if (stage->cfg.dtype == JUP_F32)
-        e = jup::f32_forward(*stage, (const float*)hidden_in, n_tokens, pos_offset, view, (float*)hidden_out, s);
+        e = jup::f32_forward(*stage, (const float*)hidden_in, n_tokens, pos_offset, view, (float*)hidden_out, s, tt);
     else
-        e = jup::bf16_forward(*stage, hidden_in, n_tokens, pos_offset, view, hidden_out, s);
-    if (e != hipSuccess) return fail(JUP_EDEVICE, "jup_stage_prefill_chunk: %s", hipGetErrorString(e));
+        e = jup::bf16_forward(*stage, hidden_in, n_tokens, pos_offset, view, hidden_out, s, nullptr, tt);
+    if (e != hipSuccess) return fail(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
     kv->len = pos_offset + n_tokens;
     return JUP_OK;
+}
+}  // namespace
+
+extern "C" {
+
+jup_status_t jup_stage_prefill_chunk(jup_stage_t* stage, const void* hidden_in, int32_t n_tokens,
+                                     int32_t pos_offset, jup_kv_t* kv, void* hidden_out, void* stream) {
+    return prefill_one("jup_stage_prefill_chunk", stage, hidden_in, n_tokens, pos_offset, nullptr, false, kv,
+                       hidden_out, stream);
+}
+
+jup_status_t jup_stage_prefill_tree(jup_stage_t* stage, const void* hidden_in, int32_t n_tokens, int32_t pos_offset,
+                                    const int32_t* parents, jup_kv_t* kv, void* hidden_out, void* stream) {
+    return prefill_one("jup_stage_prefill_tree", stage, hidden_in, n_tokens, pos_offset, parents, true, kv,
+                       hidden_out, stream);
 }
 
 jup_status_t jup_stage_prefill_branches(jup_stage_t* stage, int32_t n_branches, const void* hidden_in,

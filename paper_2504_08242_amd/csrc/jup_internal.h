@@ -37,6 +37,7 @@ struct WorkspaceLayout {
     size_t rope;  // [T, head_dim/2] float2 (cos, sin) of the chunk's positions
     size_t partial;  // bf16 only: [8][T, d] fp32 K-split partial sums of the O / down projections
     size_t branches; // bf16 only: BranchTable of a batched-branch call
+    size_t tree;     // TreeTable of a token-tree call
     size_t total;
 };
 WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T);
@@ -58,6 +59,22 @@ struct BranchTable {
     int32_t n_branches, n_tok;
     int32_t pos0[kMaxBranches];
     KvView kv[kMaxBranches];
+};
+
+// Token-tree call: token t of the chunk is rotated at pos0 + depth[t], stored in slot pos0 + t, and attends,
+// inside the chunk, to the tokens whose bit is set in sees[t] (its ancestors and itself; bit j = token j).
+constexpr int kMaxTreeTokens = JUP_MAX_TREE_TOKENS;
+static_assert(kMaxTreeTokens <= 64, "one 64-bit word of visibility per token");
+struct TreeTable {
+    int32_t n;
+    int32_t depth[kMaxTreeTokens];
+    unsigned long long sees[kMaxTreeTokens];
+};
+
+// jup_kv_keep(): entry base + slots[j] of every (layer, K|V, head) plane moves to entry base + j.
+struct KeepList {
+    int32_t n;
+    int32_t slots[kMaxTreeTokens];
 };
 
 }  // namespace jup
@@ -114,11 +131,19 @@ struct TraceScope {
 
 // ---- check-mode (fp32) path: kernels_f32.hip ------------------------------------------------------
 hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int pos, const KvView& kv,
-                       float* hidden_out, hipStream_t s);
+                       float* hidden_out, hipStream_t s, const TreeTable* tree = nullptr);
 
 // ---- matrix-core (bf16) path: kernels_bf16.hip ----------------------------------------------------
 hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s);
 hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int pos, const KvView& kv,
-                        void* hidden_out, hipStream_t s, const BranchTable* branches = nullptr);
+                        void* hidden_out, hipStream_t s, const BranchTable* branches = nullptr,
+                        const TreeTable* tree = nullptr);
+
+// ---- cache and table helpers: kv_ops.hip --------------------------------------------------------------
+// The tables of a call travel as kernel arguments and are parked in the workspace, where the kernels of the
+// call read them (no host-to-device copy on the hot path).
+void launch_write_tree_table(const TreeTable& host_table, TreeTable* dst, hipStream_t s);
+// own: the cache's own buffer; own_cap: its slots; base: first destination slot in that buffer
+void launch_kv_keep(void* own, int own_cap, int n_planes, int row_bytes, int base, const KeepList& list, hipStream_t s);
 
 }  // namespace jup

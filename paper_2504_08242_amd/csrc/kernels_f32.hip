@@ -90,17 +90,18 @@ __device__ inline const float* kv_row(const KvView& kv, int layer, int which, in
     return (const float*)kv.own + (plane * kv.own_cap + (size_t)(pos - kv.n_shared)) * dh;
 }
 
-// Rotates q and k of token t / head h in the fused [n, 3d] buffer at absolute position pos0 + t and
-// stores k (rotated) and v into the cache.  One thread per (t, h, i < dh/2).
+// Rotates q and k of token t / head h in the fused [n, 3d] buffer at absolute position pos0 + t (token
+// tree: pos0 + depth of t) and stores k (rotated) and v into cache entry pos0 + t.  One thread per
+// (t, h, i < dh/2).
 __global__ void f32_rope_append(float* __restrict__ qkv, int n, int d, int n_heads, int dh, int pos0, float theta,
-                                KvView kv, int layer) {
+                                KvView kv, int layer, const TreeTable* __restrict__ tree) {
     const int half = dh / 2;
     const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= (long long)n * n_heads * half) return;
     const int i = (int)(gid % half);
     const int h = (int)((gid / half) % n_heads);
     const int t = (int)(gid / ((long long)half * n_heads));
-    const int pos = pos0 + t;
+    const int pos = pos0 + (tree ? tree->depth[t] : t), slot = pos0 + t;
     const double ang = (double)pos * pow((double)theta, -2.0 * (double)i / (double)dh);
     const float c = (float)cos(ang), s = (float)sin(ang);
     float* q = qkv + (size_t)t * 3 * d + (size_t)h * dh;
@@ -110,8 +111,8 @@ __global__ void f32_rope_append(float* __restrict__ qkv, int n, int d, int n_hea
     q[i] = qa * c - qb * s;
     q[i + half] = qb * c + qa * s;
     const float ka = k[i], kb = k[i + half];
-    float* kc = kv_slot(kv, layer, 0, h, n_heads, dh, pos);
-    float* vc = kv_slot(kv, layer, 1, h, n_heads, dh, pos);
+    float* kc = kv_slot(kv, layer, 0, h, n_heads, dh, slot);
+    float* vc = kv_slot(kv, layer, 1, h, n_heads, dh, slot);
     kc[i] = ka * c - kb * s;
     kc[i + half] = kb * c + ka * s;
     vc[i] = v[i];
@@ -119,9 +120,11 @@ __global__ void f32_rope_append(float* __restrict__ qkv, int n, int d, int n_hea
 }
 
 // One wave per (query t, head h): softmax over the cached keys 0..pos0+t (running max / running sum),
-// weighted sum of the cached values.  Lanes split head_dim (up to 256).
+// weighted sum of the cached values.  Lanes split head_dim (up to 256).  Token tree: of the chunk's own
+// entries pos0.. only those of the query's ancestors and its own are visible.
 __global__ __launch_bounds__(kWave) void f32_attention(const float* __restrict__ qkv, float* __restrict__ o, int d,
-                                                       int n_heads, int dh, int pos0, KvView kv, int layer) {
+                                                       int n_heads, int dh, int pos0, KvView kv, int layer,
+                                                       const TreeTable* __restrict__ tree) {
     const int t = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
     const float* q = qkv + (size_t)t * 3 * d + (size_t)h * dh;
     float qr[4], acc[4] = {0.f, 0.f, 0.f, 0.f};
@@ -130,7 +133,9 @@ __global__ __launch_bounds__(kWave) void f32_attention(const float* __restrict__
     const float scale = 1.0f / sqrtf((float)dh);
     float m = -INFINITY, z = 0.f;
     const int n_keys = pos0 + t + 1;
+    const unsigned long long sees = tree ? tree->sees[t] : ~0ull;
     for (int j = 0; j < n_keys; ++j) {
+        if (j >= pos0 && !((sees >> ((j - pos0) & 63)) & 1)) continue;  // j - pos0 <= t < 64 in a tree call
         const float* kr = kv_row(kv, layer, 0, h, n_heads, dh, j);
         const float* vr = kv_row(kv, layer, 1, h, n_heads, dh, j);
         float part = 0.f;
@@ -172,7 +177,7 @@ void gemm(const float* A, int lda, const float* W, float* C, const float* R, int
 }  // namespace
 
 hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int pos, const KvView& kv,
-                       float* hidden_out, hipStream_t s) {
+                       float* hidden_out, hipStream_t s, const TreeTable* tree) {
     const jup_stage_config_t& c = st.cfg;
     const int d = c.d_model, f = c.d_ffn, H = c.n_heads, dh = c.head_dim;
     char* ws = (char*)st.workspace;
@@ -183,6 +188,11 @@ hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int p
     float* gu = (float*)(ws + st.wl.gu);
     float* act = (float*)(ws + st.wl.act);
 
+    const TreeTable* tree_dev = nullptr;
+    if (tree) {  // host table -> workspace
+        tree_dev = (const TreeTable*)(ws + st.wl.tree);
+        launch_write_tree_table(*tree, (TreeTable*)(ws + st.wl.tree), s);
+    }
     hipError_t e = hipMemcpyAsync(x, hidden_in, (size_t)n * d * 4, hipMemcpyDeviceToDevice, s);
     if (e != hipSuccess) return e;
     for (int l = 0; l < c.n_layers; ++l) {
@@ -199,9 +209,9 @@ hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int p
         {
             const long long work = (long long)n * H * (dh / 2);
             hipLaunchKernelGGL(f32_rope_append, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, qkv, n, d, H, dh,
-                               pos, c.rope_theta, kv, l);
+                               pos, c.rope_theta, kv, l, tree_dev);
         }
-        hipLaunchKernelGGL(f32_attention, dim3(n, H), dim3(kWave), 0, s, qkv, o, d, H, dh, pos, kv, l);
+        hipLaunchKernelGGL(f32_attention, dim3(n, H), dim3(kWave), 0, s, qkv, o, d, H, dh, pos, kv, l, tree_dev);
         gemm(o, d, wo, x, x, d, n, d, d, s);  // x <- x + o Wo^T (each element read and written by one thread)
         hipLaunchKernelGGL(f32_rmsnorm, dim3(n), dim3(256), 0, s, x, g2, xn, d, c.rms_eps);
         gemm(xn, d, wgu, gu, nullptr, 2 * f, n, 2 * f, d, s);

@@ -50,6 +50,13 @@ class Pair:
         torch.cuda.synchronize()
         return to_numpy(y)
 
+    def gpu_tree(self, hidden_np, pos, parents, kv=None):
+        import torch
+        x = torch.from_numpy(hidden_np).to(device="cuda:0", dtype=self.td)
+        y = self.stage.prefill_tree(x, pos, parents, kv if kv is not None else self.kv)
+        torch.cuda.synchronize()
+        return to_numpy(y)
+
     def run_both(self, hidden_np, chunks, reset=True):
         """Feeds the chunks to both sides; returns (gpu_out, oracle_out) concatenated over the chunks."""
         if reset:

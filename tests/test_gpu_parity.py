@@ -158,6 +158,138 @@ def test_f32_truncate_after_rejected_candidates_equals_never_appending_them():
     assert np.array_equal(kv_a, kv_bits(p.kv)[:, :, :, :32])
 
 
+# ------------------------------------------------------------------------------------------------
+# token tree of a speculative step (Sec. V-A): candidates verified in one call, rejected ones removed
+# ------------------------------------------------------------------------------------------------
+def tree_paths(parents):
+    paths = []
+    for t, par in enumerate(parents):
+        paths.append((paths[par] if par >= 0 else []) + [t])
+    return paths
+
+
+def run_tree_case(p, n_prefix, n_tree, seed, n_after=7):
+    """Prefix, then a token tree, then keep the deepest path and go on: GPU against the oracle at every step."""
+    parents = si.make_token_tree(n_tree, seed)
+    paths = tree_paths(parents)
+    h = p.hidden(n_prefix + n_tree + n_after)
+    pre, cand, after = h[:n_prefix], h[n_prefix:n_prefix + n_tree], h[n_prefix + n_tree:]
+    p.kv.reset(); p.oracle.reset()
+    fill_sentinel(p.kv)
+    if n_prefix:
+        p.gpu_chunk(pre, 0)
+        p.oracle.prefill_chunk(pre, 0)
+    before = kv_bits(p.kv)
+    g = p.gpu_tree(cand, n_prefix, parents)
+    o = p.oracle.prefill_tree(cand, parents, n_prefix)
+    p.check(g, o, "tree output")
+    assert len(p.kv) == n_prefix + n_tree
+    after_bits = kv_bits(p.kv)
+    assert_only_slots_changed(before, after_bits, n_prefix, n_prefix + n_tree, "tree slots")
+    p.check(p.kv_gpu()[:, :, :, :n_prefix + n_tree], p.oracle.kv[:, :, :, :n_prefix + n_tree], "tree cache")
+
+    # accept the deepest path; the kept entries are moved bit for bit, everything below base stays
+    path = max(paths, key=len)
+    assert len(path) >= 3 and path != list(range(len(path))), "the case must move entries"
+    p.kv.keep(n_prefix, path)
+    p.oracle.keep(n_prefix, path)
+    assert len(p.kv) == n_prefix + len(path) == p.oracle.kv_len
+    kept = kv_bits(p.kv)
+    assert np.array_equal(kept[:, :, :, :n_prefix], after_bits[:, :, :, :n_prefix])
+    for j, t in enumerate(path):
+        assert np.array_equal(kept[:, :, :, n_prefix + j], after_bits[:, :, :, n_prefix + t]), (j, t)
+    # ... and the sequence continues as if only the accepted tokens had ever been fed
+    g2 = p.gpu_chunk(after, len(p.kv))
+    o2 = p.oracle.prefill_chunk(after, p.oracle.kv_len)
+    p.check(g2, o2, "chunk after keep")
+    return parents, paths, cand, g
+
+
+def test_f32_token_tree_matches_the_oracle_and_keep_moves_the_accepted_path():
+    p = Pair(si.TINY, "f32", seed=21, max_positions=128, max_chunk_tokens=64)
+    run_tree_case(p, n_prefix=37, n_tree=64, seed=21)
+    run_tree_case(p, n_prefix=0, n_tree=11, seed=22)
+
+
+def test_f32_tree_node_equals_the_ordinary_call_on_its_path():
+    """The property verification relies on, on the GPU alone: row t = last row of the chain call on t's path."""
+    p = Pair(si.TINY, "f32", seed=23, max_positions=96, max_chunk_tokens=64)
+    n_prefix, n_tree = 19, 24
+    parents = si.make_token_tree(n_tree, 23)
+    h = p.hidden(n_prefix + n_tree)
+    p.gpu_chunk(h[:n_prefix], 0)
+    g = p.gpu_tree(h[n_prefix:], n_prefix, parents)
+    for t, path in enumerate(tree_paths(parents)):
+        if t % 5 and len(path) < 4:
+            continue
+        p.kv.truncate(n_prefix)
+        ref = p.gpu_chunk(h[n_prefix:][path], n_prefix)
+        assert np.max(np.abs(g[t] - ref[-1])) <= 2e-5, t   # same arithmetic, other kernel shapes and orders
+
+
+def test_f32_chain_shaped_tree_is_bitwise_the_ordinary_chunk():
+    p = Pair(si.TINY, "f32", seed=24, max_positions=64, max_chunk_tokens=64)
+    h = p.hidden(50)
+    p.gpu_chunk(h[:10], 0)
+    a = p.gpu_chunk(h[10:], 10)
+    kv_a = kv_bits(p.kv)
+    p.kv.truncate(10)
+    b = p.gpu_tree(h[10:], 10, list(range(-1, 39)))
+    assert np.array_equal(a, b)
+    assert np.array_equal(kv_a, kv_bits(p.kv))
+
+
+def test_tree_and_keep_argument_errors_leave_the_cache_untouched():
+    p = Pair(si.TINY, "f32", seed=25, max_positions=80, max_chunk_tokens=80)
+    h = p.hidden(70)
+    p.gpu_chunk(h[:8], 0)
+    E = jb.JupiterError
+    for parents, status in (([-1, 1, 0], jb.JUP_EINVAL), ([0, 0, 0], jb.JUP_EINVAL), ([-2, 0, 1], jb.JUP_EINVAL)):
+        with pytest.raises(E) as ei:
+            p.gpu_tree(h[8:11], 8, parents)
+        assert ei.value.status == status and len(p.kv) == 8
+    with pytest.raises(E) as ei:                      # more than the 64 tokens of a tree
+        p.gpu_tree(h[:65], 8, list(range(-1, 64)))
+    assert ei.value.status == jb.JUP_EINVAL and len(p.kv) == 8
+    with pytest.raises(E) as ei:                      # a hole
+        p.gpu_tree(h[8:11], 9, [-1, 0, 1])
+    assert ei.value.status == jb.JUP_EPOS
+    p.gpu_tree(h[8:14], 8, [-1, 0, 0, 1, 1, 2])
+    assert len(p.kv) == 14
+    for base, slots, status in ((8, [1, 0], jb.JUP_EINVAL), (8, [0, 0], jb.JUP_EINVAL), (8, [-1], jb.JUP_EINVAL),
+                                (8, [0, 6], jb.JUP_EPOS), (15, [], jb.JUP_EPOS), (-1, [], jb.JUP_EPOS)):
+        with pytest.raises(E) as ei:
+            p.kv.keep(base, slots)
+        assert ei.value.status == status and len(p.kv) == 14, (base, slots)
+    p.kv.keep(8, [0, 2, 5])
+    assert len(p.kv) == 11
+    p.kv.keep(8, [])                                   # all candidates rejected = truncate
+    assert len(p.kv) == 8
+
+
+def test_keep_on_a_fork_moves_only_the_forks_own_entries():
+    p = Pair(si.TINY, "f32", seed=26, max_positions=64, max_chunk_tokens=64)
+    h = p.hidden(40)
+    p.gpu_chunk(h[:16], 0)
+    parent_bits = kv_bits(p.kv)
+    fork = p.kv.fork(16, 48)
+    fill_sentinel(fork)
+    p.gpu_chunk(h[16:20], 16, kv=fork)
+    p.gpu_tree(h[20:30], 20, [-1, 0, 0, 1, 1, 2, 3, 3, 6, 8], kv=fork)
+    before = kv_bits(fork)
+    with pytest.raises(jb.JupiterError) as ei:
+        fork.keep(15, [0])                             # inside the shared prefix
+    assert ei.value.status == jb.JUP_EPOS
+    fork.keep(20, [0, 1, 3, 6, 8])
+    after = kv_bits(fork)
+    assert len(fork) == 25
+    assert np.array_equal(kv_bits(p.kv), parent_bits)
+    assert np.array_equal(after[:, :, :, :4], before[:, :, :, :4])           # own slots of positions 16..19
+    for j, t in enumerate([0, 1, 3, 6, 8]):
+        assert np.array_equal(after[:, :, :, 4 + j], before[:, :, :, 4 + t])
+    fork.destroy()
+
+
 def run_fork_case(p, n_prefix, n_private, n_chunk, n_branches):
     """Shared prompt prefix, per-branch private tokens, then one small chunk per branch (Sec. V-B)."""
     cfg = p.cfg
@@ -338,6 +470,40 @@ def test_bf16_layer0_cache_is_bit_identical_across_chunkings_and_runs():
 def test_bf16_forked_caches_share_the_prompt_prefix_small():
     p = Pair(LLAMA7B_2L, "bf16", seed=13, max_positions=80, max_chunk_tokens=64, oracle_positions=86)
     run_fork_case(p, n_prefix=70, n_private=11, n_chunk=5, n_branches=2)
+
+
+def test_bf16_token_tree_matches_the_oracle_and_keep_moves_the_accepted_path():
+    p = Pair(LLAMA7B_2L, "bf16", seed=31, max_positions=200, max_chunk_tokens=128)
+    run_tree_case(p, n_prefix=100, n_tree=64, seed=31)     # tree entries span the tiles 3..5 of 32 keys
+    run_tree_case(p, n_prefix=37, n_tree=26, seed=32)      # one query block, ragged
+    run_tree_case(p, n_prefix=0, n_tree=40, seed=33)
+
+
+def test_bf16_chain_shaped_tree_is_bitwise_the_ordinary_chunk():
+    p = Pair(LLAMA7B_2L, "bf16", seed=34, max_positions=128, max_chunk_tokens=64)
+    h = p.hidden(90)
+    p.gpu_chunk(h[:41], 0)
+    a = p.gpu_chunk(h[41:], 41)
+    kv_a = kv_bits(p.kv)
+    p.kv.truncate(41)
+    b = p.gpu_tree(h[41:], 41, list(range(-1, 48)))
+    assert np.array_equal(a, b)
+    assert np.array_equal(kv_a, kv_bits(p.kv))
+
+
+def test_bf16_tree_node_equals_the_ordinary_call_on_its_path():
+    p = Pair(LLAMA7B_2L, "bf16", seed=35, max_positions=128, max_chunk_tokens=128)
+    n_prefix, n_tree = 70, 48
+    parents = si.make_token_tree(n_tree, 35)
+    h = p.hidden(n_prefix + n_tree)
+    p.gpu_chunk(h[:n_prefix], 0)
+    g = p.gpu_tree(h[n_prefix:], n_prefix, parents)
+    for t, path in enumerate(tree_paths(parents)):
+        if t % 7:
+            continue
+        p.kv.truncate(n_prefix)
+        ref = p.gpu_chunk(h[n_prefix:][path], n_prefix)
+        assert rel_l2(g[t], ref[-1]) <= 1e-2, t   # same values, other tile shapes and summation orders
 
 
 def test_bf16_zero_output_projections_pass_input_through_bitwise():

@@ -149,6 +149,23 @@ def test_prefill_branches_without_a_stage_is_rejected():
     L.jup_kv_destroy(kv)
 
 
+def test_tree_and_keep_argument_errors_need_no_device():
+    """Everything jup_kv_keep() rejects is rejected on the host; an empty cache has nothing to keep."""
+    L = jb.lib()
+    kv = make_kv(16)
+    par = (ctypes.c_int32 * 3)(-1, 0, 1)
+    assert L.jup_stage_prefill_tree(None, FAKE, 3, 0, par, kv, FAKE, None) == jb.JUP_EINVAL
+    assert L.jup_kv_keep(None, 0, 0, None, None) == jb.JUP_EINVAL
+    one = (ctypes.c_int32 * 1)(0)
+    assert L.jup_kv_keep(kv, 0, 1, one, None) == jb.JUP_EPOS       # entry 0 does not exist
+    assert L.jup_kv_keep(kv, 1, 0, None, None) == jb.JUP_EPOS      # base behind the end
+    assert L.jup_kv_keep(kv, 0, 65, one, None) == jb.JUP_EINVAL    # more than a tree holds
+    assert L.jup_kv_keep(kv, 0, 1, None, None) == jb.JUP_EINVAL
+    assert L.jup_kv_keep(kv, 0, 0, None, None) == jb.JUP_OK        # nothing kept, nothing moved, no launch
+    assert L.jup_kv_len(kv) == 0
+    L.jup_kv_destroy(kv)
+
+
 def test_fork_rules():
     """Outline branches share the prompt's cache read-only (Sec. V-B)."""
     L = jb.lib()
