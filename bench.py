@@ -17,6 +17,8 @@ default is the metric):
   c4  13B-shaped 10-layer stage, 1024-token prompt in 8 chunks of 128 (bound by streaming the weights)
   c5  7B-shaped stage, 8 branches sharing a 512-token prefix, 64 private tokens each; a step is one
       5-token chunk at position 576 on every branch                  (decode-sized, bound by the weights)
+  tree  7B-shaped stage, one speculative step: a 64-candidate token tree verified at position 576 in one
+      call, then the accepted path kept in the cache                  (bound by the weights)
 """
 import argparse
 import json
@@ -58,7 +60,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=("c2", "c3", "c4", "c5"), default="c3")
+    ap.add_argument("--workload", choices=("c2", "c3", "c4", "c5", "tree"), default="c3")
     ap.add_argument("--chunk", type=int, default=512, help="chunk size of workload c3 (128, 256, 512 or 2048)")
     ap.add_argument("--batched", action="store_true",
                     help="workload c5: all 8 branches in one jup_stage_prefill_branches call per step")
@@ -93,6 +95,10 @@ def main():
         cfg, prompt, chunk, seed = si.LLAMA13B_STAGE, 1024, 128, 40
         what = ("configs[3]: 10-layer stage of Llama-2-13B shape (d 5120, 40 heads x 128, FFN 13824), "
                 "1024-token prompt as 8 chunks of 128")
+    elif wl == "tree":
+        cfg, prompt, chunk, seed = si.LLAMA7B_STAGE, 576, 64, 70
+        what = ("speculative step on the 8-layer stage of Llama-2-7B shape: a 64-candidate token tree verified in one "
+                "call at position 576, then the accepted path kept in the cache")
     else:
         cfg, prompt, chunk, seed = si.LLAMA7B_STAGE, 512, 128, 50
         what = ("configs[4]: 8-layer stage of Llama-2-7B shape, 8 branches sharing a 512-token prefix with 64 "
@@ -103,7 +109,7 @@ def main():
     layers_np = si.make_layers(cfg, seed, bf16=True, n_threads=16)
     hidden_np = si.make_hidden(cfg, seed, prompt, bf16=True)
     stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers_np, "bf16"), chunk)
-    kv = jb.KvCache(cfg, "bf16", prompt)
+    kv = jb.KvCache(cfg, "bf16", prompt + (chunk if wl == "tree" else 0))
     hidden = torch.from_numpy(hidden_np).to("cuda:0", torch.bfloat16)
     out = torch.empty_like(hidden)
 
@@ -135,6 +141,23 @@ def main():
             def step():
                 for b in range(n_branches):
                     stage.prefill_chunk(step_in[b], p_step, branches[b], hidden_out=step_out[b])
+    elif wl == "tree":
+        for c in range(n_chunks):  # untimed: the sequence so far
+            stage.prefill_chunk(hidden[c * chunk:(c + 1) * chunk], c * chunk, kv)
+        parents = si.make_token_tree(chunk, seed)
+        paths = []
+        for t, par in enumerate(parents):
+            paths.append((paths[par] if par >= 0 else []) + [t])
+        accepted = max(paths, key=len)
+        cand = torch.from_numpy(si.make_hidden(cfg, seed, chunk, tag=1, bf16=True)).to("cuda:0", torch.bfloat16)
+        cand_out = torch.empty_like(cand)
+        calls = [(chunk, prompt)]
+        tokens_per_step = chunk
+        tree_pairs = chunk * prompt + sum(len(pth) for pth in paths)  # prefix plus ancestors and self
+
+        def step():  # the next step's tree overwrites what this one kept
+            stage.prefill_tree(cand, prompt, parents, kv, hidden_out=cand_out)
+            kv.keep(prompt, accepted)
     else:
         calls = [(chunk, c * chunk) for c in range(n_chunks)]
         tokens_per_step = prompt
@@ -166,6 +189,8 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     tokens_per_s = tokens_per_step * args.steps / elapsed
     step_flops = sum(flops_per_call(cfg, n, p) for n, p in calls)
+    if wl == "tree":  # pairs a query really has: prefix, ancestors, itself (not the causal triangle)
+        step_flops += cfg["n_layers"] * 4.0 * cfg["d_model"] * (tree_pairs - (chunk * prompt + chunk * (chunk + 1) / 2))
     step_bytes = sum(bytes_per_call(cfg, n, p) for n, p in calls)
     if wl == "c5" and args.batched:  # one pass over the weights serves every branch
         d_, f_, L_ = cfg["d_model"], cfg["d_ffn"], cfg["n_layers"]
@@ -205,7 +230,7 @@ def main():
                      "traffic_unit": "bytes per launch (offline rocprofv3 counters)"})
 
     cpu_baseline = None
-    if not args.no_cpu_baseline and wl != "c5":
+    if not args.no_cpu_baseline and wl not in ("c5", "tree"):
         import oracle
         ns = min(max(args.cpu_sample_tokens, 1), prompt)
         ora = oracle.OracleStage(cfg, layers_np, ns)
