@@ -22,6 +22,21 @@ jup_status_t fail(jup_status_t code, const char* fmt, ...) {
 
 size_t elem_size(const jup_stage_config_t& c) { return c.dtype == JUP_BF16 ? 2 : 4; }
 
+}  // namespace
+
+namespace jup {
+// the same thread-local message for the entry points that live in other files
+jup_status_t set_error(jup_status_t code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+}  // namespace jup
+
+namespace {
+
 // Empty string when the configuration is usable, otherwise the reason.
 const char* check_cfg(const jup_stage_config_t* c) {
     if (!c) return "cfg is NULL";

@@ -129,6 +129,9 @@ struct TraceScope {
     TraceScope& operator=(const TraceScope&) = delete;
 };
 
+// Records the message jup_last_error() returns on this thread and hands the status code back (jup_api.hip).
+jup_status_t set_error(jup_status_t code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // ---- check-mode (fp32) path: kernels_f32.hip ------------------------------------------------------
 hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int pos, const KvView& kv,
                        float* hidden_out, hipStream_t s, const TreeTable* tree = nullptr);
