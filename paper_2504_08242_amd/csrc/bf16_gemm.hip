@@ -555,7 +555,11 @@ int gemm_plan_splits(int M, int N, int K) {
 
 namespace {
 // Among the instantiated widths (in 32-column blocks) of the 256-row tile, the one with the least work on the
-// busiest CU: rounds of workgroups x rows streamed per tile.  Ties go to the wider tile (fewer re-reads of A).
+// busiest CU: rounds of workgroups x time of one tile.  A tile's time grows with its width plus a fixed part
+// (pipeline fill and drain, epilogue, and the 256 rows of A it streams whatever its width) worth about two
+// column blocks: without it many narrow tiles look cheapest, and they re-read A once per tile (measured at
+// M = 2048: 1.66 GB fetched per launch and 445 us with 64-column tiles, against 325 us expected from M = 1024).
+// Ties go to the wider tile.
 int pick_blocks(int M, int N, const int* cands, int n_cands) {
     const int m_tiles = div_up(M, 256);
     int best = cands[0];
@@ -563,7 +567,7 @@ int pick_blocks(int M, int N, const int* cands, int n_cands) {
     for (int i = 0; i < n_cands; ++i) {
         const int nb = cands[i];
         const long tiles = (long)m_tiles * div_up(N, 32 * nb);
-        const long cost = div_up((int)tiles, kCUs) * (long)(32 * nb);
+        const long cost = div_up((int)tiles, kCUs) * (long)(32 * nb + 64);
         if (best_cost < 0 || cost <= best_cost) { best = nb; best_cost = cost; }
     }
     return best;

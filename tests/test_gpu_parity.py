@@ -531,17 +531,17 @@ def test_c2_7b_stage_512_tokens_in_8_chunks_of_64():
 
 
 @pytest.mark.slow
-def test_c3_7b_stage_2048_tokens_chunk_sizes_128_256_512():
-    """Config 3: the same stage, 2048-token prompt, chunkings 16x128, 8x256, 4x512 against one oracle run
-    (the oracle's own chunk invariance is pinned on the CPU)."""
-    p = Pair(si.LLAMA7B_STAGE, "bf16", seed=30, max_positions=2048, max_chunk_tokens=512)
+def test_c3_7b_stage_2048_tokens_chunk_sizes_128_to_2048():
+    """Config 3: the same stage, 2048-token prompt, chunkings 16x128, 8x256, 4x512, 2x1024 and one shot against
+    one oracle run (the oracle's own chunk invariance is pinned on the CPU)."""
+    p = Pair(si.LLAMA7B_STAGE, "bf16", seed=30, max_positions=2048, max_chunk_tokens=2048)
     hidden = p.hidden(2048)
     o = []
     for c in range(4):
         o.append(p.oracle.prefill_chunk(hidden[c * 512:(c + 1) * 512], c * 512))
         print(f"oracle chunk {c} done", flush=True)
     o = np.concatenate(o)
-    for size in (512, 256, 128):
+    for size in (512, 1024, 2048, 256, 128):
         p.kv.reset()
         g = np.concatenate([p.gpu_chunk(hidden[s:s + size], s) for s in range(0, 2048, size)])
         p.check(g, o, f"chunk size {size}")
