@@ -52,7 +52,7 @@ constexpr int G_BK = 32;
 
 constexpr int kLdsBudget = 160 * 1024;
 
-template <int BMB, int NB, int WM, int WN>
+template <int BMB, int NB, int WM, int WN, int LW = 0>
 struct Shape {
     static constexpr int BM = 32 * BMB;             // rows of the tile: 256 for prefill-sized chunks, 128 or 64 for
                                                     // short ones (a short chunk is bound by streaming the weights:
@@ -62,9 +62,13 @@ struct Shape {
     static constexpr int WAVES = WM * WN;
     static constexpr int ROWS = BM + 32 * NB;       // LDS rows per stage: A rows then W rows
     static constexpr int STAGE_BYTES = ROWS * 64;
-    static constexpr int NL = ROWS / 16;            // 1 KB load units (16 rows) per stage, dealt round-robin to the waves
-    static constexpr int LPW = (NL + WAVES - 1) / WAVES;  // load instructions per stage of the waves that have the most
-    static constexpr int REM = NL % WAVES;          // waves below REM issue LPW loads, the others LPW - 1 (0: all LPW)
+    // LW = 0: every wave fetches its share of a stage between its MFMAs.  LW > 0: LW extra waves do nothing but
+    // fetch, and the WAVES computing waves issue no vector-memory instruction inside the K loop.
+    static constexpr int LOADERS = LW > 0 ? LW : WAVES;  // waves that issue the global->LDS loads
+    static constexpr int THREADS = 64 * (WAVES + LW);
+    static constexpr int NL = ROWS / 16;            // 1 KB load units (16 rows) per stage, dealt round-robin to the loading waves
+    static constexpr int LPW = (NL + LOADERS - 1) / LOADERS;  // load instructions per stage of the waves that have the most
+    static constexpr int REM = NL % LOADERS;        // loading waves below REM issue LPW loads, the others LPW - 1 (0: all LPW)
     static_assert(NB % WN == 0 && BMB % WM == 0, "tile does not split evenly over the waves");
     // as many ring slots as LDS holds (at most 8: the in-flight count must fit the 6-bit vmcnt)
     static constexpr int STAGES = kLdsBudget / STAGE_BYTES > 8 ? 8 : kLdsBudget / STAGE_BYTES;
@@ -114,6 +118,18 @@ __device__ __forceinline__ void sched_half() {
     }
 }
 
+// Waits until at most g of this wave's load groups (one group = the CNT loads of one stage) are still in
+// flight; more than ST - 3 are never allowed to be.
+template <int ST, int CNT>
+__device__ __forceinline__ void wait_groups(int g) {
+    if (g >= ST - 3) wait_vmcnt<(ST - 3) * CNT>();
+    else if (g == 4) wait_vmcnt<(ST > 7 ? 4 : 0) * CNT>();
+    else if (g == 3) wait_vmcnt<(ST > 6 ? 3 : 0) * CNT>();
+    else if (g == 2) wait_vmcnt<(ST > 5 ? 2 : 0) * CNT>();
+    else if (g == 1) wait_vmcnt<1 * CNT>();
+    else wait_vmcnt<0>();
+}
+
 // Fragments of one K/16 sub-step of a wave: MB row blocks, NB column blocks.
 template <int MB, int NB>
 struct Frags {
@@ -121,15 +137,16 @@ struct Frags {
     bf16x8 b[NB];
 };
 
-template <int BMB, int NB, int WM, int WN, int EPI>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
-    using S = Shape<BMB, NB, WM, WN>;
+template <int BMB, int NB, int WM, int WN, int EPI, int LW = 0>
+__global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs a) {
+    using S = Shape<BMB, NB, WM, WN, LW>;
     constexpr int G_BM = S::BM;
     constexpr int NBW = S::NBW, MBW = S::MBW;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WM, wn = wave / WM;  // wave owns row blocks [wm MBW, +MBW) x column blocks [wn NBW, +NBW)
+    const int lw = LW > 0 ? wave - S::WAVES : wave;  // index among the loading waves (negative: a computing wave)
 
     // ---- which tile ---------------------------------------------------------------------------------
     // Workgroup b runs on XCD b % 8.  Tiles are numbered so that each XCD owns one contiguous range of
@@ -152,13 +169,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
     // instruction moves four super-rows: lane i's 16 bytes land at byte 16 i of the instruction's 1 KB.
     // Unit j of a stage = rows [16j, 16j+16) of the LDS image = 1 KB that is contiguous in the tiled operand
     // too (half a 2 KB block), so one load instruction is a wave-uniform base plus 16 bytes per lane.  Unit
-    // j = q * WAVES + wave belongs to this wave; HAS_LAST says whether its unit q = LPW-1 exists.
+    // j = q * LOADERS + lw belongs to loading wave lw; HAS_LAST says whether its unit q = LPW-1 exists.
     const char* ubase[S::LPW];
     const int kt_total = a.K / G_BK;
     const unsigned lane16 = lane * 16;
 #pragma unroll
     for (int q = 0; q < S::LPW; ++q) {
-        const int j = min(q * S::WAVES + wave, S::NL - 1);
+        const int j = min(q * S::LOADERS + max(lw, 0), S::NL - 1);
         const u16* base;
         int blk;
         if (j < G_BM / 16) {
@@ -173,7 +190,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
     auto issue_one = [&](int q, int stage, int kt) {
         __builtin_amdgcn_global_load_lds(
             (const __attribute__((address_space(1))) void*)(uniform_ptr(ubase[q] + (size_t)kt * 2048) + lane16),
-            (__attribute__((address_space(3))) void*)(smem + stage * S::STAGE_BYTES + (q * S::WAVES + wave) * 1024),
+            (__attribute__((address_space(3))) void*)(smem + stage * S::STAGE_BYTES + (q * S::LOADERS + lw) * 1024),
             16, 0, 0);
     };
     auto issue = [&](auto has_last, int stage, int kt) {
@@ -181,6 +198,43 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
         for (int q = 0; q < CNT; ++q) issue_one(q, stage, kt);
     };
+
+    // ---- loading waves (LW > 0) ----------------------------------------------------------------------------
+    // The whole life of a loading wave: fill the ring, then per stage wait for the loads of the NEXT stage,
+    // meet the computing waves at their barrier (which also tells that they are done with the stage before),
+    // and refill the slot that this frees.  Same barriers, in the same number, as the computing waves below.
+    // A global->LDS load holds the wave that issues it for about a hundred cycles; here that wave has
+    // nothing else to do, and the computing waves issue nothing but MFMAs and LDS reads.
+    if constexpr (LW > 0) {
+        if (lw >= 0) {
+            auto run = [&](auto has_last) {
+                constexpr int CNT = S::REM == 0 || decltype(has_last)::value ? S::LPW : S::LPW - 1;
+                constexpr int ST = S::STAGES;
+#pragma unroll
+                for (int s = 0; s < ST - 1; ++s)
+                    if (s < KT) issue(has_last, s, s);
+                if (KT >= ST - 1) wait_vmcnt<(ST - 2) * CNT>();
+                else wait_vmcnt<0>();
+                __builtin_amdgcn_s_barrier();
+                int stage = 0;
+                for (int kt = 0; kt + 1 < KT; ++kt) {  // every stage but the last starts with a barrier
+                    wait_groups<ST, CNT>(KT - 1 - (kt + 1));
+                    __builtin_amdgcn_s_barrier();
+                    if (kt + ST - 1 < KT) issue(has_last, stage == 0 ? ST - 1 : stage - 1, kt + ST - 1);
+                    stage = stage + 1 == ST ? 0 : stage + 1;
+                }
+            };
+            if constexpr (S::REM == 0) {
+                run(std::true_type{});
+            } else {
+                if (lw < S::REM) run(std::true_type{});
+                else run(std::false_type{});
+            }
+            if (EPI != EPI_PARTIAL) __builtin_amdgcn_s_barrier();  // the one barrier of the epilogue
+            return;
+        }
+    }
+    constexpr bool FETCH = LW == 0;  // the computing waves fetch their share themselves
 
     // ---- LDS -> register fragment addresses -------------------------------------------------------------
     // Fragment row = 32*block + c (c = lane & 31), chunk = 2*ks + hh.  Block bases are multiples of 32,
@@ -227,26 +281,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
     // The whole K loop exists once per load count (waves with and without the last load unit), so that no
     // load sits under a condition: a branch inside the loop would also cut it into scheduling regions.
     auto k_loop = [&](auto has_last) {
-    constexpr int CNT = S::REM == 0 || decltype(has_last)::value ? S::LPW : S::LPW - 1;  // loads per stage
+    constexpr int CNT = !FETCH ? 0 : S::REM == 0 || decltype(has_last)::value ? S::LPW : S::LPW - 1;  // loads per stage
+    if constexpr (FETCH) {
 #pragma unroll
-    for (int s = 0; s < ST - 1; ++s)
-        if (s < KT) issue(has_last, s, s);
-    if (KT >= ST - 1) wait_vmcnt<(ST - 2) * CNT>();  // stage 0 landed, the others may be in flight
-    else wait_vmcnt<0>();
+        for (int s = 0; s < ST - 1; ++s)
+            if (s < KT) issue(has_last, s, s);
+        if (KT >= ST - 1) wait_vmcnt<(ST - 2) * CNT>();  // stage 0 landed, the others may be in flight
+        else wait_vmcnt<0>();
+    }
     __builtin_amdgcn_s_barrier();
     load_frags(f0, 0, 0);
     wait_lgkmcnt0();
     if (GEMM_EXPERIMENT & 4) f1 = f0;
-
-    // Waits until at most g of this wave's load groups (one group = one stage) are still in flight.
-    auto wait_groups = [&](int g) {
-        if (g >= ST - 3) wait_vmcnt<(ST - 3) * CNT>();
-        else if (g == 4) wait_vmcnt<(ST > 7 ? 4 : 0) * CNT>();
-        else if (g == 3) wait_vmcnt<(ST > 6 ? 3 : 0) * CNT>();
-        else if (g == 2) wait_vmcnt<(ST > 5 ? 2 : 0) * CNT>();
-        else if (g == 1) wait_vmcnt<1 * CNT>();
-        else wait_vmcnt<0>();
-    };
 
     // Stage kt.  On entry f0 holds its sub-step 0.  The barrier at the top publishes stage kt+1 (whose
     // sub-step 0 is prefetched in the second half) and retires stage kt-1, which every wave finished
@@ -264,7 +310,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
         if (REFILL) {
 #if GEMM_TIMELINE
             const unsigned long long t0 = __builtin_amdgcn_s_memtime();
-            wait_vmcnt<(ST - 3) * CNT>();
+            if (FETCH) wait_vmcnt<(ST - 3) * CNT>();
             const unsigned long long t1 = __builtin_amdgcn_s_memtime();
             __builtin_amdgcn_s_barrier();
             const unsigned long long t2 = __builtin_amdgcn_s_memtime();
@@ -272,11 +318,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
             if (tl_first == 0) tl_first = t0;
             tl_last = t2;
 #else
-            wait_vmcnt<(ST - 3) * CNT>();
+            if (FETCH) wait_vmcnt<(ST - 3) * CNT>();
             if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
 #endif
         } else if (!LAST) {
-            wait_groups(KT - 1 - (kt + 1));  // stages issued after kt+1 may stay in flight
+            if (FETCH) wait_groups<ST, CNT>(KT - 1 - (kt + 1));  // stages issued after kt+1 may stay in flight
             if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
         }
         // Memory instructions are dealt out between the MFMAs, and the compiler's scheduler is fenced at
@@ -284,8 +330,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
         // matrix pipe runs dry.  Fragment reads come first in a half, the global->LDS loads after them
         // (spreading the loads among the reads, or keeping the last MFMAs free of both, measured slower).
         constexpr int NM = MBW * NBW;
-        constexpr int V1 = REFILL && !(GEMM_EXPERIMENT & 1) ? (CNT + 1) / 2 : 0;
-        constexpr int V2 = REFILL && !(GEMM_EXPERIMENT & 1) ? CNT - V1 : 0;
+        constexpr int V1 = REFILL && FETCH && !(GEMM_EXPERIMENT & 1) ? (CNT + 1) / 2 : 0;
+        constexpr int V2 = REFILL && FETCH && !(GEMM_EXPERIMENT & 1) ? CNT - V1 : 0;
         auto half = [&]<int... M>(std::integer_sequence<int, M...>, auto second) {
             constexpr bool SECOND = decltype(second)::value;
             constexpr int RD = (GEMM_EXPERIMENT & 4) || (SECOND && LAST) ? 0 : MBW + NBW;
@@ -336,7 +382,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
         do_stage(std::false_type{}, std::false_type{}, kt, stage, prev_slot(stage), next_slot(stage));
     if (kt < KT) do_stage(std::false_type{}, std::true_type{}, kt, stage, prev_slot(stage), next_slot(stage));
     };
-    if constexpr (S::REM == 0) {
+    if constexpr (S::REM == 0 || !FETCH) {
         k_loop(std::true_type{});
     } else {
         if (wave < S::REM) k_loop(std::true_type{});
@@ -504,22 +550,22 @@ int div_up(int x, int y) { return (x + y - 1) / y; }
 // Row blocks of the tile for a chunk of M tokens.
 int pick_row_blocks(int M) { return M > 128 ? 8 : M > 64 ? 4 : 2; }
 
-template <int BMB, int NB, int WM, int WN, int EPI>
+template <int BMB, int NB, int WM, int WN, int EPI, int LW = 0>
 hipError_t launch(GemmArgs a, hipStream_t s) {
     a.n_stride = 32 * NB;
     a.n_tiles = div_up(a.N, a.n_stride);
     a.m_tiles = div_up(a.M, 32 * BMB);
     a.kt_per_split = a.K / G_BK / a.splits;
     const int grid = a.m_tiles * a.n_tiles * a.splits;
-    constexpr size_t lds_bytes = Shape<BMB, NB, WM, WN>::LDS_BYTES;
-    hipLaunchKernelGGL((gemm_bf16<BMB, NB, WM, WN, EPI>), dim3(grid), dim3(64 * WM * WN), lds_bytes, s, a);
+    using S = Shape<BMB, NB, WM, WN, LW>;
+    hipLaunchKernelGGL((gemm_bf16<BMB, NB, WM, WN, EPI, LW>), dim3(grid), dim3(S::THREADS), S::LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
-template <int BMB, int NB, int WM, int WN, int EPI>
+template <int BMB, int NB, int WM, int WN, int EPI, int LW = 0>
 hipError_t configure_one() {
-    return hipFuncSetAttribute((const void*)gemm_bf16<BMB, NB, WM, WN, EPI>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, Shape<BMB, NB, WM, WN>::LDS_BYTES);
+    return hipFuncSetAttribute((const void*)gemm_bf16<BMB, NB, WM, WN, EPI, LW>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, Shape<BMB, NB, WM, WN, LW>::LDS_BYTES);
 }
 
 }  // namespace
@@ -527,17 +573,24 @@ hipError_t configure_one() {
 // Instantiations: (row blocks, column blocks, wave grid) per epilogue.  256-row tiles for prefill-sized
 // chunks; 128- and 64-row tiles with narrow N for short chunks, where the grid must be wide enough to keep
 // every CU streaming weights.
+// Loading waves of the three shapes that carry a prefill-sized chunk (0 = the computing waves fetch).  Measured
+// with 4 (one per SIMD) at M = 512: gate/up 89.0 -> 92.5 us, QKV 61.6 -> 65.2 us, down 51.7 -> 54.5 us.  Unlike
+// in the attention kernel, taking the loads off the computing waves does not pay here: their issue slots were
+// not what the K loop waits for, and a third wave per SIMD costs more than it hides.  Kept for experiments.
+#ifndef GEMM_LW
+#define GEMM_LW 0
+#endif
 #define JUP_GEMM_SHAPES(X)                                                          \
-    X(8, 1, 4, 1, EPI_QKV) X(8, 2, 4, 1, EPI_QKV) X(8, 3, 8, 1, EPI_QKV)            \
-    X(4, 2, 4, 1, EPI_QKV) X(2, 2, 2, 2, EPI_QKV)                                   \
-    X(8, 2, 4, 1, EPI_SWIGLU) X(8, 3, 4, 1, EPI_SWIGLU) X(8, 4, 4, 2, EPI_SWIGLU) X(8, 6, 4, 2, EPI_SWIGLU) \
-    X(4, 4, 4, 1, EPI_SWIGLU) X(2, 4, 2, 2, EPI_SWIGLU)                             \
-    X(8, 4, 4, 2, EPI_PARTIAL) X(4, 4, 4, 1, EPI_PARTIAL) X(2, 4, 2, 2, EPI_PARTIAL)
+    X(8, 1, 4, 1, EPI_QKV, 0) X(8, 2, 4, 1, EPI_QKV, 0) X(8, 3, 8, 1, EPI_QKV, GEMM_LW)            \
+    X(4, 2, 4, 1, EPI_QKV, 0) X(2, 2, 2, 2, EPI_QKV, 0)                                   \
+    X(8, 2, 4, 1, EPI_SWIGLU, 0) X(8, 3, 4, 1, EPI_SWIGLU, 0) X(8, 4, 4, 2, EPI_SWIGLU, 0) X(8, 6, 4, 2, EPI_SWIGLU, GEMM_LW) \
+    X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0)                             \
+    X(8, 4, 4, 2, EPI_PARTIAL, GEMM_LW) X(4, 4, 4, 1, EPI_PARTIAL, 0) X(2, 4, 2, 2, EPI_PARTIAL, 0)
 
 hipError_t gemm_configure() {
     hipError_t e = hipSuccess;
     auto acc = [&](hipError_t r) { if (e == hipSuccess) e = r; };
-#define X(BMB, NB, WM, WN, EPI) acc(configure_one<BMB, NB, WM, WN, EPI>());
+#define X(BMB, NB, WM, WN, EPI, LW) acc(configure_one<BMB, NB, WM, WN, EPI, LW>());
     JUP_GEMM_SHAPES(X)
 #undef X
     return e;
@@ -581,7 +634,7 @@ hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s) {
     if (bmb == 4) return launch<4, 2, 4, 1, EPI_QKV>(a, s);
     static const int cands[] = {1, 2, 3};
     const int nb = pick_blocks(a.M, a.N, cands, 3);
-    if (nb == 3) return launch<8, 3, 8, 1, EPI_QKV>(a, s);  // 8 waves of 32 x 96: measured 1.3 % faster than 4 of 64 x 96
+    if (nb == 3) return launch<8, 3, 8, 1, EPI_QKV, GEMM_LW>(a, s);  // 8 waves of 32 x 96: measured 1.3 % faster than 4 of 64 x 96
     if (nb == 2) return launch<8, 2, 4, 1, EPI_QKV>(a, s);
     return launch<8, 1, 4, 1, EPI_QKV>(a, s);
 }
@@ -593,7 +646,7 @@ hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
     if (bmb == 4) return launch<4, 4, 4, 1, EPI_SWIGLU>(a, s);
     static const int cands[] = {2, 3, 4, 6};
     const int nb = pick_blocks(a.M, a.N, cands, 4);
-    if (nb == 6) return launch<8, 6, 4, 2, EPI_SWIGLU>(a, s);
+    if (nb == 6) return launch<8, 6, 4, 2, EPI_SWIGLU, GEMM_LW>(a, s);
     if (nb == 4) return launch<8, 4, 4, 2, EPI_SWIGLU>(a, s);
     if (nb == 3) return launch<8, 3, 4, 1, EPI_SWIGLU>(a, s);
     return launch<8, 2, 4, 1, EPI_SWIGLU>(a, s);
@@ -604,7 +657,7 @@ hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
     const int bmb = pick_row_blocks(a.M);
     if (bmb == 2) return launch<2, 4, 2, 2, EPI_PARTIAL>(a, s);
     if (bmb == 4) return launch<4, 4, 4, 1, EPI_PARTIAL>(a, s);
-    return launch<8, 4, 4, 2, EPI_PARTIAL>(a, s);
+    return launch<8, 4, 4, 2, EPI_PARTIAL, GEMM_LW>(a, s);
 }
 
 }  // namespace jup
