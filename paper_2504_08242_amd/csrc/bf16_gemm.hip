@@ -584,7 +584,7 @@ hipError_t configure_one() {
     X(8, 1, 4, 1, EPI_QKV, 0) X(8, 2, 4, 1, EPI_QKV, 0) X(8, 3, 8, 1, EPI_QKV, GEMM_LW)            \
     X(4, 2, 4, 1, EPI_QKV, 0) X(2, 2, 2, 2, EPI_QKV, 0)                                   \
     X(8, 2, 4, 1, EPI_SWIGLU, 0) X(8, 3, 4, 1, EPI_SWIGLU, 0) X(8, 4, 4, 2, EPI_SWIGLU, 0) X(8, 6, 4, 2, EPI_SWIGLU, GEMM_LW) \
-    X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0)                             \
+    X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0) X(4, 3, 4, 1, EPI_SWIGLU, 0) X(2, 3, 2, 3, EPI_SWIGLU, 0) \
     X(8, 4, 4, 2, EPI_PARTIAL, GEMM_LW) X(4, 4, 4, 1, EPI_PARTIAL, 0) X(2, 4, 2, 2, EPI_PARTIAL, 0)
 
 hipError_t gemm_configure() {
@@ -642,8 +642,12 @@ hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s) {
 hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
     a.splits = 1;
     const int bmb = pick_row_blocks(a.M);
-    if (bmb == 2) return launch<2, 4, 2, 2, EPI_SWIGLU>(a, s);
-    if (bmb == 4) return launch<4, 4, 4, 1, EPI_SWIGLU>(a, s);
+    // A short chunk is bound by streaming the weights, and every CU that streams adds bandwidth: the narrower
+    // tile (96 columns) when its tiles still fit one round of workgroups (measured at 64 rows, N = 22016:
+    // 230 workgroups 38.0 us, 172 workgroups of 128 columns 40.9 us, 344 of 64 columns 47.1 us).
+    const bool narrow = div_up(a.N, 96) <= kCUs;
+    if (bmb == 2) return narrow ? launch<2, 3, 2, 3, EPI_SWIGLU>(a, s) : launch<2, 4, 2, 2, EPI_SWIGLU>(a, s);
+    if (bmb == 4) return narrow ? launch<4, 3, 4, 1, EPI_SWIGLU>(a, s) : launch<4, 4, 4, 1, EPI_SWIGLU>(a, s);
     static const int cands[] = {2, 3, 4, 6};
     const int nb = pick_blocks(a.M, a.N, cands, 4);
     if (nb == 6) return launch<8, 6, 4, 2, EPI_SWIGLU, GEMM_LW>(a, s);
