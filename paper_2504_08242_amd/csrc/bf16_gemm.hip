@@ -585,7 +585,7 @@ hipError_t configure_one() {
     X(4, 2, 4, 1, EPI_QKV, 0) X(2, 2, 2, 2, EPI_QKV, 0)                                   \
     X(8, 2, 4, 1, EPI_SWIGLU, 0) X(8, 3, 4, 1, EPI_SWIGLU, 0) X(8, 4, 4, 2, EPI_SWIGLU, 0) X(8, 6, 4, 2, EPI_SWIGLU, GEMM_LW) \
     X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0) X(4, 3, 4, 1, EPI_SWIGLU, 0) X(2, 3, 2, 3, EPI_SWIGLU, 0) \
-    X(8, 4, 4, 2, EPI_PARTIAL, GEMM_LW) X(4, 4, 4, 1, EPI_PARTIAL, 0) X(2, 4, 2, 2, EPI_PARTIAL, 0)
+    X(8, 4, 4, 2, EPI_PARTIAL, GEMM_LW) X(4, 4, 4, 1, EPI_PARTIAL, 0) X(2, 4, 2, 2, EPI_PARTIAL, 0) X(2, 2, 2, 2, EPI_PARTIAL, 0) X(4, 2, 4, 1, EPI_PARTIAL, 0)
 
 hipError_t gemm_configure() {
     hipError_t e = hipSuccess;
@@ -596,15 +596,32 @@ hipError_t gemm_configure() {
     return e;
 }
 
-// K splits for the projections whose N (= d_model) alone cannot fill the chip.
-int gemm_plan_splits(int M, int N, int K) {
-    const int m_tiles = div_up(M, 32 * pick_row_blocks(M));
-    const int n_tiles = div_up(N, 128);
+// The projections whose N (= d_model) alone cannot fill the chip are split along K; the fp32 partial sums are
+// added up, in split order, by the reduce + norm kernel that follows.
+namespace {
+// splits for tiles of 32*nb columns: doubled while the grid stays within one round of workgroups and the K
+// stages divide evenly
+int splits_for(int M, int N, int K, int nb) {
+    const int tiles = div_up(M, 32 * pick_row_blocks(M)) * div_up(N, 32 * nb);
     int splits = 1;
-    // double while it keeps the grid within one wave of workgroups and the K stages divide evenly
-    while (m_tiles * n_tiles * splits * 2 <= kCUs && (K / G_BK) % (splits * 2) == 0 && splits < 8) splits *= 2;
+    while (tiles * splits * 2 <= kCUs && (K / G_BK) % (splits * 2) == 0 && splits < 8) splits *= 2;
     return splits;
 }
+}  // namespace
+
+// Column blocks of the partial-sum tile.  Short chunks take 64-column tiles instead of 128 when the wide tile
+// would leave a workgroup only a few K stages (fill and drain of its pipeline would dominate): half the
+// splits, so half the partial sums to write and to read back.  Measured on the 7B shapes: 64-row chunks O
+// 13.3 -> 12.5 us, down 23.0 -> 22.3 us, reduce + norm 8.2 -> 7.6 us; 128-row chunks O 18.2 -> 15.8 us (down,
+// with 43 stages per workgroup, keeps the wide tile: 28.3 vs 29.5 us).
+int gemm_partial_col_blocks(int M, int N, int K) {
+    const int bmb = pick_row_blocks(M);
+    if (bmb >= 8) return 4;
+    const int stages_wide = K / G_BK / splits_for(M, N, K, 4);
+    return stages_wide < (bmb == 2 ? 64 : 32) ? 2 : 4;
+}
+
+int gemm_plan_splits(int M, int N, int K) { return splits_for(M, N, K, gemm_partial_col_blocks(M, N, K)); }
 
 namespace {
 // Among the instantiated widths (in 32-column blocks) of the 256-row tile, the one with the least work on the
@@ -659,8 +676,9 @@ hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
 hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
     a.splits = gemm_plan_splits(a.M, a.N, a.K);
     const int bmb = pick_row_blocks(a.M);
-    if (bmb == 2) return launch<2, 4, 2, 2, EPI_PARTIAL>(a, s);
-    if (bmb == 4) return launch<4, 4, 4, 1, EPI_PARTIAL>(a, s);
+    const bool narrow = gemm_partial_col_blocks(a.M, a.N, a.K) == 2;
+    if (bmb == 2) return narrow ? launch<2, 2, 2, 2, EPI_PARTIAL>(a, s) : launch<2, 4, 2, 2, EPI_PARTIAL>(a, s);
+    if (bmb == 4) return narrow ? launch<4, 2, 4, 1, EPI_PARTIAL>(a, s) : launch<4, 4, 4, 1, EPI_PARTIAL>(a, s);
     return launch<8, 4, 4, 2, EPI_PARTIAL, GEMM_LW>(a, s);
 }
 
