@@ -64,6 +64,10 @@ def main():
     ap.add_argument("--chunk", type=int, default=512, help="chunk size of workload c3 (128, 256, 512 or 2048)")
     ap.add_argument("--batched", action="store_true",
                     help="workload c5: all 8 branches in one jup_stage_prefill_branches call per step")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="feed the chunks of a prompt one call after the other instead of one jup_stage_prefill_chunks "
+                         "call whose consecutive chunks overlap on two streams (profiling runs use this, so that "
+                         "a kernel's duration is its own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024,
                     help="the oracle is timed on the first this-many tokens of the prompt, fed in the same chunks")
@@ -162,11 +166,21 @@ def main():
         calls = [(chunk, c * chunk) for c in range(n_chunks)]
         tokens_per_step = prompt
 
-        def step():
+        def step_sequential():
             kv.reset()
             for c in range(n_chunks):
                 lo = c * chunk
                 stage.prefill_chunk(hidden[lo:lo + chunk], lo, kv, hidden_out=out[lo:lo + chunk])
+
+        if args.no_overlap or n_chunks < 2:
+            step = step_sequential
+        else:
+            stage.enable_overlap()
+            what += "; one call for the whole prompt, consecutive chunks overlapping on two streams"
+
+            def step():
+                kv.reset()
+                stage.prefill_chunks(hidden, [chunk] * n_chunks, 0, kv, hidden_out=out)
     torch.cuda.synchronize()
     print(f"[bench] inputs ready in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
@@ -198,13 +212,16 @@ def main():
     step_tflops = step_flops / (ms_per_step * 1e-3) / 1e12
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # Second pass: the same steps with an event pair around every launch of one kernel class at a time.
+    # Second pass: the same work with an event pair around every launch of one kernel class at a time, the
+    # chunks one after the other (overlapping chunks share the GPU, and a kernel's duration would include its wait
+    # for the other chunk's kernels).
+    trace_step = step_sequential if wl in ("c2", "c3", "c4") else step
     per_kernel = {}
     for name in ("gemm_gate_up", "gemm_qkv", "gemm_down", "gemm_o", "attention", "rmsnorm"):
         stage.trace(jb.KERNEL_IDS[name], max_launches=4 * cfg["n_layers"] * len(calls) * max(args.steps, 1))
         reps = args.steps if name == "gemm_gate_up" else min(args.steps, 3)
         for _ in range(reps):
-            step()
+            trace_step()
         torch.cuda.synchronize()
         ms, launches, dropped = stage.trace_read()
         per_kernel[name] = {"avg_us": ms / max(launches, 1) * 1e3, "launches_per_step": launches // max(reps, 1),

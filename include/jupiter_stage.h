@@ -218,6 +218,36 @@ JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hid
                                      int32_t pos_offset, jup_kv_t *kv, void *hidden_out, void *stream);
 
 /*
+ * Several consecutive chunks of one prompt in one call (Sec. IV-A.2: the sub-sequences s_1..s_M are injected one
+ * after the other; sub-sequence s_i needs, layer by layer, what the stage cached for s_1..s_{i-1}, and nothing
+ * else of them).  Equal, bit for bit, to n_chunks calls of jup_stage_prefill_chunk() in order, the first at
+ * pos_offset: outputs, cache contents and final length.
+ *   hidden_in     [sum of chunk_tokens, d_model]; the chunks follow each other
+ *   chunk_tokens  HOST array [n_chunks], each 0 .. the stage's max_chunk_tokens
+ *   hidden_out    [sum of chunk_tokens, d_model]; may be the same buffer as hidden_in
+ * After jup_stage_enable_overlap() a JUP_BF16 stage lets consecutive chunks overlap on the GPU: chunk i+1 runs on
+ * a second stream with a scratch buffer of its own and waits, per layer, only for chunk i's cache append before its
+ * attention, so the ramp-up and the tail of one chunk's kernels are filled with the other chunk's work (the paper
+ * fills the stages of a pipeline with sub-sequences in the same way, across devices).  On return all work is
+ * ordered before whatever is enqueued on `stream` next.  Without jup_stage_enable_overlap(), and in check mode,
+ * the chunks simply run one after the other on `stream`.
+ * Errors: as jup_stage_prefill_chunk(); every chunk is validated before anything is enqueued.
+ */
+JUP_API jup_status_t jup_stage_prefill_chunks(jup_stage_t *stage, const void *hidden_in, int32_t n_chunks,
+                                      const int32_t *chunk_tokens, int32_t pos_offset, jup_kv_t *kv,
+                                      void *hidden_out, void *stream);
+
+/*
+ * Gives the stage what jup_stage_prefill_chunks() needs to overlap consecutive chunks: a second scratch buffer
+ * (DEVICE, 256-byte aligned, at least jup_stage_workspace_bytes(cfg, max_chunk_tokens) bytes, borrowed until
+ * jup_stage_destroy()).  Creates one stream of default priority and 2 * n_layers + 2 events, which
+ * jup_stage_destroy() releases.  Call once, not on the hot path.
+ * Errors: JUP_EINVAL (NULL, misaligned, too small, same buffer as the stage's workspace, called twice),
+ * JUP_ENOMEM, JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_stage_enable_overlap(jup_stage_t *stage, void *workspace2, size_t workspace2_bytes);
+
+/*
  * The same stage forward for several branches at once.  In outline-based pipeline parallel decoding the
  * branches of one request are independent sub-sequences over a shared prompt cache (Sec. V-B, Fig. 11),
  * each advanced by a few tokens per step (Sec. V-A: one token plus speculative candidates).  The paper

@@ -66,6 +66,8 @@ def lib():
             "jup_kv_destroy": (i32, [vp]),
             "jup_stage_prefill_chunk": (i32, [vp, vp, i32, i32, vp, vp, vp]),
             "jup_stage_prefill_branches": (i32, [vp, i32, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), vp, vp]),
+            "jup_stage_prefill_chunks": (i32, [vp, vp, i32, ctypes.POINTER(i32), i32, vp, vp, vp]),
+            "jup_stage_enable_overlap": (i32, [vp, vp, sz]),
             "jup_stage_prefill_tree": (i32, [vp, vp, i32, i32, ctypes.POINTER(i32), vp, vp, vp]),
             "jup_stage_trace": (i32, [vp, i32, i32]),
             "jup_stage_trace_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32),
@@ -213,6 +215,27 @@ class Stage:
         _check(lib().jup_stage_prefill_chunk(self.handle, ctypes.c_void_p(hidden_in.data_ptr()), n, int(pos_offset),
                                              kv.handle, ctypes.c_void_p(hidden_out.data_ptr()),
                                              _stream_handle(stream)))
+        return hidden_out
+
+    def enable_overlap(self):
+        """Second scratch buffer (and, inside the library, a second stream) so that prefill_chunks overlaps chunks."""
+        import torch
+        ccfg = make_config(self.cfg, self.dtype)
+        nbytes = lib().jup_stage_workspace_bytes(ctypes.byref(ccfg), self.max_chunk_tokens)
+        self.workspace2 = torch.empty(nbytes, dtype=torch.uint8, device=self.workspace.device)
+        _check(lib().jup_stage_enable_overlap(self.handle, ctypes.c_void_p(self.workspace2.data_ptr()), nbytes))
+
+    def prefill_chunks(self, hidden_in, chunk_tokens, pos_offset, kv, hidden_out=None, stream=None):
+        """hidden_in: [sum(chunk_tokens), d_model]; the chunks follow each other from pos_offset. Returns hidden_out."""
+        import torch
+        k = len(chunk_tokens)
+        assert int(hidden_in.shape[0]) == sum(int(c) for c in chunk_tokens)
+        assert hidden_in.is_contiguous() and hidden_in.dtype == _torch_dtype(self.dtype)
+        if hidden_out is None:
+            hidden_out = torch.empty_like(hidden_in)
+        arr = (ctypes.c_int32 * max(1, k))(*[int(c) for c in chunk_tokens])
+        _check(lib().jup_stage_prefill_chunks(self.handle, ctypes.c_void_p(hidden_in.data_ptr()), k, arr, int(pos_offset),
+                                              kv.handle, ctypes.c_void_p(hidden_out.data_ptr()), _stream_handle(stream)))
         return hidden_out
 
     def prefill_tree(self, hidden_in, pos_offset, parents, kv, hidden_out=None, stream=None):

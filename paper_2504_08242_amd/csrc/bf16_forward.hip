@@ -36,13 +36,15 @@ hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* lay
 // branch b are appended to and attend over cache bt->kv[b] from position bt->pos0[b] (pos and kv are unused).
 // Everything that is not attention or cache traffic sees one [n, d] activation matrix either way, so the
 // stage's weights are streamed once for all branches.
+// link != nullptr: scratch buffer and cross-stream events of a chunk that overlaps with its neighbours.
 // tree != nullptr (host table, bt == nullptr): the n tokens are a token tree; only the rotary positions
 // (pos + depth) and the mask inside the chunk differ from an ordinary chunk.
 hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int pos, const KvView& kv,
-                        void* hidden_out, hipStream_t s, const BranchTable* bt, const TreeTable* tree) {
+                        void* hidden_out, hipStream_t s, const BranchTable* bt, const TreeTable* tree,
+                        const ChunkLink* link) {
     const jup_stage_config_t& c = st.cfg;
     const int d = c.d_model, f = c.d_ffn, H = c.n_heads;
-    char* ws = (char*)st.workspace;
+    char* ws = (char*)(link && link->workspace ? link->workspace : st.workspace);
     float* x32 = (float*)(ws + st.wl.x32);
     u16* xn = (u16*)(ws + st.wl.xn);
     u16* q = (u16*)(ws + st.wl.q);
@@ -89,6 +91,10 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
             a.branches = bt_dev;
             e = launch_gemm_qkv(a, s);
         }
+        // keys and values of this layer are in the cache: the next chunk may attend to them; this chunk needs
+        // those of the chunk before it
+        if (link && link->record_qkv && e == hipSuccess) e = hipEventRecord(link->record_qkv[l], s);
+        if (link && link->wait_qkv && e == hipSuccess) e = hipStreamWaitEvent(s, link->wait_qkv[l], 0);
         {
             TraceScope ts(st, JUP_K_ATTENTION, s);
             if (bt) launch_branch_attention(q, o, bt->n_tok, bt->n_branches, d, H, bt_dev, l, s);

@@ -155,6 +155,7 @@ jup_status_t jup_stage_create(const jup_stage_config_t* cfg, const jup_layer_wei
     st->pl = jup::packed_layout(*cfg);
     st->wl = jup::workspace_layout(*cfg, max_chunk_tokens);
     st->trace = nullptr;
+    st->overlap = nullptr;
 
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
@@ -200,10 +201,58 @@ static void trace_release(jup_stage* st) {
     st->trace = nullptr;
 }
 
+static void overlap_release(jup_stage* st) {
+    jup_overlap* o = st->overlap;
+    if (!o) return;
+    for (int lane = 0; lane < 2; ++lane) {
+        if (!o->ev_qkv[lane]) continue;
+        for (int l = 0; l < st->cfg.n_layers; ++l)
+            if (o->ev_qkv[lane][l]) (void)hipEventDestroy(o->ev_qkv[lane][l]);
+        delete[] o->ev_qkv[lane];
+    }
+    if (o->ev_fork) (void)hipEventDestroy(o->ev_fork);
+    if (o->ev_join) (void)hipEventDestroy(o->ev_join);
+    if (o->stream) (void)hipStreamDestroy(o->stream);
+    delete o;
+    st->overlap = nullptr;
+}
+
 void jup_stage_destroy(jup_stage_t* stage) {
     if (!stage) return;
     trace_release(stage);
+    overlap_release(stage);
     delete stage;
+}
+
+jup_status_t jup_stage_enable_overlap(jup_stage_t* stage, void* workspace2, size_t workspace2_bytes) {
+    const char* me = "jup_stage_enable_overlap";
+    if (!stage) return fail(JUP_EINVAL, "%s: stage is NULL", me);
+    if (stage->overlap) return fail(JUP_EINVAL, "%s: already enabled", me);
+    if (!workspace2 || misaligned(workspace2)) return fail(JUP_EINVAL, "%s: workspace2 must be non-NULL and 256-byte aligned", me);
+    if (workspace2 == stage->workspace) return fail(JUP_EINVAL, "%s: workspace2 must not be the stage's workspace", me);
+    const size_t need = jup_stage_workspace_bytes(&stage->cfg, stage->max_chunk_tokens);
+    if (workspace2_bytes < need) return fail(JUP_EINVAL, "%s: workspace2 has %zu bytes, %zu needed", me, workspace2_bytes, need);
+    jup_overlap* o = new (std::nothrow) jup_overlap();
+    if (!o) return fail(JUP_ENOMEM, "%s: out of host memory", me);
+    const int L = stage->cfg.n_layers;
+    o->workspace = workspace2;
+    stage->overlap = o;  // from here on overlap_release() cleans up whatever exists
+    hipError_t e = hipStreamCreateWithFlags(&o->stream, hipStreamNonBlocking);  // default priority
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&o->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&o->ev_join, hipEventDisableTiming);
+    for (int lane = 0; lane < 2 && e == hipSuccess; ++lane) {
+        o->ev_qkv[lane] = new (std::nothrow) hipEvent_t[L > 0 ? L : 1]();
+        if (!o->ev_qkv[lane]) {
+            overlap_release(stage);
+            return fail(JUP_ENOMEM, "%s: out of host memory", me);
+        }
+        for (int l = 0; l < L && e == hipSuccess; ++l) e = hipEventCreateWithFlags(&o->ev_qkv[lane][l], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+        overlap_release(stage);
+        return fail(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
+    }
+    return JUP_OK;
 }
 
 jup_status_t jup_stage_trace(jup_stage_t* stage, int32_t kernel_id, int32_t max_launches) {
@@ -494,6 +543,88 @@ jup_status_t jup_stage_prefill_tree(jup_stage_t* stage, const void* hidden_in, i
                                     const int32_t* parents, jup_kv_t* kv, void* hidden_out, void* stream) {
     return prefill_one("jup_stage_prefill_tree", stage, hidden_in, n_tokens, pos_offset, parents, true, kv,
                        hidden_out, stream);
+}
+
+jup_status_t jup_stage_prefill_chunks(jup_stage_t* stage, const void* hidden_in, int32_t n_chunks,
+                                      const int32_t* chunk_tokens, int32_t pos_offset, jup_kv_t* kv, void* hidden_out,
+                                      void* stream) {
+    const char* me = "jup_stage_prefill_chunks";
+    if (!stage) return fail(JUP_EINVAL, "%s: stage is NULL", me);
+    if (!kv) return fail(JUP_EINVAL, "%s: kv is NULL", me);
+    if (n_chunks < 0 || (n_chunks > 0 && !chunk_tokens)) return fail(JUP_EINVAL, "%s: bad chunk list", me);
+    if (!same_shape(stage->cfg, kv->cfg)) return fail(JUP_EINVAL, "%s: the cache was made for another configuration", me);
+    // everything is validated before anything is enqueued: the chunks are consecutive, so only the first position
+    // and the total length matter beyond the per-chunk limits
+    long total = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        if (chunk_tokens[c] < 0) return fail(JUP_EINVAL, "%s: chunk_tokens[%d]=%d is negative", me, c, chunk_tokens[c]);
+        if (chunk_tokens[c] > stage->max_chunk_tokens)
+            return fail(JUP_ECAP, "%s: chunk_tokens[%d]=%d exceeds the stage's max_chunk_tokens=%d", me, c, chunk_tokens[c],
+                        stage->max_chunk_tokens);
+        total += chunk_tokens[c];
+    }
+    if (total > INT32_MAX) return fail(JUP_ECAP, "%s: too many tokens", me);
+    jup_status_t rc = jup_kv_check_append(kv, (int32_t)total, pos_offset);
+    if (rc != JUP_OK) {
+        char tmp[400];
+        snprintf(tmp, sizeof(tmp), "%s", g_err);
+        return fail(rc, "%s: %s", me, tmp);
+    }
+    if (kv->parent && kv->parent->len < kv->n_shared)
+        return fail(JUP_EPOS, "%s: the parent cache holds %d positions, fewer than the %d shared", me, kv->parent->len,
+                    kv->n_shared);
+    if (total > 0 && (!hidden_in || !hidden_out)) return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must not be NULL", me);
+
+    const size_t row_bytes = (size_t)stage->cfg.d_model * elem_size(stage->cfg);
+    jup_overlap* o = stage->cfg.dtype == JUP_BF16 && stage->cfg.n_layers > 0 ? stage->overlap : nullptr;
+    int busy = 0;  // chunks with tokens so far
+    for (int c = 0; c < n_chunks; ++c) busy += chunk_tokens[c] > 0;
+    if (!o || busy < 2) {  // one after the other on the caller's stream
+        int32_t pos = pos_offset;
+        const char* in = (const char*)hidden_in;
+        char* out = (char*)hidden_out;
+        for (int c = 0; c < n_chunks; ++c) {
+            rc = prefill_one(me, stage, in, chunk_tokens[c], pos, nullptr, false, kv, out, stream);
+            if (rc != JUP_OK) return rc;
+            pos += chunk_tokens[c];
+            in += (size_t)chunk_tokens[c] * row_bytes;
+            out += (size_t)chunk_tokens[c] * row_bytes;
+        }
+        if (n_chunks == 0 || total == 0) kv->len = pos_offset;
+        return JUP_OK;
+    }
+
+    // Two lanes: chunk number i (among those with tokens) runs on the caller's stream when i is even, on the
+    // stage's second stream when i is odd.  A lane is a stream plus a scratch buffer, so chunks i and i+2 are
+    // ordered by their stream; chunk i+1 waits, layer by layer, for chunk i's cache append before its attention.
+    hipStream_t s0 = (hipStream_t)stream;
+    hipError_t e = hipEventRecord(o->ev_fork, s0);  // the second lane starts behind what the caller enqueued before
+    if (e == hipSuccess) e = hipStreamWaitEvent(o->stream, o->ev_fork, 0);
+    const jup::KvView view = view_of(kv);
+    int32_t pos = pos_offset;
+    const char* in = (const char*)hidden_in;
+    char* out = (char*)hidden_out;
+    int i = 0;
+    for (int c = 0; c < n_chunks && e == hipSuccess; ++c) {
+        const int n = chunk_tokens[c];
+        if (n == 0) continue;
+        const int lane = i & 1;
+        jup::ChunkLink link;
+        link.workspace = lane ? o->workspace : stage->workspace;
+        link.record_qkv = o->ev_qkv[lane];
+        link.wait_qkv = i > 0 ? o->ev_qkv[lane ^ 1] : nullptr;
+        e = jup::bf16_forward(*stage, in, n, pos, view, out, lane ? o->stream : s0, nullptr, nullptr, &link);
+        pos += n;
+        in += (size_t)n * row_bytes;
+        out += (size_t)n * row_bytes;
+        ++i;
+    }
+    // the caller's stream continues when the second lane is done
+    if (e == hipSuccess) e = hipEventRecord(o->ev_join, o->stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(s0, o->ev_join, 0);
+    if (e != hipSuccess) return fail(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
+    kv->len = pos;
+    return JUP_OK;
 }
 
 jup_status_t jup_stage_prefill_branches(jup_stage_t* stage, int32_t n_branches, const void* hidden_in,

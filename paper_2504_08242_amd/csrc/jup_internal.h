@@ -99,6 +99,17 @@ struct jup_trace {
     int32_t dropped;    // launches not timed because the pool was full
 };
 
+// Second lane of jup_stage_prefill_chunks(): consecutive chunks alternate between the caller's stream with the
+// stage's workspace and this stream with a workspace of its own.  ev_qkv[lane][l] is recorded when the lane's
+// current chunk has written its keys and values of layer l; the next chunk (other lane) waits for it before its
+// attention of that layer.
+struct jup_overlap {
+    void* workspace;
+    hipStream_t stream;
+    hipEvent_t ev_fork, ev_join;
+    hipEvent_t* ev_qkv[2];  // [n_layers] each
+};
+
 struct jup_stage {
     jup_stage_config_t cfg;
     void* packed;
@@ -106,7 +117,8 @@ struct jup_stage {
     int32_t max_chunk_tokens;
     jup::PackedLayout pl;
     jup::WorkspaceLayout wl;
-    jup_trace* trace;  // NULL when tracing is off
+    jup_trace* trace;      // NULL when tracing is off
+    jup_overlap* overlap;  // NULL until jup_stage_enable_overlap()
 };
 
 namespace jup {
@@ -138,9 +150,17 @@ hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int p
 
 // ---- matrix-core (bf16) path: kernels_bf16.hip ----------------------------------------------------
 hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s);
+// How one forward is tied to the forwards of the neighbouring chunks (jup_stage_prefill_chunks): which scratch
+// buffer it uses, the events it records after the cache append of every layer, and the events (of the chunk
+// before it, running on the other stream) it waits for before the attention of every layer.
+struct ChunkLink {
+    void* workspace = nullptr;             // nullptr: the stage's own
+    const hipEvent_t* record_qkv = nullptr;  // [n_layers] or nullptr
+    const hipEvent_t* wait_qkv = nullptr;    // [n_layers] or nullptr
+};
 hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int pos, const KvView& kv,
                         void* hidden_out, hipStream_t s, const BranchTable* branches = nullptr,
-                        const TreeTable* tree = nullptr);
+                        const TreeTable* tree = nullptr, const ChunkLink* link = nullptr);
 
 // ---- cache and table helpers: kv_ops.hip --------------------------------------------------------------
 // The tables of a call travel as kernel arguments and are parked in the workspace, where the kernels of the

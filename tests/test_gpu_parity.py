@@ -506,6 +506,70 @@ def test_bf16_tree_node_equals_the_ordinary_call_on_its_path():
         assert rel_l2(g[t], ref[-1]) <= 1e-2, t   # same values, other tile shapes and summation orders
 
 
+def run_chunks_case(p, chunks, pos0_chunks=()):
+    """jup_stage_prefill_chunks against one call per chunk: outputs, cache and length, bit for bit."""
+    import torch
+    total = sum(pos0_chunks) + sum(chunks)
+    h = p.hidden(total)
+    def prefix():
+        p.kv.reset()
+        fill_sentinel(p.kv)
+        pos = 0
+        for n in pos0_chunks:
+            p.gpu_chunk(h[pos:pos + n], pos)
+            pos += n
+        return pos
+    pos0 = prefix()
+    want, pos = [], pos0
+    for n in chunks:
+        want.append(p.gpu_chunk(h[pos:pos + n], pos))
+        pos += n
+    want = np.concatenate(want) if want else np.zeros((0, p.cfg["d_model"]), np.float32)
+    kv_want, len_want = kv_bits(p.kv), len(p.kv)
+    prefix()
+    x = torch.from_numpy(h[pos0:]).to(device="cuda:0", dtype=p.td)
+    y = p.stage.prefill_chunks(x, chunks, pos0, p.kv)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_numpy(y), want)
+    assert len(p.kv) == len_want
+    assert np.array_equal(kv_bits(p.kv), kv_want)
+    return want, h[pos0:]
+
+
+def test_bf16_overlapped_chunks_equal_one_call_per_chunk_bitwise():
+    """Consecutive chunks on two streams: chunk i+1 may only read what chunk i has already cached."""
+    p = Pair(LLAMA7B_2L, "bf16", seed=41, max_positions=700, max_chunk_tokens=192)
+    run_chunks_case(p, [64, 64, 64])                       # not enabled yet: one after the other
+    p.stage.enable_overlap()
+    for rep in range(3):                                    # repeated: a missing dependency shows as a flaky mismatch
+        run_chunks_case(p, [128, 37, 0, 5, 192, 64, 1, 100], pos0_chunks=[50])
+    got, h = run_chunks_case(p, [160, 160, 160, 160])
+    o = [p.oracle.prefill_chunk(h[i * 160:(i + 1) * 160], i * 160) for i in range(4)]
+    p.check(got, np.concatenate(o), "overlapped chunks vs oracle")
+    run_chunks_case(p, [96])                                # a single chunk takes the plain path
+    run_chunks_case(p, [])
+
+
+def test_prefill_chunks_argument_errors_and_check_mode():
+    p = Pair(si.TINY, "f32", seed=42, max_positions=64, max_chunk_tokens=32)
+    run_chunks_case(p, [32, 7, 0, 20])                      # check mode: sequential, same results
+    import torch
+    x = torch.zeros((40, p.cfg["d_model"]), device="cuda:0", dtype=p.td)
+    p.kv.reset()
+    for chunks, status in (([33, 7], jb.JUP_ECAP), ([32, -1, 9], jb.JUP_EINVAL)):
+        with pytest.raises(jb.JupiterError) as ei:
+            p.stage.prefill_chunks(x[:sum(max(c, 0) for c in chunks)], chunks, 0, p.kv)
+        assert ei.value.status == status and len(p.kv) == 0
+    with pytest.raises(jb.JupiterError) as ei:              # the chunks together overflow the cache
+        p.stage.prefill_chunks(torch.zeros((70, p.cfg["d_model"]), device="cuda:0", dtype=p.td), [30, 30, 10], 0, p.kv)
+    assert ei.value.status == jb.JUP_ECAP and len(p.kv) == 0
+    with pytest.raises(jb.JupiterError) as ei:              # a hole before the first chunk
+        p.stage.prefill_chunks(x[:10], [10], 3, p.kv)
+    assert ei.value.status == jb.JUP_EPOS
+    with pytest.raises(jb.JupiterError):                    # check mode has no second lane to enable... but the call is accepted
+        p.stage.enable_overlap(); p.stage.enable_overlap()  # twice is an error
+
+
 def test_bf16_zero_output_projections_pass_input_through_bitwise():
     cfg = LLAMA7B_2L
     layers = si.make_layers(cfg, seed=14, bf16=True)
