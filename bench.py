@@ -68,6 +68,9 @@ def main():
                     help="feed the chunks of a prompt one call after the other instead of one jup_stage_prefill_chunks "
                          "call whose consecutive chunks overlap on two streams (profiling runs use this, so that "
                          "a kernel's duration is its own)")
+    ap.add_argument("--lanes", type=int, default=4,
+                    help="lanes enabled for the overlapped call (2..4; the library uses two of them for chunks above "
+                         "128 tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024,
                     help="the oracle is timed on the first this-many tokens of the prompt, fed in the same chunks")
@@ -175,8 +178,8 @@ def main():
         if args.no_overlap or n_chunks < 2:
             step = step_sequential
         else:
-            stage.enable_overlap()
-            what += "; one call for the whole prompt, consecutive chunks overlapping on two streams"
+            stage.enable_overlap(args.lanes)
+            what += f"; one call for the whole prompt, consecutive chunks overlapping on {2 if chunk > 128 else args.lanes} streams"
 
             def step():
                 kv.reset()

@@ -225,12 +225,15 @@ JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hid
  *   hidden_in     [sum of chunk_tokens, d_model]; the chunks follow each other
  *   chunk_tokens  HOST array [n_chunks], each 0 .. the stage's max_chunk_tokens
  *   hidden_out    [sum of chunk_tokens, d_model]; may be the same buffer as hidden_in
- * After jup_stage_enable_overlap() a JUP_BF16 stage lets consecutive chunks overlap on the GPU: chunk i+1 runs on
- * a second stream with a scratch buffer of its own and waits, per layer, only for chunk i's cache append before its
- * attention, so the ramp-up and the tail of one chunk's kernels are filled with the other chunk's work (the paper
- * fills the stages of a pipeline with sub-sequences in the same way, across devices).  On return all work is
- * ordered before whatever is enqueued on `stream` next.  Without jup_stage_enable_overlap(), and in check mode,
- * the chunks simply run one after the other on `stream`.
+ * After jup_stage_enable_overlap() a JUP_BF16 stage lets consecutive chunks overlap on the GPU: they go round
+ * n_lanes lanes (a stream plus a scratch buffer each; lane 0 is `stream` with the stage's own workspace), and a
+ * chunk waits, per layer, only for the cache appends of the chunks before it before its own attention.  The
+ * ramp-up and the tail of one chunk's kernels are then filled with another chunk's work, and the weights of a
+ * layer that one chunk streamed from HBM are still in the last-level cache when the next chunk asks for them
+ * (the paper fills the stages of a pipeline with sub-sequences in the same way, across devices).  Chunks of more
+ * than 128 tokens use two of the lanes, shorter ones all that were enabled.  On return all
+ * work is ordered before whatever is enqueued on `stream` next.  Without jup_stage_enable_overlap(), and in check
+ * mode, the chunks simply run one after the other on `stream`.
  * Errors: as jup_stage_prefill_chunk(); every chunk is validated before anything is enqueued.
  */
 JUP_API jup_status_t jup_stage_prefill_chunks(jup_stage_t *stage, const void *hidden_in, int32_t n_chunks,
@@ -238,14 +241,17 @@ JUP_API jup_status_t jup_stage_prefill_chunks(jup_stage_t *stage, const void *hi
                                       void *hidden_out, void *stream);
 
 /*
- * Gives the stage what jup_stage_prefill_chunks() needs to overlap consecutive chunks: a second scratch buffer
- * (DEVICE, 256-byte aligned, at least jup_stage_workspace_bytes(cfg, max_chunk_tokens) bytes, borrowed until
- * jup_stage_destroy()).  Creates one stream of default priority and 2 * n_layers + 2 events, which
+ * Gives the stage what jup_stage_prefill_chunks() needs to overlap consecutive chunks on n_lanes lanes
+ * (2 .. JUP_MAX_LANES): scratch for the further lanes, one DEVICE buffer, 256-byte aligned, of at least
+ * (n_lanes - 1) * jup_stage_workspace_bytes(cfg, max_chunk_tokens) bytes, borrowed until jup_stage_destroy().
+ * Creates n_lanes - 1 streams of default priority and n_lanes * (n_layers + 1) events, which
  * jup_stage_destroy() releases.  Call once, not on the hot path.
- * Errors: JUP_EINVAL (NULL, misaligned, too small, same buffer as the stage's workspace, called twice),
- * JUP_ENOMEM, JUP_EDEVICE.
+ * Errors: JUP_EINVAL (NULL, n_lanes out of range, misaligned, too small, overlapping the stage's workspace,
+ * called twice), JUP_ENOMEM, JUP_EDEVICE.
  */
-JUP_API jup_status_t jup_stage_enable_overlap(jup_stage_t *stage, void *workspace2, size_t workspace2_bytes);
+#define JUP_MAX_LANES 4
+JUP_API jup_status_t jup_stage_enable_overlap(jup_stage_t *stage, int32_t n_lanes, void *lane_workspaces,
+                                      size_t lane_workspaces_bytes);
 
 /*
  * The same stage forward for several branches at once.  In outline-based pipeline parallel decoding the

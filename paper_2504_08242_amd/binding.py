@@ -67,7 +67,7 @@ def lib():
             "jup_stage_prefill_chunk": (i32, [vp, vp, i32, i32, vp, vp, vp]),
             "jup_stage_prefill_branches": (i32, [vp, i32, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), vp, vp]),
             "jup_stage_prefill_chunks": (i32, [vp, vp, i32, ctypes.POINTER(i32), i32, vp, vp, vp]),
-            "jup_stage_enable_overlap": (i32, [vp, vp, sz]),
+            "jup_stage_enable_overlap": (i32, [vp, i32, vp, sz]),
             "jup_stage_prefill_tree": (i32, [vp, vp, i32, i32, ctypes.POINTER(i32), vp, vp, vp]),
             "jup_stage_trace": (i32, [vp, i32, i32]),
             "jup_stage_trace_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32),
@@ -217,13 +217,14 @@ class Stage:
                                              _stream_handle(stream)))
         return hidden_out
 
-    def enable_overlap(self):
-        """Second scratch buffer (and, inside the library, a second stream) so that prefill_chunks overlaps chunks."""
+    def enable_overlap(self, n_lanes=2):
+        """Scratch buffers (and, inside the library, streams) for n_lanes - 1 further lanes of prefill_chunks."""
         import torch
         ccfg = make_config(self.cfg, self.dtype)
-        nbytes = lib().jup_stage_workspace_bytes(ctypes.byref(ccfg), self.max_chunk_tokens)
-        self.workspace2 = torch.empty(nbytes, dtype=torch.uint8, device=self.workspace.device)
-        _check(lib().jup_stage_enable_overlap(self.handle, ctypes.c_void_p(self.workspace2.data_ptr()), nbytes))
+        nbytes = lib().jup_stage_workspace_bytes(ctypes.byref(ccfg), self.max_chunk_tokens) * max(1, int(n_lanes) - 1)
+        self.lane_workspaces = torch.empty(nbytes, dtype=torch.uint8, device=self.workspace.device)
+        _check(lib().jup_stage_enable_overlap(self.handle, int(n_lanes), ctypes.c_void_p(self.lane_workspaces.data_ptr()),
+                                              nbytes))
 
     def prefill_chunks(self, hidden_in, chunk_tokens, pos_offset, kv, hidden_out=None, stream=None):
         """hidden_in: [sum(chunk_tokens), d_model]; the chunks follow each other from pos_offset. Returns hidden_out."""

@@ -94,7 +94,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         // keys and values of this layer are in the cache: the next chunk may attend to them; this chunk needs
         // those of the chunk before it
         if (link && link->record_qkv && e == hipSuccess) e = hipEventRecord(link->record_qkv[l], s);
-        if (link && link->wait_qkv && e == hipSuccess) e = hipStreamWaitEvent(s, link->wait_qkv[l], 0);
+        for (int w = 0; link && w < link->n_wait && e == hipSuccess; ++w) e = hipStreamWaitEvent(s, link->wait_qkv[w][l], 0);
         {
             TraceScope ts(st, JUP_K_ATTENTION, s);
             if (bt) launch_branch_attention(q, o, bt->n_tok, bt->n_branches, d, H, bt_dev, l, s);

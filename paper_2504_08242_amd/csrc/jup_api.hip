@@ -204,15 +204,16 @@ static void trace_release(jup_stage* st) {
 static void overlap_release(jup_stage* st) {
     jup_overlap* o = st->overlap;
     if (!o) return;
-    for (int lane = 0; lane < 2; ++lane) {
-        if (!o->ev_qkv[lane]) continue;
-        for (int l = 0; l < st->cfg.n_layers; ++l)
-            if (o->ev_qkv[lane][l]) (void)hipEventDestroy(o->ev_qkv[lane][l]);
-        delete[] o->ev_qkv[lane];
+    for (int lane = 0; lane < jup::kMaxLanes; ++lane) {
+        if (o->ev_qkv[lane]) {
+            for (int l = 0; l < st->cfg.n_layers; ++l)
+                if (o->ev_qkv[lane][l]) (void)hipEventDestroy(o->ev_qkv[lane][l]);
+            delete[] o->ev_qkv[lane];
+        }
+        if (o->ev_join[lane]) (void)hipEventDestroy(o->ev_join[lane]);
+        if (o->stream[lane]) (void)hipStreamDestroy(o->stream[lane]);
     }
     if (o->ev_fork) (void)hipEventDestroy(o->ev_fork);
-    if (o->ev_join) (void)hipEventDestroy(o->ev_join);
-    if (o->stream) (void)hipStreamDestroy(o->stream);
     delete o;
     st->overlap = nullptr;
 }
@@ -224,23 +225,32 @@ void jup_stage_destroy(jup_stage_t* stage) {
     delete stage;
 }
 
-jup_status_t jup_stage_enable_overlap(jup_stage_t* stage, void* workspace2, size_t workspace2_bytes) {
+jup_status_t jup_stage_enable_overlap(jup_stage_t* stage, int32_t n_lanes, void* lane_workspaces,
+                                      size_t lane_workspaces_bytes) {
     const char* me = "jup_stage_enable_overlap";
     if (!stage) return fail(JUP_EINVAL, "%s: stage is NULL", me);
     if (stage->overlap) return fail(JUP_EINVAL, "%s: already enabled", me);
-    if (!workspace2 || misaligned(workspace2)) return fail(JUP_EINVAL, "%s: workspace2 must be non-NULL and 256-byte aligned", me);
-    if (workspace2 == stage->workspace) return fail(JUP_EINVAL, "%s: workspace2 must not be the stage's workspace", me);
-    const size_t need = jup_stage_workspace_bytes(&stage->cfg, stage->max_chunk_tokens);
-    if (workspace2_bytes < need) return fail(JUP_EINVAL, "%s: workspace2 has %zu bytes, %zu needed", me, workspace2_bytes, need);
+    if (n_lanes < 2 || n_lanes > JUP_MAX_LANES) return fail(JUP_EINVAL, "%s: n_lanes=%d is outside 2..%d", me, n_lanes, JUP_MAX_LANES);
+    if (!lane_workspaces || misaligned(lane_workspaces))
+        return fail(JUP_EINVAL, "%s: lane_workspaces must be non-NULL and 256-byte aligned", me);
+    const size_t each = jup_stage_workspace_bytes(&stage->cfg, stage->max_chunk_tokens);  // a multiple of 256
+    const size_t need = each * (size_t)(n_lanes - 1);
+    if (lane_workspaces_bytes < need) return fail(JUP_EINVAL, "%s: lane_workspaces has %zu bytes, %zu needed", me, lane_workspaces_bytes, need);
+    const char* lo = (const char*)lane_workspaces;
+    const char* ws = (const char*)stage->workspace;
+    if (lo < ws + each && ws < lo + need) return fail(JUP_EINVAL, "%s: lane_workspaces overlaps the stage's workspace", me);
     jup_overlap* o = new (std::nothrow) jup_overlap();
     if (!o) return fail(JUP_ENOMEM, "%s: out of host memory", me);
     const int L = stage->cfg.n_layers;
-    o->workspace = workspace2;
+    o->n_lanes = n_lanes;
     stage->overlap = o;  // from here on overlap_release() cleans up whatever exists
-    hipError_t e = hipStreamCreateWithFlags(&o->stream, hipStreamNonBlocking);  // default priority
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&o->ev_fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&o->ev_join, hipEventDisableTiming);
-    for (int lane = 0; lane < 2 && e == hipSuccess; ++lane) {
+    hipError_t e = hipEventCreateWithFlags(&o->ev_fork, hipEventDisableTiming);
+    for (int lane = 0; lane < n_lanes && e == hipSuccess; ++lane) {
+        if (lane > 0) {
+            o->workspace[lane] = (char*)lane_workspaces + each * (size_t)(lane - 1);
+            e = hipStreamCreateWithFlags(&o->stream[lane], hipStreamNonBlocking);  // default priority
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&o->ev_join[lane], hipEventDisableTiming);
+        }
         o->ev_qkv[lane] = new (std::nothrow) hipEvent_t[L > 0 ? L : 1]();
         if (!o->ev_qkv[lane]) {
             overlap_release(stage);
@@ -594,12 +604,20 @@ jup_status_t jup_stage_prefill_chunks(jup_stage_t* stage, const void* hidden_in,
         return JUP_OK;
     }
 
-    // Two lanes: chunk number i (among those with tokens) runs on the caller's stream when i is even, on the
-    // stage's second stream when i is odd.  A lane is a stream plus a scratch buffer, so chunks i and i+2 are
-    // ordered by their stream; chunk i+1 waits, layer by layer, for chunk i's cache append before its attention.
+    // Chunk number i (among those with tokens) runs on lane i mod n_lanes.  A lane is a stream plus a scratch buffer,
+    // so the chunks of one lane are ordered by their stream; against the chunks before it on the other lanes a chunk
+    // waits, layer by layer, for their cache append before its attention.
     hipStream_t s0 = (hipStream_t)stream;
-    hipError_t e = hipEventRecord(o->ev_fork, s0);  // the second lane starts behind what the caller enqueued before
-    if (e == hipSuccess) e = hipStreamWaitEvent(o->stream, o->ev_fork, 0);
+    // Short chunks gain from every lane they get (measured with 64- and 128-token chunks: each further lane hides
+    // more launch gaps and lets more chunks share one pass of the weights through the last-level cache); chunks
+    // that fill the chip by themselves are best with two (a third only adds contention: 4 x 512 tokens, -5 %).
+    int longest = 0;
+    for (int c = 0; c < n_chunks; ++c) longest = chunk_tokens[c] > longest ? chunk_tokens[c] : longest;
+    int n_lanes = longest > 128 ? 2 : o->n_lanes;
+    if (n_lanes > o->n_lanes) n_lanes = o->n_lanes;
+    if (n_lanes > busy) n_lanes = busy;
+    hipError_t e = hipEventRecord(o->ev_fork, s0);  // the other lanes start behind what the caller enqueued before
+    for (int lane = 1; lane < n_lanes && e == hipSuccess; ++lane) e = hipStreamWaitEvent(o->stream[lane], o->ev_fork, 0);
     const jup::KvView view = view_of(kv);
     int32_t pos = pos_offset;
     const char* in = (const char*)hidden_in;
@@ -608,20 +626,23 @@ jup_status_t jup_stage_prefill_chunks(jup_stage_t* stage, const void* hidden_in,
     for (int c = 0; c < n_chunks && e == hipSuccess; ++c) {
         const int n = chunk_tokens[c];
         if (n == 0) continue;
-        const int lane = i & 1;
+        const int lane = i % n_lanes;
         jup::ChunkLink link;
-        link.workspace = lane ? o->workspace : stage->workspace;
+        link.workspace = lane ? o->workspace[lane] : stage->workspace;
         link.record_qkv = o->ev_qkv[lane];
-        link.wait_qkv = i > 0 ? o->ev_qkv[lane ^ 1] : nullptr;
-        e = jup::bf16_forward(*stage, in, n, pos, view, out, lane ? o->stream : s0, nullptr, nullptr, &link);
+        for (int other = 0; other < n_lanes; ++other)  // lanes that already hold a chunk of this call
+            if (other != lane && other < i) link.wait_qkv[link.n_wait++] = o->ev_qkv[other];
+        e = jup::bf16_forward(*stage, in, n, pos, view, out, lane ? o->stream[lane] : s0, nullptr, nullptr, &link);
         pos += n;
         in += (size_t)n * row_bytes;
         out += (size_t)n * row_bytes;
         ++i;
     }
-    // the caller's stream continues when the second lane is done
-    if (e == hipSuccess) e = hipEventRecord(o->ev_join, o->stream);
-    if (e == hipSuccess) e = hipStreamWaitEvent(s0, o->ev_join, 0);
+    // the caller's stream continues when the other lanes are done
+    for (int lane = 1; lane < n_lanes && e == hipSuccess; ++lane) {
+        e = hipEventRecord(o->ev_join[lane], o->stream[lane]);
+        if (e == hipSuccess) e = hipStreamWaitEvent(s0, o->ev_join[lane], 0);
+    }
     if (e != hipSuccess) return fail(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
     kv->len = pos;
     return JUP_OK;

@@ -99,15 +99,18 @@ struct jup_trace {
     int32_t dropped;    // launches not timed because the pool was full
 };
 
-// Second lane of jup_stage_prefill_chunks(): consecutive chunks alternate between the caller's stream with the
-// stage's workspace and this stream with a workspace of its own.  ev_qkv[lane][l] is recorded when the lane's
-// current chunk has written its keys and values of layer l; the next chunk (other lane) waits for it before its
-// attention of that layer.
+// Lanes of jup_stage_prefill_chunks(): consecutive chunks go round the lanes; lane 0 is the caller's stream with
+// the stage's workspace, every further lane a stream and a workspace of its own.  ev_qkv[lane][l] is recorded when
+// the lane's current chunk has written its keys and values of layer l; a chunk waits, before its attention of
+// layer l, for that event of every other lane (the chunks before it that its own stream does not order).
+namespace jup { constexpr int kMaxLanes = JUP_MAX_LANES; }
 struct jup_overlap {
-    void* workspace;
-    hipStream_t stream;
-    hipEvent_t ev_fork, ev_join;
-    hipEvent_t* ev_qkv[2];  // [n_layers] each
+    int32_t n_lanes;
+    void* workspace[jup::kMaxLanes];     // [0] unused
+    hipStream_t stream[jup::kMaxLanes];  // [0] unused
+    hipEvent_t ev_fork;
+    hipEvent_t ev_join[jup::kMaxLanes];  // [0] unused
+    hipEvent_t* ev_qkv[jup::kMaxLanes];  // [n_layers] each
 };
 
 struct jup_stage {
@@ -154,9 +157,10 @@ hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* lay
 // buffer it uses, the events it records after the cache append of every layer, and the events (of the chunk
 // before it, running on the other stream) it waits for before the attention of every layer.
 struct ChunkLink {
-    void* workspace = nullptr;             // nullptr: the stage's own
-    const hipEvent_t* record_qkv = nullptr;  // [n_layers] or nullptr
-    const hipEvent_t* wait_qkv = nullptr;    // [n_layers] or nullptr
+    void* workspace = nullptr;                 // nullptr: the stage's own
+    const hipEvent_t* record_qkv = nullptr;    // [n_layers] or nullptr
+    int n_wait = 0;                            // other lanes that hold an earlier chunk
+    const hipEvent_t* wait_qkv[kMaxLanes] = {};  // [n_layers] each
 };
 hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int pos, const KvView& kv,
                         void* hidden_out, hipStream_t s, const BranchTable* branches = nullptr,

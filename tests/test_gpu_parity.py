@@ -536,11 +536,12 @@ def run_chunks_case(p, chunks, pos0_chunks=()):
     return want, h[pos0:]
 
 
-def test_bf16_overlapped_chunks_equal_one_call_per_chunk_bitwise():
-    """Consecutive chunks on two streams: chunk i+1 may only read what chunk i has already cached."""
+@pytest.mark.parametrize("n_lanes", [2, 3, 4])
+def test_bf16_overlapped_chunks_equal_one_call_per_chunk_bitwise(n_lanes):
+    """Consecutive chunks on several streams: a chunk may only read what the chunks before it have already cached."""
     p = Pair(LLAMA7B_2L, "bf16", seed=41, max_positions=700, max_chunk_tokens=192)
     run_chunks_case(p, [64, 64, 64])                       # not enabled yet: one after the other
-    p.stage.enable_overlap()
+    p.stage.enable_overlap(n_lanes)
     for rep in range(3):                                    # repeated: a missing dependency shows as a flaky mismatch
         run_chunks_case(p, [128, 37, 0, 5, 192, 64, 1, 100], pos0_chunks=[50])
     got, h = run_chunks_case(p, [160, 160, 160, 160])
@@ -566,8 +567,12 @@ def test_prefill_chunks_argument_errors_and_check_mode():
     with pytest.raises(jb.JupiterError) as ei:              # a hole before the first chunk
         p.stage.prefill_chunks(x[:10], [10], 3, p.kv)
     assert ei.value.status == jb.JUP_EPOS
-    with pytest.raises(jb.JupiterError):                    # check mode has no second lane to enable... but the call is accepted
-        p.stage.enable_overlap(); p.stage.enable_overlap()  # twice is an error
+    for bad in (1, 5):
+        with pytest.raises(jb.JupiterError) as ei:
+            p.stage.enable_overlap(bad)
+        assert ei.value.status == jb.JUP_EINVAL
+    with pytest.raises(jb.JupiterError):                    # accepted once (check mode then still runs the chunks in turn)
+        p.stage.enable_overlap(2); p.stage.enable_overlap(2)  # twice is an error
 
 
 def test_bf16_zero_output_projections_pass_input_through_bitwise():

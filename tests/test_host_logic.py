@@ -171,7 +171,7 @@ def test_prefill_chunks_without_a_stage_is_rejected():
     kv = make_kv(16)
     n = (ctypes.c_int32 * 2)(4, 4)
     assert L.jup_stage_prefill_chunks(None, FAKE, 2, n, 0, kv, FAKE, None) == jb.JUP_EINVAL
-    assert L.jup_stage_enable_overlap(None, FAKE, 1 << 20) == jb.JUP_EINVAL
+    assert L.jup_stage_enable_overlap(None, 2, FAKE, 1 << 20) == jb.JUP_EINVAL
     assert L.jup_kv_len(kv) == 0
     L.jup_kv_destroy(kv)
 
