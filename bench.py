@@ -6,8 +6,12 @@ processes a 2048-token prompt chunk by chunk (4 chunks of 512), every chunk atte
 of the earlier ones.  A step is one pass of the whole hot path over that prompt.  Inputs are seeded synthetic
 tensors (hidden ~ N(0,1), weights ~ N(0, 0.02^2)) already resident in HBM when the timed region starts.
 
+A step feeds the whole prompt with ONE jup_stage_prefill_chunks call: consecutive chunks overlap on two streams
+(up to four for chunks of 128 tokens or fewer), each chunk waiting per layer only for the cache appends of the
+chunks before it; --no-overlap feeds them one call after the other.
+
 Prints ONE JSON line.  `roofline` is for the dominant kernel (the gate/up GEMM with the SwiGLU epilogue),
-timed in place with HIP events in a second pass over the same steps; `cpu_baseline` is the CPU oracle
+timed in place with HIP events in a second pass that feeds the chunks one call after the other; `cpu_baseline` is the CPU oracle
 timed on this machine's host cores on a bounded sample of the same workload.
 
 --workload selects the other benchmark configurations (same JSON line; they are reporting runs, the
@@ -245,7 +249,9 @@ def main():
         achieved = dom_bytes / dom_s / 1e9
         roofline = {"bound": "hbm", "kernel": "gemm_bf16<gate_up+swiglu>", "achieved": round(achieved, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4)}
-    roofline.update({"avg_launch_us": round(dom["avg_us"], 2), "flop_per_launch": dom_flops,
+    roofline.update({"timed": "event pairs around each launch in a pass that feeds the chunks one call after the other "
+                              "(in the overlapped call two chunks share the GPU and a launch waits for its share)",
+                     "avg_launch_us": round(dom["avg_us"], 2), "flop_per_launch": dom_flops,
                      "algorithmic_bytes": dom_bytes, "traffic": GATE_UP_TRAFFIC_BYTES.get((wl, chunk)),
                      "traffic_unit": "bytes per launch (offline rocprofv3 counters)"})
 
