@@ -7,7 +7,7 @@ of the earlier ones.  A step is one pass of the whole hot path over that prompt.
 tensors (hidden ~ N(0,1), weights ~ N(0, 0.02^2)) already resident in HBM when the timed region starts.
 
 A step feeds the whole prompt with ONE jup_stage_prefill_chunks call: consecutive chunks overlap on two streams
-(up to four for chunks of 128 tokens or fewer), each chunk waiting per layer only for the cache appends of the
+(up to four for chunks of 256 tokens or fewer), each chunk waiting per layer only for the cache appends of the
 chunks before it; --no-overlap feeds them one call after the other.
 
 Prints ONE JSON line.  `roofline` is for the dominant kernel (the gate/up GEMM with the SwiGLU epilogue),
@@ -74,7 +74,7 @@ def main():
                          "a kernel's duration is its own)")
     ap.add_argument("--lanes", type=int, default=4,
                     help="lanes enabled for the overlapped call (2..4; the library uses two of them for chunks above "
-                         "128 tokens)")
+                         "256 tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024,
                     help="the oracle is timed on the first this-many tokens of the prompt, fed in the same chunks")
@@ -183,7 +183,7 @@ def main():
             step = step_sequential
         else:
             stage.enable_overlap(args.lanes)
-            what += f"; one call for the whole prompt, consecutive chunks overlapping on {2 if chunk > 128 else args.lanes} streams"
+            what += f"; one call for the whole prompt, consecutive chunks overlapping on {2 if chunk > 256 else args.lanes} streams"
 
             def step():
                 kv.reset()

@@ -231,7 +231,7 @@ JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hid
  * ramp-up and the tail of one chunk's kernels are then filled with another chunk's work, and the weights of a
  * layer that one chunk streamed from HBM are still in the last-level cache when the next chunk asks for them
  * (the paper fills the stages of a pipeline with sub-sequences in the same way, across devices).  Chunks of more
- * than 128 tokens use two of the lanes, shorter ones all that were enabled.  On return all
+ * than 256 tokens use two of the lanes, shorter ones all that were enabled.  On return all
  * work is ordered before whatever is enqueued on `stream` next.  Without jup_stage_enable_overlap(), and in check
  * mode, the chunks simply run one after the other on `stream`.
  * Errors: as jup_stage_prefill_chunk(); every chunk is validated before anything is enqueued.
