@@ -1,7 +1,7 @@
 // Orchestration of the bf16 (matrix-core) path: one stage forward over one sub-sequence with its
 // cached prefix (Jupiter paper, Sec. IV-A.2); decoder layer of Sec. II-A in its Llama-2 form.
 //
-// Per layer, seven launches on the caller's stream:
+// Per layer, seven launches on one stream (the caller's, or a lane's stream of the overlapped multi-chunk call):
 //   reduce+norm  ->  QKV GEMM (+ rotary + KV append)  ->  chunk attention  ->  O GEMM (K-split partials)
 //   ->  reduce+norm  ->  gate/up GEMM (+ SwiGLU)  ->  down GEMM (K-split partials)
 // The projections back to d_model are too narrow to fill 256 CUs with tall tiles, so they split K and

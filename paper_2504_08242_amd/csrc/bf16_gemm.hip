@@ -12,7 +12,7 @@
 //     128 x 96 (2 x 2) by 20 % although the latter read a third less from LDS: with one wave per SIMD
 //     every wait of that wave idles the matrix pipe, with two the other wave's MFMAs cover it.
 //     (The 16x16x32 form sustains only ~70 % of the 32x32x16 rate on this chip, measured.)
-//   * K advances in stages of 32 through a 5-stage LDS ring filled by direct global->LDS loads
+//   * K advances in stages of 32 through an LDS ring (as many slots as fit, at most 8) filled by direct global->LDS loads
 //     (16 bytes per lane, no register staging).  A stage holds two K/16 sub-steps; the fragments of
 //     one sub-step are read from LDS while the matrix cores work on the other.
 //   * LDS rows are 64 bytes (32 bf16).  Four rows form a 256-byte super-row; chunk c of row r sits at

@@ -151,7 +151,7 @@ jup_status_t set_error(jup_status_t code, const char* fmt, ...) __attribute__((f
 hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int pos, const KvView& kv,
                        float* hidden_out, hipStream_t s, const TreeTable* tree = nullptr);
 
-// ---- matrix-core (bf16) path: kernels_bf16.hip ----------------------------------------------------
+// ---- matrix-core (bf16) path: bf16_forward.hip (and bf16_gemm / bf16_attention / bf16_misc) ----------------------------------------------------
 hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s);
 // How one forward is tied to the forwards of the neighbouring chunks (jup_stage_prefill_chunks): which scratch
 // buffer it uses, the events it records after the cache append of every layer, and the events (of the chunk
