@@ -618,6 +618,18 @@ def test_c3_7b_stage_2048_tokens_chunk_sizes_128_to_2048():
         kv = p.kv_gpu()
         for l in range(8):
             assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, (size, l)
+        if size == 512:
+            g512, kv512 = g, kv_bits(p.kv)
+    # the launch configuration of the benchmark: the whole prompt in one call, chunks overlapping on the GPU
+    import torch
+    p.stage.enable_overlap(4)
+    x = torch.from_numpy(hidden).to(device="cuda:0", dtype=p.td)
+    for chunks in ([512] * 4, [128] * 16):
+        p.kv.reset()
+        y = to_numpy(p.stage.prefill_chunks(x, chunks, 0, p.kv))
+        p.check(y, o, f"one call, chunks {chunks[0]}")
+        if chunks[0] == 512:
+            assert np.array_equal(y, g512) and np.array_equal(kv_bits(p.kv), kv512)
 
 
 @pytest.mark.slow
