@@ -597,6 +597,19 @@ def test_c2_7b_stage_512_tokens_in_8_chunks_of_64():
     kv = p.kv_gpu()
     for l in range(8):
         assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, l
+    assert_one_call_equals(p, hidden, [64] * 8, g)
+
+
+def assert_one_call_equals(p, hidden, chunks, want):
+    """The benchmark's launch configuration: the prompt in one call, chunks overlapping on four lanes."""
+    import torch
+    bits = kv_bits(p.kv)
+    p.stage.enable_overlap(4)
+    p.kv.reset()
+    x = torch.from_numpy(hidden).to(device="cuda:0", dtype=p.td)
+    y = to_numpy(p.stage.prefill_chunks(x, chunks, 0, p.kv))
+    assert np.array_equal(y, want)
+    assert np.array_equal(kv_bits(p.kv), bits)
 
 
 @pytest.mark.slow
@@ -648,6 +661,7 @@ def test_c4_13b_stage_1024_tokens_in_8_chunks_of_128():
     kv = p.kv_gpu()
     for l in range(10):
         assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, l
+    assert_one_call_equals(p, hidden, [128] * 8, np.concatenate(g))
 
 
 @pytest.mark.slow
