@@ -100,8 +100,8 @@ __device__ inline float max_across_halves(float x) {
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-template <int NQ>
-__global__ __launch_bounds__(256 * NQ + 256) void chunk_attention_bf16(const u16* __restrict__ q, u16* __restrict__ o,
+template <int NQ, int LPQ = 1>
+__global__ __launch_bounds__(256 * NQ + 256 * LPQ) void chunk_attention_bf16(const u16* __restrict__ q, u16* __restrict__ o,
                                                                   int n, int d_model, int n_heads, int pos0_arg,
                                                                   KvView kv_arg, int layer, float scale_log2e,
                                                                   const BranchTable* __restrict__ branches,
@@ -113,8 +113,12 @@ __global__ __launch_bounds__(256 * NQ + 256) void chunk_attention_bf16(const u16
     // key quarter.  A global->LDS load holds the issuing wave for about a hundred cycles (the address path of a
     // CU takes 64 bytes per clock, and all quarters refill at the same moment): issued by the computing waves,
     // the loads of a round cost them as much as the round's arithmetic.
+    // LPQ = 2: two loader waves per key quarter, one for the K part of a tile and one for the V part (a single wave
+    // issues a 1 KB load every 64 cycles at best; with one query block per workgroup the round is as long as
+    // the fill, and two loaders halve it).
     const bool loader = wave >= 4 * NQ;
     const int g = wave & 3, qb = loader ? 0 : wave >> 2;
+    const int lpart = LPQ == 2 ? (wave - 4 * NQ) >> 2 : -1;  // loader: 0 = K only, 1 = V only, -1 = both
     const int c = lane & 31, hh = lane >> 5;
     const int head = blockIdx.x % n_heads;
     const int q_blocks = (n + NQ * 32 - 1) / (NQ * 32);
@@ -174,8 +178,8 @@ __global__ __launch_bounds__(256 * NQ + 256) void chunk_attention_bf16(const u16
             }
         };
         auto fill = [&](int tile, int slot) __attribute__((always_inline)) {
-            fill_part(tile, slot, false);
-            fill_part(tile, slot, true);
+            if (lpart != 1) fill_part(tile, slot, false);
+            if (lpart != 0) fill_part(tile, slot, true);
         };
         if (cnt > 0) fill(g, 0);
         for (int it = 0; it < max_cnt; ++it) {
@@ -361,7 +365,7 @@ __global__ __launch_bounds__(256 * NQ + 256) void chunk_attention_bf16(const u16
                                 oacc[db][4 * gg + 2] * wscale, oacc[db][4 * gg + 3] * wscale);
     }
     __syncthreads();
-    for (int idx = tid; idx < NQ * 32 * 16; idx += 256 * NQ) {
+    for (int idx = tid; idx < NQ * 32 * 16; idx += 256 * NQ) {  // the computing threads (tid < 256 NQ)
         const int qr = idx >> 4, ch = idx & 15;
         const int qrow = q0 + qr;
         if (qrow >= n) continue;
@@ -391,20 +395,22 @@ __global__ __launch_bounds__(256 * NQ + 256) void chunk_attention_bf16(const u16
 }  // namespace
 
 hipError_t attention_configure() {
-    hipError_t e = hipFuncSetAttribute((const void*)chunk_attention_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)chunk_attention_bf16<1, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        kAttLds);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute((const void*)chunk_attention_bf16<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                kAttLds);
 }
 
-// Block sizes: 4 NQ computing waves + 4 loader waves.
+// Block sizes: 4 NQ computing waves + 4 loader waves per part loaded separately.  Chunks of up to 64 tokens run
+// one query block per workgroup with separate K and V loaders (decode-sized attention is a chain of short
+// rounds, each as long as its tile fill); longer chunks two query blocks sharing every tile.
 void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
                             int layer, hipStream_t s, const TreeTable* tree) {
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
     const BranchTable* none = nullptr;
-    if (n <= 32)
-        hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3((n + 31) / 32 * n_heads), dim3(512), kAttLds, s, q, o, n,
+    if (n <= 64)
+        hipLaunchKernelGGL((chunk_attention_bf16<1, 2>), dim3((n + 31) / 32 * n_heads), dim3(768), kAttLds, s, q, o, n,
                            d_model, n_heads, pos0, kv, layer, scale_log2e, none, tree);
     else
         hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(768), kAttLds, s, q, o, n,
@@ -416,8 +422,8 @@ void launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
     const KvView none{};
     const TreeTable* no_tree = nullptr;
-    if (n <= 32)
-        hipLaunchKernelGGL(chunk_attention_bf16<1>, dim3(n_branches * ((n + 31) / 32) * n_heads), dim3(512), kAttLds,
+    if (n <= 64)
+        hipLaunchKernelGGL((chunk_attention_bf16<1, 2>), dim3(n_branches * ((n + 31) / 32) * n_heads), dim3(768), kAttLds,
                            s, q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches, no_tree);
     else
         hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3(n_branches * ((n + 63) / 64) * n_heads), dim3(768), kAttLds,
