@@ -93,6 +93,7 @@ struct GemmArgs {
     KvView kv;
     int layer, n_heads, d_model, pos0;
     const BranchTable* branches;  // non-null: row m belongs to branch m / n_tok (kv and pos0 above are unused)
+    bool shared_gpu;     // another chunk's kernels run beside this launch (overlapped multi-chunk call)
     // EPI_PARTIAL
     float* partial;  // [splits][M][N] fp32
     // EPI_SWIGLU

@@ -89,6 +89,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
             a.A = xn; a.W = (const u16*)(wb + st.pl.wqkv); a.M = n; a.N = 3 * d; a.K = d;
             a.q_out = q; a.rope = rope; a.kv = kv; a.layer = l; a.n_heads = H; a.d_model = d; a.pos0 = pos;
             a.branches = bt_dev;
+            a.shared_gpu = link != nullptr;
             e = launch_gemm_qkv(a, s);
         }
         // keys and values of this layer are in the cache: the next chunk may attend to them; this chunk needs

@@ -451,22 +451,25 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
     } else {  // EPI_QKV
         // Packed column 32j + 16a + c' of a Q/K head is rotary index 16j + c' + 64a (a = 0/1: partners i and
         // i + 64); V columns keep their order.  The accumulators go through a wave-private fp32 strip
-        // [32*MBW rows][32*NBW columns] in LDS; then a lane rotates 8 consecutive indices of one row and stores
-        // 16 bytes.
+        // [32 rows][32*NBW columns] in LDS, one row block of the wave at a time; then a lane rotates 8 consecutive
+        // indices of one row and stores 16 bytes.
         constexpr int SW = 32 * NBW + 8;  // strip row stride in floats (rows 4 apart fall 32 banks apart)
         __builtin_amdgcn_s_barrier();     // every wave is done with the ring (no reads or DMA in flight)
-        float* strip = (float*)smem + wave * (WROWS * SW);
+        // one row block (32 rows) of the wave at a time, so that the strips of all waves fit the ring's LDS
+        static_assert(S::WAVES * 32 * SW * 4 <= S::LDS_BYTES, "epilogue strips exceed the LDS of the ring");
+        float* strip = (float*)smem + wave * (32 * SW);
+        // lane = 4 * row_in_pass + sub: 16 rows per pass, sub picks 8 of a block's 32 packed columns
+        const int sub = lane & 3, rl0 = lane >> 2;
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb) {
+        if (mb > 0) __builtin_amdgcn_wave_barrier();  // the strip reads of the block before are done (lgkmcnt 0 below)
 #pragma unroll
         for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-            for (int mb = 0; mb < MBW; ++mb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    strip[(mb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3)) * SW + nb * 32 + c] = acc[mb][nb][i];
+            for (int i = 0; i < 16; ++i)
+                strip[(8 * (i >> 2) + 4 * hh + (i & 3)) * SW + nb * 32 + c] = acc[mb][nb][i];
         wait_lgkmcnt0();
         __builtin_amdgcn_wave_barrier();
-        // lane = 4 * row_in_pass + sub: 16 rows per pass, sub picks 8 of a block's 32 packed columns
-        const int sub = lane & 3, rl0 = lane >> 2;
 #pragma unroll
         for (int nb = 0; nb < NBW; ++nb) {
             const int col = nw0 + nb * 32;  // packed column of the block: one (q|k|v, head, j) for all lanes
@@ -489,9 +492,9 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
                 stride = 0;
             }
 #pragma unroll
-            for (int p = 0; p < WROWS / 16; ++p) {
+            for (int p = 0; p < 2; ++p) {
                 const int rl = p * 16 + rl0;
-                const int m = m0 + wm * WROWS + rl;
+                const int m = m0 + wm * WROWS + mb * 32 + rl;
                 if (m >= a.M) continue;
                 u16* out_ptr;
                 if (which != 0 && a.branches) {  // row m is token t of branch b: that branch's cache and position
@@ -527,6 +530,8 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
                 for (int e2 = 0; e2 < 4; ++e2) out[e2] = pack_bf16x2(v[2 * e2], v[2 * e2 + 1]);
                 *(u32x4*)out_ptr = out;
             }
+        }
+        wait_lgkmcnt0();  // this block's strip reads have returned before the next block overwrites the strip
         }
     }
 #if GEMM_TIMELINE
@@ -581,7 +586,7 @@ hipError_t configure_one() {
 #define GEMM_LW 0
 #endif
 #define JUP_GEMM_SHAPES(X)                                                          \
-    X(8, 1, 4, 1, EPI_QKV, 0) X(8, 2, 4, 1, EPI_QKV, 0) X(8, 3, 8, 1, EPI_QKV, GEMM_LW)            \
+    X(8, 1, 4, 1, EPI_QKV, 0) X(8, 2, 4, 1, EPI_QKV, 0) X(8, 3, 8, 1, EPI_QKV, GEMM_LW) X(8, 6, 4, 2, EPI_QKV, 0)            \
     X(4, 2, 4, 1, EPI_QKV, 0) X(2, 2, 2, 2, EPI_QKV, 0)                                   \
     X(8, 2, 4, 1, EPI_SWIGLU, 0) X(8, 3, 4, 1, EPI_SWIGLU, 0) X(8, 4, 4, 2, EPI_SWIGLU, 0) X(8, 6, 4, 2, EPI_SWIGLU, GEMM_LW) \
     X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0) X(4, 3, 4, 1, EPI_SWIGLU, 0) X(2, 3, 2, 3, EPI_SWIGLU, 0) \
@@ -651,6 +656,10 @@ hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s) {
     if (bmb == 4) return launch<4, 2, 4, 1, EPI_QKV>(a, s);
     static const int cands[] = {1, 2, 3};
     const int nb = pick_blocks(a.M, a.N, cands, 3);
+    // Beside another chunk's kernels (overlapped multi-chunk call) half as many tiles of twice the width do the
+    // same work in a quarter less CU time, and the other chunk uses the CUs they leave free: 76 us instead of 59 us
+    // for this launch alone, but +1.7 % for the 4 x 512 prompt.  Alone on the chip the narrow tile wins (-6 %).
+    if (nb == 3 && a.shared_gpu && a.M > 256) return launch<8, 6, 4, 2, EPI_QKV, 0>(a, s);
     if (nb == 3) return launch<8, 3, 8, 1, EPI_QKV, GEMM_LW>(a, s);  // 8 waves of 32 x 96: measured 1.3 % faster than 4 of 64 x 96
     if (nb == 2) return launch<8, 2, 4, 1, EPI_QKV>(a, s);
     return launch<8, 1, 4, 1, EPI_QKV>(a, s);
