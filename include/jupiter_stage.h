@@ -220,8 +220,11 @@ JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hid
 /*
  * Several consecutive chunks of one prompt in one call (Sec. IV-A.2: the sub-sequences s_1..s_M are injected one
  * after the other; sub-sequence s_i needs, layer by layer, what the stage cached for s_1..s_{i-1}, and nothing
- * else of them).  Equal, bit for bit, to n_chunks calls of jup_stage_prefill_chunk() in order, the first at
- * pos_offset: outputs, cache contents and final length.
+ * else of them).  Computes what n_chunks calls of jup_stage_prefill_chunk() in order compute, the first at
+ * pos_offset: the same cache entries are written, the final length is the same, and without
+ * jup_stage_enable_overlap() outputs and cache values are equal bit for bit.  With it they are equal up to the
+ * summation order of fp32 partial sums (the projections back to d_model split K into fewer pieces while other
+ * chunks share the GPU), i.e. to the last bits of a bf16 value; the call is deterministic either way.
  *   hidden_in     [sum of chunk_tokens, d_model]; the chunks follow each other
  *   chunk_tokens  HOST array [n_chunks], each 0 .. the stage's max_chunk_tokens
  *   hidden_out    [sum of chunk_tokens, d_model]; may be the same buffer as hidden_in
@@ -230,8 +233,9 @@ JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hid
  * chunk waits, per layer, only for the cache appends of the chunks before it before its own attention.  The
  * ramp-up and the tail of one chunk's kernels are then filled with another chunk's work, and the weights of a
  * layer that one chunk streamed from HBM are still in the last-level cache when the next chunk asks for them
- * (the paper fills the stages of a pipeline with sub-sequences in the same way, across devices).  Chunks of more
- * than 256 tokens use two of the lanes, shorter ones all that were enabled.  On return all
+ * (the paper fills the stages of a pipeline with sub-sequences in the same way, across devices).  Chunks of up
+ * to 256 tokens use all enabled lanes; longer ones all of them when their number is a multiple of four, else two.
+ * On return all
  * work is ordered before whatever is enqueued on `stream` next.  Without jup_stage_enable_overlap(), and in check
  * mode, the chunks simply run one after the other on `stream`.
  * Errors: as jup_stage_prefill_chunk(); every chunk is validated before anything is enqueued.

@@ -105,7 +105,7 @@ enum GemmKind { GEMM_QKV, GEMM_O, GEMM_GATE_UP, GEMM_DOWN };
 
 // Fills the tiling fields of `a` for the given problem and launches.  Returns the number of K splits
 // used (the caller sums that many partial buffers for EPI_PARTIAL).
-int gemm_plan_splits(int M, int N, int K);
+int gemm_plan_splits(int M, int N, int K, bool shared);  // shared: see GemmArgs::shared_gpu
 hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s);
 hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s);
 hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s);

@@ -69,7 +69,8 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         launch_rope_table(rope, n, pos, c.rope_theta, s);
     }
 
-    const int splits_o = gemm_plan_splits(n, d, d), splits_down = gemm_plan_splits(n, d, f);
+    const bool shared = link != nullptr;  // other chunks' kernels run beside this chunk's
+    const int splits_o = gemm_plan_splits(n, d, d, shared), splits_down = gemm_plan_splits(n, d, f, shared);
     hipError_t e = hipSuccess;
     for (int l = 0; l < c.n_layers && e == hipSuccess; ++l) {
         const char* wb = (const char*)st.packed + (size_t)l * st.pl.layer_bytes;
@@ -89,7 +90,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
             a.A = xn; a.W = (const u16*)(wb + st.pl.wqkv); a.M = n; a.N = 3 * d; a.K = d;
             a.q_out = q; a.rope = rope; a.kv = kv; a.layer = l; a.n_heads = H; a.d_model = d; a.pos0 = pos;
             a.branches = bt_dev;
-            a.shared_gpu = link != nullptr;
+            a.shared_gpu = shared;
             e = launch_gemm_qkv(a, s);
         }
         // keys and values of this layer are in the cache: the next chunk may attend to them; this chunk needs
@@ -104,7 +105,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         {
             TraceScope ts(st, JUP_K_GEMM_O, s);
             GemmArgs a{};
-            a.A = o; a.W = (const u16*)(wb + st.pl.wo); a.M = n; a.N = d; a.K = d; a.partial = partial;
+            a.A = o; a.W = (const u16*)(wb + st.pl.wo); a.M = n; a.N = d; a.K = d; a.partial = partial; a.shared_gpu = shared;
             if (e == hipSuccess) e = launch_gemm_partial(a, s);
         }
         {
@@ -120,7 +121,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         {
             TraceScope ts(st, JUP_K_GEMM_DOWN, s);
             GemmArgs a{};
-            a.A = act; a.W = (const u16*)(wb + st.pl.wdown); a.M = n; a.N = d; a.K = f; a.partial = partial;
+            a.A = act; a.W = (const u16*)(wb + st.pl.wdown); a.M = n; a.N = d; a.K = f; a.partial = partial; a.shared_gpu = shared;
             if (e == hipSuccess) e = launch_gemm_partial(a, s);
         }
     }

@@ -626,7 +626,17 @@ int gemm_partial_col_blocks(int M, int N, int K) {
     return stages_wide < (bmb == 2 ? 64 : 32) ? 2 : 4;
 }
 
-int gemm_plan_splits(int M, int N, int K) { return splits_for(M, N, K, gemm_partial_col_blocks(M, N, K)); }
+// shared: another chunk's kernels run beside this launch (overlapped multi-chunk call).  Filling the chip with one
+// launch then matters less than the work per output: at most two splits (half or a quarter of the partial sums to
+// write and read back, longer K loops per workgroup); the CUs a launch leaves free go to the other chunks.
+// Measured on the 7B shapes with four lanes: 4 x 512 tokens 274k -> 286k tokens/s, 8 x 256 tokens 204k -> 224k,
+// 16 x 128 and 8 x 64 tokens +3-4 % (no split at all: -4 % there); alone on the chip the same cap costs 8 % (one
+// launch then has to fill it).
+int gemm_plan_splits(int M, int N, int K, bool shared) {
+    int s = splits_for(M, N, K, gemm_partial_col_blocks(M, N, K));
+    const int cap = shared ? 2 : 8;
+    return s > cap ? cap : s;
+}
 
 namespace {
 // Among the instantiated widths (in 32-column blocks) of the 256-row tile, the one with the least work on the
@@ -683,7 +693,7 @@ hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
 }
 
 hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
-    a.splits = gemm_plan_splits(a.M, a.N, a.K);
+    a.splits = gemm_plan_splits(a.M, a.N, a.K, a.shared_gpu);
     const int bmb = pick_row_blocks(a.M);
     const bool narrow = gemm_partial_col_blocks(a.M, a.N, a.K) == 2;
     if (bmb == 2) return narrow ? launch<2, 2, 2, 2, EPI_PARTIAL>(a, s) : launch<2, 4, 2, 2, EPI_PARTIAL>(a, s);

@@ -609,11 +609,12 @@ jup_status_t jup_stage_prefill_chunks(jup_stage_t* stage, const void* hidden_in,
     // waits, layer by layer, for their cache append before its attention.
     hipStream_t s0 = (hipStream_t)stream;
     // Short chunks gain from every lane they get (measured with 64-, 128- and 256-token chunks: each further lane hides
-    // more launch gaps and lets more chunks share one pass of the weights through the last-level cache); chunks
-    // that fill the chip by themselves are best with two (a third only adds contention: 4 x 512 tokens, -5 %).
+    // more launch gaps and lets more chunks share one pass of the weights through the last-level cache).  Longer
+    // chunks take all four lanes when their number is a multiple of four and two otherwise: with 4 x 512 tokens
+    // on three lanes the fourth chunk queues behind the first and ends up running alone (-6 %).
     int longest = 0;
     for (int c = 0; c < n_chunks; ++c) longest = chunk_tokens[c] > longest ? chunk_tokens[c] : longest;
-    int n_lanes = longest > 256 ? 2 : o->n_lanes;
+    int n_lanes = longest > 256 && busy % 4 != 0 ? 2 : o->n_lanes;
     if (n_lanes > o->n_lanes) n_lanes = o->n_lanes;
     if (n_lanes > busy) n_lanes = busy;
     hipError_t e = hipEventRecord(o->ev_fork, s0);  // the other lanes start behind what the caller enqueued before

@@ -506,8 +506,14 @@ def test_bf16_tree_node_equals_the_ordinary_call_on_its_path():
         assert rel_l2(g[t], ref[-1]) <= 1e-2, t   # same values, other tile shapes and summation orders
 
 
-def run_chunks_case(p, chunks, pos0_chunks=()):
-    """jup_stage_prefill_chunks against one call per chunk: outputs, cache and length, bit for bit."""
+def assert_same_cache_entries(got_bits, want_bits, sentinel_bits):
+    """The same entries were written (everything else still holds the sentinel), whatever their values."""
+    assert np.array_equal(got_bits == sentinel_bits, want_bits == sentinel_bits)
+
+
+def run_chunks_case(p, chunks, pos0_chunks=(), exact=True):
+    """jup_stage_prefill_chunks against one call per chunk: outputs, cache and length.  Bit for bit when the chunks
+    run one after the other; up to fp32 summation order (fewer K splits) when they overlap."""
     import torch
     total = sum(pos0_chunks) + sum(chunks)
     h = p.hidden(total)
@@ -525,26 +531,40 @@ def run_chunks_case(p, chunks, pos0_chunks=()):
         want.append(p.gpu_chunk(h[pos:pos + n], pos))
         pos += n
     want = np.concatenate(want) if want else np.zeros((0, p.cfg["d_model"]), np.float32)
-    kv_want, len_want = kv_bits(p.kv), len(p.kv)
+    kv_want, kvv_want, len_want = kv_bits(p.kv), p.kv_gpu(), len(p.kv)
     prefix()
     x = torch.from_numpy(h[pos0:]).to(device="cuda:0", dtype=p.td)
-    y = p.stage.prefill_chunks(x, chunks, pos0, p.kv)
+    y = to_numpy(p.stage.prefill_chunks(x, chunks, pos0, p.kv))
     torch.cuda.synchronize()
-    assert np.array_equal(to_numpy(y), want)
     assert len(p.kv) == len_want
-    assert np.array_equal(kv_bits(p.kv), kv_want)
-    return want, h[pos0:]
+    if exact:
+        assert np.array_equal(y, want)
+        assert np.array_equal(kv_bits(p.kv), kv_want)
+    else:
+        sentinel = np.int32(0x7FC12345) if p.dtype == "f32" else np.int16(0x7FC1)
+        assert_same_cache_entries(kv_bits(p.kv), kv_want, sentinel)
+        if len(want):
+            assert rel_l2(y, want) <= 4e-3, rel_l2(y, want)      # bf16 last-bit differences after two layers
+            live = kv_want != sentinel
+            assert rel_l2(p.kv_gpu()[live], kvv_want[live]) <= 4e-3
+        # deterministic: the same call again gives the same bits
+        bits1 = kv_bits(p.kv)
+        prefix()
+        y2 = to_numpy(p.stage.prefill_chunks(x, chunks, pos0, p.kv))
+        assert np.array_equal(y2, y) and np.array_equal(kv_bits(p.kv), bits1)
+    return y, h[pos0:]
 
 
 @pytest.mark.parametrize("n_lanes", [2, 3, 4])
-def test_bf16_overlapped_chunks_equal_one_call_per_chunk_bitwise(n_lanes):
-    """Consecutive chunks on several streams: a chunk may only read what the chunks before it have already cached."""
+def test_bf16_overlapped_chunks_equal_one_call_per_chunk(n_lanes):
+    """Consecutive chunks on several streams: a chunk may only read what the chunks before it have already cached.
+    A missing dependency would show as a mismatch far above rounding, or as a run-to-run difference."""
     p = Pair(LLAMA7B_2L, "bf16", seed=41, max_positions=700, max_chunk_tokens=192)
     run_chunks_case(p, [64, 64, 64])                       # not enabled yet: one after the other
     p.stage.enable_overlap(n_lanes)
     for rep in range(3):                                    # repeated: a missing dependency shows as a flaky mismatch
-        run_chunks_case(p, [128, 37, 0, 5, 192, 64, 1, 100], pos0_chunks=[50])
-    got, h = run_chunks_case(p, [160, 160, 160, 160])
+        run_chunks_case(p, [128, 37, 0, 5, 192, 64, 1, 100], pos0_chunks=[50], exact=False)
+    got, h = run_chunks_case(p, [160, 160, 160, 160], exact=False)
     o = [p.oracle.prefill_chunk(h[i * 160:(i + 1) * 160], i * 160) for i in range(4)]
     p.check(got, np.concatenate(o), "overlapped chunks vs oracle")
     run_chunks_case(p, [96])                                # a single chunk takes the plain path
@@ -597,19 +617,23 @@ def test_c2_7b_stage_512_tokens_in_8_chunks_of_64():
     kv = p.kv_gpu()
     for l in range(8):
         assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, l
-    assert_one_call_equals(p, hidden, [64] * 8, g)
+    p.check(assert_one_call_equals(p, hidden, [64] * 8, g), o, "one call, overlapped")
 
 
 def assert_one_call_equals(p, hidden, chunks, want):
-    """The benchmark's launch configuration: the prompt in one call, chunks overlapping on four lanes."""
+    """The benchmark's launch configuration: the prompt in one call, chunks overlapping on four lanes.  Against the
+    oracle at the parity bar, and against one call per chunk up to fp32 summation order."""
     import torch
-    bits = kv_bits(p.kv)
+    kv_want = p.kv_gpu()
     p.stage.enable_overlap(4)
     p.kv.reset()
     x = torch.from_numpy(hidden).to(device="cuda:0", dtype=p.td)
     y = to_numpy(p.stage.prefill_chunks(x, chunks, 0, p.kv))
-    assert np.array_equal(y, want)
-    assert np.array_equal(kv_bits(p.kv), bits)
+    assert len(p.kv) == sum(chunks)
+    # bf16 last-bit differences, compounded over the 8-10 layers of these stages (GPU vs oracle is ~1e-2 here)
+    assert rel_l2(y, want) <= 1.2e-2, rel_l2(y, want)
+    assert rel_l2(p.kv_gpu(), kv_want) <= 8e-3, rel_l2(p.kv_gpu(), kv_want)
+    return y
 
 
 @pytest.mark.slow
@@ -632,7 +656,7 @@ def test_c3_7b_stage_2048_tokens_chunk_sizes_128_to_2048():
         for l in range(8):
             assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, (size, l)
         if size == 512:
-            g512, kv512 = g, kv_bits(p.kv)
+            g512 = g
     # the launch configuration of the benchmark: the whole prompt in one call, chunks overlapping on the GPU
     import torch
     p.stage.enable_overlap(4)
@@ -642,7 +666,10 @@ def test_c3_7b_stage_2048_tokens_chunk_sizes_128_to_2048():
         y = to_numpy(p.stage.prefill_chunks(x, chunks, 0, p.kv))
         p.check(y, o, f"one call, chunks {chunks[0]}")
         if chunks[0] == 512:
-            assert np.array_equal(y, g512) and np.array_equal(kv_bits(p.kv), kv512)
+            assert rel_l2(y, g512) <= 1.2e-2, rel_l2(y, g512)   # fewer K splits: fp32 summation order differs
+            kv1 = p.kv_gpu()
+            for l in range(8):
+                assert rel_l2(kv1[l], p.oracle.kv[l]) <= BF16_REL_L2, l
 
 
 @pytest.mark.slow
@@ -661,7 +688,7 @@ def test_c4_13b_stage_1024_tokens_in_8_chunks_of_128():
     kv = p.kv_gpu()
     for l in range(10):
         assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, l
-    assert_one_call_equals(p, hidden, [128] * 8, np.concatenate(g))
+    p.check(assert_one_call_equals(p, hidden, [128] * 8, np.concatenate(g)), np.concatenate(o), "one call, overlapped")
 
 
 @pytest.mark.slow
