@@ -115,7 +115,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         {
             TraceScope ts(st, JUP_K_GEMM_GATE_UP, s);
             GemmArgs a{};
-            a.A = xn; a.W = (const u16*)(wb + st.pl.wgu); a.M = n; a.N = 2 * f; a.K = d; a.act = act;
+            a.A = xn; a.W = (const u16*)(wb + st.pl.wgu); a.M = n; a.N = 2 * f; a.K = d; a.act = act; a.shared_gpu = shared;
             if (e == hipSuccess) e = launch_gemm_swiglu(a, s);
         }
         {

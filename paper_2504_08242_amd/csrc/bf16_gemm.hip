@@ -589,7 +589,7 @@ hipError_t configure_one() {
     X(8, 1, 4, 1, EPI_QKV, 0) X(8, 2, 4, 1, EPI_QKV, 0) X(8, 3, 8, 1, EPI_QKV, GEMM_LW) X(8, 6, 4, 2, EPI_QKV, 0)            \
     X(4, 2, 4, 1, EPI_QKV, 0) X(2, 2, 2, 2, EPI_QKV, 0)                                   \
     X(8, 2, 4, 1, EPI_SWIGLU, 0) X(8, 3, 4, 1, EPI_SWIGLU, 0) X(8, 4, 4, 2, EPI_SWIGLU, 0) X(8, 6, 4, 2, EPI_SWIGLU, GEMM_LW) \
-    X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0) X(4, 3, 4, 1, EPI_SWIGLU, 0) X(2, 3, 2, 3, EPI_SWIGLU, 0) \
+    X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0) X(4, 3, 4, 1, EPI_SWIGLU, 0) X(2, 3, 2, 3, EPI_SWIGLU, 0) X(4, 6, 4, 1, EPI_SWIGLU, 0) X(2, 6, 2, 3, EPI_SWIGLU, 0) \
     X(8, 4, 4, 2, EPI_PARTIAL, GEMM_LW) X(4, 4, 4, 1, EPI_PARTIAL, 0) X(2, 4, 2, 2, EPI_PARTIAL, 0) X(2, 2, 2, 2, EPI_PARTIAL, 0) X(4, 2, 4, 1, EPI_PARTIAL, 0)
 
 hipError_t gemm_configure() {
@@ -681,6 +681,11 @@ hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
     // A short chunk is bound by streaming the weights, and every CU that streams adds bandwidth: the narrower
     // tile (96 columns) when its tiles still fit one round of workgroups (measured at 64 rows, N = 22016:
     // 230 workgroups 38.0 us, 172 workgroups of 128 columns 40.9 us, 344 of 64 columns 47.1 us).
+    // Beside other chunks' kernels (overlapped multi-chunk call) the opposite holds: 192-column tiles, fewer and
+    // longer-running workgroups, and the other chunks take the CUs they leave (64-token chunks +1.5 %, 128-token
+    // chunks +2.5 %, the 13B shapes +4 % over 128 columns, which in turn beat 96 by 2-6 % there).
+    if (a.shared_gpu && bmb == 2) return launch<2, 6, 2, 3, EPI_SWIGLU>(a, s);
+    if (a.shared_gpu && bmb == 4) return launch<4, 6, 4, 1, EPI_SWIGLU>(a, s);
     const bool narrow = div_up(a.N, 96) <= kCUs;
     if (bmb == 2) return narrow ? launch<2, 3, 2, 3, EPI_SWIGLU>(a, s) : launch<2, 4, 2, 2, EPI_SWIGLU>(a, s);
     if (bmb == 4) return narrow ? launch<4, 3, 4, 1, EPI_SWIGLU>(a, s) : launch<4, 4, 4, 1, EPI_SWIGLU>(a, s);
