@@ -588,9 +588,9 @@ hipError_t configure_one() {
 #define JUP_GEMM_SHAPES(X)                                                          \
     X(8, 1, 4, 1, EPI_QKV, 0) X(8, 2, 4, 1, EPI_QKV, 0) X(8, 3, 8, 1, EPI_QKV, GEMM_LW) X(8, 6, 4, 2, EPI_QKV, 0)            \
     X(4, 2, 4, 1, EPI_QKV, 0) X(2, 2, 2, 2, EPI_QKV, 0)                                   \
-    X(8, 2, 4, 1, EPI_SWIGLU, 0) X(8, 3, 4, 1, EPI_SWIGLU, 0) X(8, 4, 4, 2, EPI_SWIGLU, 0) X(8, 6, 4, 2, EPI_SWIGLU, GEMM_LW) \
+    X(8, 2, 4, 1, EPI_SWIGLU, 0) X(8, 3, 4, 1, EPI_SWIGLU, 0) X(8, 4, 4, 2, EPI_SWIGLU, 0) X(8, 6, 4, 2, EPI_SWIGLU, GEMM_LW) X(8, 8, 4, 2, EPI_SWIGLU, 0) \
     X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0) X(4, 3, 4, 1, EPI_SWIGLU, 0) X(2, 3, 2, 3, EPI_SWIGLU, 0) X(4, 6, 4, 1, EPI_SWIGLU, 0) X(2, 6, 2, 3, EPI_SWIGLU, 0) \
-    X(8, 4, 4, 2, EPI_PARTIAL, GEMM_LW) X(4, 4, 4, 1, EPI_PARTIAL, 0) X(2, 4, 2, 2, EPI_PARTIAL, 0) X(2, 2, 2, 2, EPI_PARTIAL, 0) X(4, 2, 4, 1, EPI_PARTIAL, 0)
+    X(8, 4, 4, 2, EPI_PARTIAL, GEMM_LW) X(8, 8, 4, 2, EPI_PARTIAL, 0) X(4, 4, 4, 1, EPI_PARTIAL, 0) X(2, 4, 2, 2, EPI_PARTIAL, 0) X(2, 2, 2, 2, EPI_PARTIAL, 0) X(4, 2, 4, 1, EPI_PARTIAL, 0)
 
 hipError_t gemm_configure() {
     hipError_t e = hipSuccess;
@@ -633,7 +633,9 @@ int gemm_partial_col_blocks(int M, int N, int K) {
 // 16 x 128 and 8 x 64 tokens +3-4 % (no split at all: -4 % there); alone on the chip the same cap costs 8 % (one
 // launch then has to fill it).
 int gemm_plan_splits(int M, int N, int K, bool shared) {
-    int s = splits_for(M, N, K, gemm_partial_col_blocks(M, N, K));
+    // prefill-sized chunks beside other chunks' kernels: 256 x 256 tiles (see launch_gemm_partial)
+    const int nb = shared && pick_row_blocks(M) >= 8 ? 8 : gemm_partial_col_blocks(M, N, K);
+    const int s = splits_for(M, N, K, nb);
     const int cap = shared ? 2 : 8;
     return s > cap ? cap : s;
 }
@@ -691,6 +693,8 @@ hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
     if (bmb == 4) return narrow ? launch<4, 3, 4, 1, EPI_SWIGLU>(a, s) : launch<4, 4, 4, 1, EPI_SWIGLU>(a, s);
     static const int cands[] = {2, 3, 4, 6};
     const int nb = pick_blocks(a.M, a.N, cands, 4);
+    // beside other chunks' kernels: the widest tile (see launch_gemm_qkv); 256 x 256 over 256 x 192: +1.9 %
+    if (nb == 6 && a.shared_gpu) return launch<8, 8, 4, 2, EPI_SWIGLU, 0>(a, s);
     if (nb == 6) return launch<8, 6, 4, 2, EPI_SWIGLU, GEMM_LW>(a, s);
     if (nb == 4) return launch<8, 4, 4, 2, EPI_SWIGLU>(a, s);
     if (nb == 3) return launch<8, 3, 4, 1, EPI_SWIGLU>(a, s);
@@ -703,6 +707,8 @@ hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
     const bool narrow = gemm_partial_col_blocks(a.M, a.N, a.K) == 2;
     if (bmb == 2) return narrow ? launch<2, 2, 2, 2, EPI_PARTIAL>(a, s) : launch<2, 4, 2, 2, EPI_PARTIAL>(a, s);
     if (bmb == 4) return narrow ? launch<4, 2, 4, 1, EPI_PARTIAL>(a, s) : launch<4, 4, 4, 1, EPI_PARTIAL>(a, s);
+    // beside other chunks' kernels: the widest tile, as for QKV and gate/up (256 x 256 over 256 x 128: +2.4 %)
+    if (a.shared_gpu) return launch<8, 8, 4, 2, EPI_PARTIAL, 0>(a, s);
     return launch<8, 4, 4, 2, EPI_PARTIAL, GEMM_LW>(a, s);
 }
 
