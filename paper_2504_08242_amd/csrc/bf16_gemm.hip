@@ -633,8 +633,8 @@ int gemm_partial_col_blocks(int M, int N, int K) {
 // 16 x 128 and 8 x 64 tokens +3-4 % (no split at all: -4 % there); alone on the chip the same cap costs 8 % (one
 // launch then has to fill it).
 int gemm_plan_splits(int M, int N, int K, bool shared) {
-    // prefill-sized chunks beside other chunks' kernels: 256 x 256 tiles (see launch_gemm_partial)
-    const int nb = shared && pick_row_blocks(M) >= 8 ? 8 : gemm_partial_col_blocks(M, N, K);
+    // beside other chunks' kernels: the widest tile of the chunk's row count (see launch_gemm_partial)
+    const int nb = shared ? (pick_row_blocks(M) >= 8 ? 8 : 4) : gemm_partial_col_blocks(M, N, K);
     const int s = splits_for(M, N, K, nb);
     const int cap = shared ? 2 : 8;
     return s > cap ? cap : s;
@@ -704,7 +704,8 @@ hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
 hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
     a.splits = gemm_plan_splits(a.M, a.N, a.K, a.shared_gpu);
     const int bmb = pick_row_blocks(a.M);
-    const bool narrow = gemm_partial_col_blocks(a.M, a.N, a.K) == 2;
+    // (short chunks beside other chunks' kernels keep the 128-column tile: 64-token chunks +3 %, 128-token +5 %)
+    const bool narrow = gemm_partial_col_blocks(a.M, a.N, a.K) == 2 && !a.shared_gpu;
     if (bmb == 2) return narrow ? launch<2, 2, 2, 2, EPI_PARTIAL>(a, s) : launch<2, 4, 2, 2, EPI_PARTIAL>(a, s);
     if (bmb == 4) return narrow ? launch<4, 2, 4, 1, EPI_PARTIAL>(a, s) : launch<4, 4, 4, 1, EPI_PARTIAL>(a, s);
     // beside other chunks' kernels: the widest tile, as for QKV and gate/up (256 x 256 over 256 x 128: +2.4 %)
