@@ -64,9 +64,10 @@ __device__ inline int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i
 constexpr int kKT = 32;                 // keys per tile
 constexpr int kTileBytes = kKT * 256;   // one K or V tile: 32 rows of 128 bf16
 constexpr int kSlotBytes = 2 * kTileBytes;
-constexpr int kWaveLds = 2 * kSlotBytes;  // two slots (K + V each) per key quarter = 32 KB
-// dynamic LDS: the merge at the end needs four fp32 [64][132] regions plus the statistics
-constexpr int kStatOffset = 4 * 64 * 132 * 4;               // softmax statistics of the four quarters (past the tile slots)
+constexpr int kWaveLds = 2 * kSlotBytes;  // two slots (K + V each) per key partition = 32 KB
+// dynamic LDS: the merge at the end needs KP fp32 [32 NQ][132] regions plus the statistics; KP * NQ = 8 at most, so
+// the sizes below (KP = 4 partitions of 64 queries, or 2 of 128) cover every instantiation
+constexpr int kStatOffset = 4 * 64 * 132 * 4;               // softmax statistics (past the tile slots and the regions)
 static_assert(kStatOffset >= 4 * kWaveLds, "the statistics are written while other waves still read their slots");
 constexpr int kAttLds = kStatOffset + 2 * 4 * 64 * 4;
 static_assert(kAttLds >= 4 * kWaveLds && kAttLds <= 160 * 1024, "LDS budget");
@@ -100,8 +101,8 @@ __device__ inline float max_across_halves(float x) {
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-template <int NQ, int LPQ = 1>
-__global__ __launch_bounds__(256 * NQ + 256 * LPQ) void chunk_attention_bf16(const u16* __restrict__ q, u16* __restrict__ o,
+template <int NQ, int LPQ = 1, int KP = 4>
+__global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(const u16* __restrict__ q, u16* __restrict__ o,
                                                                   int n, int d_model, int n_heads, int pos0_arg,
                                                                   KvView kv_arg, int layer, float scale_log2e,
                                                                   const BranchTable* __restrict__ branches,
@@ -116,9 +117,12 @@ __global__ __launch_bounds__(256 * NQ + 256 * LPQ) void chunk_attention_bf16(con
     // LPQ = 2: two loader waves per key quarter, one for the K part of a tile and one for the V part (a single wave
     // issues a 1 KB load every 64 cycles at best; with one query block per workgroup the round is as long as
     // the fill, and two loaders halve it).
-    const bool loader = wave >= 4 * NQ;
-    const int g = wave & 3, qb = loader ? 0 : wave >> 2;
-    const int lpart = LPQ == 2 ? (wave - 4 * NQ) >> 2 : -1;  // loader: 0 = K only, 1 = V only, -1 = both
+    // KP = number of key partitions (4 quarters, or 2 halves for 128 queries per workgroup: each tile then serves
+    // twice the queries, which halves the bytes filled per flop).
+    static_assert(KP * NQ <= 8 && (KP == 2 || KP == 4), "LDS regions and statistics are sized for 8 x 32 query rows");
+    const bool loader = wave >= KP * NQ;
+    const int g = wave % KP, qb = loader ? 0 : wave / KP;
+    const int lpart = LPQ == 2 ? (wave - KP * NQ) / KP : -1;  // loader: 0 = K only, 1 = V only, -1 = both
     const int c = lane & 31, hh = lane >> 5;
     const int head = blockIdx.x % n_heads;
     const int q_blocks = (n + NQ * 32 - 1) / (NQ * 32);
@@ -141,8 +145,8 @@ __global__ __launch_bounds__(256 * NQ + 256 * LPQ) void chunk_attention_bf16(con
     const size_t plane_k = ((size_t)layer * 2 + 0) * n_heads + head;
     const size_t plane_v = ((size_t)layer * 2 + 1) * n_heads + head;
 
-    const int cnt = n_tiles > g ? (n_tiles - g + 3) / 4 : 0;  // tiles of this key quarter
-    const int max_cnt = (n_tiles + 3) / 4;                    // of quarter 0: every wave runs that many rounds
+    const int cnt = n_tiles > g ? (n_tiles - g + KP - 1) / KP : 0;  // tiles of this key partition
+    const int max_cnt = (n_tiles + KP - 1) / KP;                    // of partition 0: every wave runs that many rounds
     if (loader) {
         // The whole life of a loader wave: one tile ahead of the computing waves, the same barriers as they.
         // Tile fill (loader waves).  Load j covers rows 4j..4j+3 (1 KB of LDS); lane i lands at
@@ -185,7 +189,7 @@ __global__ __launch_bounds__(256 * NQ + 256 * LPQ) void chunk_attention_bf16(con
         for (int it = 0; it < max_cnt; ++it) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the tile of this round has landed
             __builtin_amdgcn_s_barrier();                     // ... and the other slot is free
-            if (it + 1 < cnt) fill(g + 4 * (it + 1), (it + 1) & 1);
+            if (it + 1 < cnt) fill(g + KP * (it + 1), (it + 1) & 1);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();  // the two barriers of the merge
@@ -232,7 +236,7 @@ __global__ __launch_bounds__(256 * NQ + 256 * LPQ) void chunk_attention_bf16(con
         ATT_T(tb);
         if (it >= cnt) continue;
         ATT_T(t0);
-        const int tile = g + 4 * it, slot = it & 1;
+        const int tile = g + KP * it, slot = it & 1;
         const unsigned char* k_base = grp + slot * kSlotBytes;
         const unsigned v_base = grp_addr + slot * kSlotBytes + kTileBytes;
 
@@ -330,29 +334,31 @@ __global__ __launch_bounds__(256 * NQ + 256 * LPQ) void chunk_attention_bf16(con
     const unsigned long long tl_loop_end = __builtin_amdgcn_s_memtime();
 #endif
 
-    // ---- merge the four key quarters of every query block ----------------------------------------------------------
+    // ---- merge the key partitions of every query block -------------------------------------------------------------
     constexpr int kORow = 132;
-    constexpr int kRegion = 64 * kORow;                     // floats per key quarter: [64 queries][132]
+    constexpr int QR = 32 * NQ;                             // query rows of the workgroup
+    constexpr int kRegion = QR * kORow;                     // floats per key partition: [QR queries][132]
+    static_assert(KP * kRegion * 4 <= kStatOffset, "merge regions overlap the statistics");
     float* obuf = (float*)lds;
-    float* stat_m = (float*)(lds + kStatOffset);            // [4][64]
-    float* stat_l = stat_m + 4 * 64;
+    float* stat_m = (float*)(lds + kStatOffset);            // [KP][QR]
+    float* stat_l = stat_m + KP * QR;
     {
         const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
         if (hh == 0) {
-            stat_m[g * 64 + qb * 32 + c] = m_run;
-            stat_l[g * 64 + qb * 32 + c] = l_tot;
+            stat_m[g * QR + qb * 32 + c] = m_run;
+            stat_l[g * QR + qb * 32 + c] = l_tot;
         }
     }
     __syncthreads();  // statistics visible; every wave is done with the tile slots
     {
         float m_all = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) m_all = fmaxf(m_all, stat_m[w * 64 + qb * 32 + c]);
+        for (int w = 0; w < KP; ++w) m_all = fmaxf(m_all, stat_m[w * QR + qb * 32 + c]);
         float l_all = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float mw = stat_m[w * 64 + qb * 32 + c];
-            l_all += mw == -INFINITY ? 0.f : stat_l[w * 64 + qb * 32 + c] * exp2f(mw - m_all);
+        for (int w = 0; w < KP; ++w) {
+            const float mw = stat_m[w * QR + qb * 32 + c];
+            l_all += mw == -INFINITY ? 0.f : stat_l[w * QR + qb * 32 + c] * exp2f(mw - m_all);
         }
         const float wscale = m_run == -INFINITY ? 0.f : exp2f(m_run - m_all) / l_all;
         float* mine = obuf + g * kRegion + (qb * 32 + c) * kORow;
@@ -365,14 +371,14 @@ __global__ __launch_bounds__(256 * NQ + 256 * LPQ) void chunk_attention_bf16(con
                                 oacc[db][4 * gg + 2] * wscale, oacc[db][4 * gg + 3] * wscale);
     }
     __syncthreads();
-    for (int idx = tid; idx < NQ * 32 * 16; idx += 256 * NQ) {  // the computing threads (tid < 256 NQ)
+    for (int idx = tid; idx < QR * 16; idx += 64 * KP * NQ) {  // the computing threads (tid < 64 KP NQ)
         const int qr = idx >> 4, ch = idx & 15;
         const int qrow = q0 + qr;
         if (qrow >= n) continue;
         const float* src = obuf + qr * kORow + ch * 8;
         float4 a = *(const float4*)src, b = *(const float4*)(src + 4);
 #pragma unroll
-        for (int w = 1; w < 4; ++w) {
+        for (int w = 1; w < KP; ++w) {
             const float4 a2 = *(const float4*)(src + w * kRegion), b2 = *(const float4*)(src + w * kRegion + 4);
             a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
             b.x += b2.x; b.y += b2.y; b.z += b2.z; b.w += b2.w;
@@ -398,6 +404,9 @@ hipError_t attention_configure() {
     hipError_t e = hipFuncSetAttribute((const void*)chunk_attention_bf16<1, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        kAttLds);
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)chunk_attention_bf16<4, 2, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kAttLds);
+    if (e != hipSuccess) return e;
     return hipFuncSetAttribute((const void*)chunk_attention_bf16<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                kAttLds);
 }
@@ -406,9 +415,18 @@ hipError_t attention_configure() {
 // one query block per workgroup with separate K and V loaders (decode-sized attention is a chain of short
 // rounds, each as long as its tile fill); longer chunks two query blocks sharing every tile.
 void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
-                            int layer, hipStream_t s, const TreeTable* tree) {
+                            int layer, hipStream_t s, const TreeTable* tree, bool shared_gpu) {
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
     const BranchTable* none = nullptr;
+    // Beside other chunks' kernels (overlapped multi-chunk call): 128 queries per workgroup against two key halves,
+    // half as many workgroups, each tile filled once for twice the queries.  Alone on the chip this is slower (half
+    // the CUs idle: 33.7 vs 20.1 us at 512 queries over 1536 cached keys); beside other chunks it takes a sixth less
+    // CU time: 4 x 512 tokens +2.4 %, no difference at 256-token chunks.
+    if (shared_gpu && n > 256) {
+        hipLaunchKernelGGL((chunk_attention_bf16<4, 2, 2>), dim3((n + 127) / 128 * n_heads), dim3(768), kAttLds, s, q, o,
+                           n, d_model, n_heads, pos0, kv, layer, scale_log2e, none, tree);
+        return;
+    }
     if (n <= 64)
         hipLaunchKernelGGL((chunk_attention_bf16<1, 2>), dim3((n + 31) / 32 * n_heads), dim3(768), kAttLds, s, q, o, n,
                            d_model, n_heads, pos0, kv, layer, scale_log2e, none, tree);

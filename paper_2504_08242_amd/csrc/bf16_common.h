@@ -116,7 +116,7 @@ hipError_t gemm_configure();  // raises the dynamic-LDS limit of every instantia
 hipError_t attention_configure();  // raises the dynamic-LDS limit (once per process)
 // tree (device pointer, may be null): inside the chunk a query sees the tokens of its row of the table only
 void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
-                            int layer, hipStream_t s, const TreeTable* tree = nullptr);
+                            int layer, hipStream_t s, const TreeTable* tree = nullptr, bool shared_gpu = false);
 // n_branches chunks of n tokens each (rows b*n .. b*n+n-1 of q and o), every one against its own cache
 void launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_model, int n_heads,
                              const BranchTable* branches, int layer, hipStream_t s);

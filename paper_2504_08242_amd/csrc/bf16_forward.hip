@@ -100,7 +100,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         {
             TraceScope ts(st, JUP_K_ATTENTION, s);
             if (bt) launch_branch_attention(q, o, bt->n_tok, bt->n_branches, d, H, bt_dev, l, s);
-            else launch_chunk_attention(q, o, n, d, H, pos, kv, l, s, tree_dev);
+            else launch_chunk_attention(q, o, n, d, H, pos, kv, l, s, tree_dev, shared);
         }
         {
             TraceScope ts(st, JUP_K_GEMM_O, s);
