@@ -673,6 +673,38 @@ def test_c3_7b_stage_2048_tokens_chunk_sizes_128_to_2048():
 
 
 @pytest.mark.slow
+def test_bf16_long_prefix_8192_cached_positions():
+    """One 7B-shaped layer behind a long prompt: the 8192-token prefix goes in as one overlapped call of 2048-token
+    chunks; then a 512-token chunk, a ragged short one and a 26-node token tree attend over more than 8192 cached
+    positions (several hundred key tiles per query block, rotary angles at large positions)."""
+    import torch
+    cfg = dict(si.LLAMA7B_STAGE, n_layers=1)
+    n_prefix = 8192
+    p = Pair(cfg, "bf16", seed=60, max_positions=n_prefix + 640, max_chunk_tokens=2048)
+    hidden = p.hidden(n_prefix + 512 + 37 + 26)
+    o = []
+    for s in range(0, n_prefix, 1024):
+        o.append(p.oracle.prefill_chunk(hidden[s:s + 1024], s))
+        print(f"oracle prefix chunk at {s} done", flush=True)
+    p.stage.enable_overlap(4)
+    x = torch.from_numpy(hidden[:n_prefix]).to(device="cuda:0", dtype=p.td)
+    g = to_numpy(p.stage.prefill_chunks(x, [2048] * 4, 0, p.kv))
+    p.check(g, np.concatenate(o), "prefix")
+    p.check(g[-2048:], np.concatenate(o)[-2048:], "last prefix chunk")
+    pos = n_prefix
+    for n in (512, 37):
+        h = hidden[pos:pos + n]
+        p.check(p.gpu_chunk(h, pos), p.oracle.prefill_chunk(h, pos), f"chunk of {n} at {pos}")
+        pos += n
+    parents = si.make_token_tree(26, 60)
+    h = hidden[pos:pos + 26]
+    p.check(p.gpu_tree(h, pos, parents), p.oracle.prefill_tree(h, parents, pos), f"tree at {pos}")
+    kv = p.kv_gpu()[0][:, :, :pos + 26]
+    for which in range(2):
+        assert rel_l2(kv[which], p.oracle.kv[0, which, :, :pos + 26]) <= BF16_REL_L2, which
+
+
+@pytest.mark.slow
 def test_c4_13b_stage_1024_tokens_in_8_chunks_of_128():
     """Config 4: 10 layers of Llama-2-13B shape, bf16, 1024 tokens as 8x128."""
     p = Pair(si.LLAMA13B_STAGE, "bf16", seed=40, max_positions=1024, max_chunk_tokens=128)
