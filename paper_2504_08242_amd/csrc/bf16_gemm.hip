@@ -587,7 +587,7 @@ hipError_t configure_one() {
 #endif
 #define JUP_GEMM_SHAPES(X)                                                          \
     X(8, 1, 4, 1, EPI_QKV, 0) X(8, 2, 4, 1, EPI_QKV, 0) X(8, 3, 8, 1, EPI_QKV, GEMM_LW) X(8, 6, 4, 2, EPI_QKV, 0)            \
-    X(4, 2, 4, 1, EPI_QKV, 0) X(2, 2, 2, 2, EPI_QKV, 0)                                   \
+    X(4, 2, 4, 1, EPI_QKV, 0) X(2, 2, 2, 2, EPI_QKV, 0) X(4, 3, 4, 1, EPI_QKV, 0)                                                            \
     X(8, 2, 4, 1, EPI_SWIGLU, 0) X(8, 3, 4, 1, EPI_SWIGLU, 0) X(8, 4, 4, 2, EPI_SWIGLU, 0) X(8, 6, 4, 2, EPI_SWIGLU, GEMM_LW) X(8, 8, 4, 2, EPI_SWIGLU, 0) \
     X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0) X(4, 3, 4, 1, EPI_SWIGLU, 0) X(2, 3, 2, 3, EPI_SWIGLU, 0) X(4, 6, 4, 1, EPI_SWIGLU, 0) X(2, 6, 2, 3, EPI_SWIGLU, 0) \
     X(8, 4, 4, 2, EPI_PARTIAL, GEMM_LW) X(8, 8, 4, 2, EPI_PARTIAL, 0) X(4, 4, 4, 1, EPI_PARTIAL, 0) X(2, 4, 2, 2, EPI_PARTIAL, 0) X(2, 2, 2, 2, EPI_PARTIAL, 0) X(4, 2, 4, 1, EPI_PARTIAL, 0)
@@ -664,6 +664,10 @@ int pick_blocks(int M, int N, const int* cands, int n_cands) {
 hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s) {
     a.splits = 1;
     const int bmb = pick_row_blocks(a.M);
+    // 128-token chunks beside other chunks' kernels: 96-column tiles (half again as much work per workgroup; alone on
+    // the chip 64 columns win, 24.0 vs 28.8 us at 64 rows).  Measured with four lanes: 13B shapes, 8 x 128 tokens
+    // +2 %; 7B shapes, 16 x 128 tokens +0-1 %; 192 columns +4 % and -1 %; 64-token chunks no difference either way.
+    if (a.shared_gpu && bmb == 4) return launch<4, 3, 4, 1, EPI_QKV>(a, s);
     if (bmb == 2) return launch<2, 2, 2, 2, EPI_QKV>(a, s);
     if (bmb == 4) return launch<4, 2, 4, 1, EPI_QKV>(a, s);
     static const int cands[] = {1, 2, 3};
