@@ -6,9 +6,9 @@ processes a 2048-token prompt chunk by chunk (4 chunks of 512), every chunk atte
 of the earlier ones.  A step is one pass of the whole hot path over that prompt.  Inputs are seeded synthetic
 tensors (hidden ~ N(0,1), weights ~ N(0, 0.02^2)) already resident in HBM when the timed region starts.
 
-A step feeds the whole prompt with ONE jup_stage_prefill_chunks call: consecutive chunks overlap on two streams
-(up to four for chunks of 256 tokens or fewer), each chunk waiting per layer only for the cache appends of the
-chunks before it; --no-overlap feeds them one call after the other.
+A step feeds the whole prompt with ONE jup_stage_prefill_chunks call: consecutive chunks overlap on up to four
+streams (two for chunks above 256 tokens whose number is not a multiple of four), each chunk waiting per layer only
+for the cache appends of the chunks before it; --no-overlap feeds them one call after the other.
 
 Prints ONE JSON line.  `roofline` is for the dominant kernel (the gate/up GEMM with the SwiGLU epilogue),
 timed in place with HIP events in a second pass that feeds the chunks one call after the other; `cpu_baseline` is the CPU oracle
@@ -70,11 +70,11 @@ def main():
                     help="workload c5: all 8 branches in one jup_stage_prefill_branches call per step")
     ap.add_argument("--no-overlap", action="store_true",
                     help="feed the chunks of a prompt one call after the other instead of one jup_stage_prefill_chunks "
-                         "call whose consecutive chunks overlap on two streams (profiling runs use this, so that "
+                         "call whose consecutive chunks overlap on several streams (profiling runs use this, so that "
                          "a kernel's duration is its own)")
     ap.add_argument("--lanes", type=int, default=4,
-                    help="lanes enabled for the overlapped call (2..4; the library uses two of them for chunks above "
-                         "256 tokens)")
+                    help="lanes enabled for the overlapped call (2..4; for chunks above 256 tokens the library uses all "
+                         "of them only when the number of chunks is a multiple of four, else two)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024,
                     help="the oracle is timed on the first this-many tokens of the prompt, fed in the same chunks")
@@ -183,7 +183,9 @@ def main():
             step = step_sequential
         else:
             stage.enable_overlap(args.lanes)
-            what += f"; one call for the whole prompt, consecutive chunks overlapping on {2 if chunk > 256 else args.lanes} streams"
+            # the library's lane rule (jup_stage_prefill_chunks)
+            lanes_used = min(2 if chunk > 256 and n_chunks % 4 else args.lanes, n_chunks)
+            what += f"; one call for the whole prompt, consecutive chunks overlapping on {lanes_used} streams"
 
             def step():
                 kv.reset()
