@@ -606,6 +606,42 @@ def test_bf16_zero_output_projections_pass_input_through_bitwise():
     assert np.array_equal(p.gpu_chunk(hidden, 0), hidden)
 
 
+@pytest.mark.parametrize("d_model,n_heads,d_ffn,n_layers", [(256, 2, 128, 3), (768, 6, 896, 2), (1536, 12, 4224, 2)])
+def test_bf16_small_and_odd_stage_shapes(d_model, n_heads, d_ffn, n_layers):
+    """The smallest widths the bf16 path accepts and widths that are no power of two: K loops of one to a few stages
+    per workgroup, tiles wider than the matrix, the generic reduce + norm, every row-tile height (chunks of 5 to 200
+    tokens), a token tree and an overlapped multi-chunk call."""
+    import torch
+    cfg = dict(si.LLAMA7B_STAGE, d_model=d_model, n_heads=n_heads, d_ffn=d_ffn, n_layers=n_layers)
+    p = Pair(cfg, "bf16", seed=70 + n_heads, max_positions=900, max_chunk_tokens=200)
+    chunks = [5, 64, 100, 200, 31]
+    hidden = p.hidden(sum(chunks) + 26 + 401)
+    g, o = p.run_both(hidden, chunks)
+    p.check(g, o, "chunk by chunk")
+    row = 0
+    for n in chunks:
+        p.check(g[row:row + n], o[row:row + n], f"chunk of {n} at {row}")
+        row += n
+    parents = si.make_token_tree(26, 70)
+    h = hidden[row:row + 26]
+    p.check(p.gpu_tree(h, row, parents), p.oracle.prefill_tree(h, parents, row), "tree")
+    row += 26
+    kv = p.kv_gpu()[:, :, :, :row]
+    for l in range(n_layers):
+        assert rel_l2(kv[l], p.oracle.kv[l, :, :, :row]) <= BF16_REL_L2, l
+    # the same prompt prefix again plus more, in one overlapped call behind the tree
+    more = [100, 200, 37, 64]
+    p.stage.enable_overlap(4)
+    x = torch.from_numpy(hidden[row:row + sum(more)]).to(device="cuda:0", dtype=p.td)
+    y = to_numpy(p.stage.prefill_chunks(x, more, row, p.kv))
+    want, pos = [], row
+    for n in more:
+        want.append(p.oracle.prefill_chunk(hidden[pos:pos + n], pos))
+        pos += n
+    p.check(y, np.concatenate(want), "overlapped call")
+    assert len(p.kv) == pos
+
+
 def test_c2_7b_stage_512_tokens_in_8_chunks_of_64():
     """Config 2: 8 layers of Llama-2-7B shape, bf16, 512-token prompt as 8 chunks of 64."""
     p = Pair(si.LLAMA7B_STAGE, "bf16", seed=20, max_positions=512, max_chunk_tokens=64)
