@@ -741,6 +741,25 @@ def test_bf16_long_prefix_8192_cached_positions():
 
 
 @pytest.mark.slow
+def test_bf16_widest_stage_d_model_8192():
+    """The widest model the bf16 path accepts (d_model 8192, 64 heads; FFN 28672 as in a 70B-class layer), one
+    layer: a 512-token chunk, a 64-token chunk and a 5-token chunk."""
+    cfg = dict(si.LLAMA7B_STAGE, d_model=8192, n_heads=64, d_ffn=28672, n_layers=1)
+    p = Pair(cfg, "bf16", seed=80, max_positions=640, max_chunk_tokens=512)
+    print("weights ready", flush=True)
+    chunks = [512, 64, 5]
+    hidden = p.hidden(sum(chunks))
+    g, o = p.run_both(hidden, chunks)
+    row = 0
+    for n in chunks:
+        p.check(g[row:row + n], o[row:row + n], f"chunk of {n} at {row}")
+        row += n
+    kv = p.kv_gpu()[0][:, :, :row]
+    for which in range(2):
+        assert rel_l2(kv[which], p.oracle.kv[0, which, :, :row]) <= BF16_REL_L2, which
+
+
+@pytest.mark.slow
 def test_c4_13b_stage_1024_tokens_in_8_chunks_of_128():
     """Config 4: 10 layers of Llama-2-13B shape, bf16, 1024 tokens as 8x128."""
     p = Pair(si.LLAMA13B_STAGE, "bf16", seed=40, max_positions=1024, max_chunk_tokens=128)
