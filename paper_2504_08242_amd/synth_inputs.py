@@ -32,6 +32,7 @@ import numpy as np
 WEIGHT_NAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_mlp")
 HIDDEN_STREAM = 1_000_000
 TREE_STREAM = 2_000_000
+W4_STREAM = 3_000_000
 
 # Architectures of the five benchmark configurations.
 TINY = dict(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ffn=688, rms_eps=1e-5, rope_theta=1e4)
@@ -104,3 +105,42 @@ def make_token_tree(n_tokens, seed, max_depth=4):
         parents[t] = ok[rng.choice(len(ok), p=w / w.sum())]
         depth[t] = depth[parents[t]] + 1
     return parents
+
+
+def make_w4_layers(cfg, seed, weight_std=0.02, n_threads=8):
+    """Seeded 4-bit projection matrices: per layer a dict with, for each of the seven matrices, ``name`` = uint8
+    [out, in/2] (two 4-bit codes per byte) and ``name + '_scale'`` = fp32 [out, in/128], plus the two gains
+    (fp32, bf16-representable).  Codes are round(2.3 z) + 8 clipped to 0..15 with z ~ N(0,1) and scales are
+    weight_std / 2.3 times (0.75 + U(0, 0.5)) rounded to bf16, so that the expanded matrices look like N(0,
+    weight_std^2) weights after round-to-nearest 4-bit quantisation.  Bytes and scales come straight from the
+    generator: there is no quantiser, hence none to share between the two sides."""
+    matrices = [n for n in WEIGHT_NAMES if not n.startswith("g_")]
+
+    def one(job):
+        l, name = job
+        idx = WEIGHT_NAMES.index(name)
+        if name.startswith("g_"):
+            return make_weight(cfg, seed, l, name, bf16=True)
+        n_out, n_in = weight_shape(cfg, name)
+        rng = np.random.default_rng([seed, W4_STREAM, l, idx])
+        z = rng.standard_normal((n_out, n_in), dtype=np.float32)
+        z *= np.float32(2.3)
+        np.rint(z, out=z)
+        z += np.float32(8.0)
+        np.clip(z, 0.0, 15.0, out=z)
+        codes = z.astype(np.uint8)
+        packed = codes[:, 0::2] | (codes[:, 1::2] << np.uint8(4))
+        u = rng.random((n_out, n_in // 128), dtype=np.float32)
+        scale = round_to_bf16(np.float32(weight_std / 2.3) * (np.float32(0.75) + np.float32(0.5) * u))
+        return np.ascontiguousarray(packed), scale
+
+    jobs = [(l, n) for l in range(cfg["n_layers"]) for n in WEIGHT_NAMES]
+    with ThreadPoolExecutor(max_workers=n_threads) as ex:
+        res = list(ex.map(one, jobs))
+    layers = [dict() for _ in range(cfg["n_layers"])]
+    for (l, n), r in zip(jobs, res):
+        if n.startswith("g_"):
+            layers[l][n] = r
+        else:
+            layers[l][n], layers[l][n + "_scale"] = r
+    return layers
