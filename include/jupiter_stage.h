@@ -39,6 +39,13 @@
  *     stream is kept in fp32 inside a call.  dtype JUP_F32 ("check mode"): the
  *     same mathematics with fp32 storage and fp32 arithmetic throughout, on
  *     plain (non matrix-core) kernels; it exists to pin indexing and semantics.
+ *   - dtype JUP_BF16_W4: as JUP_BF16, except that the seven projection matrices of a layer are given as
+ *     4-bit codes with group-wise fp32 scales (the paper evaluates INT4 models, Sec. VI-A; it names no
+ *     scheme, this is the library's): W[n][k] = scale[n][k / 128] * (code[n][k] - 8), codes 0..15 stored two
+ *     per byte, row-major [out_features, in_features / 2], the low four bits of a byte holding the even k.
+ *     Hidden states, gains and the KV cache stay bfloat16.  The kernels behind it are built for decode-sized
+ *     chunks (Sec. V), which are bound by streaming the weights: up to 16 tokens stream every matrix once;
+ *     longer chunks are accepted and computed 16 rows at a time, re-reading the codes for every 16 rows.
  *   - Calls validate their arguments on the host before anything is enqueued;
  *     on error nothing is enqueued, no state changes, and jup_last_error()
  *     holds a message.  Kernel work is asynchronous on the given HIP stream.
@@ -62,7 +69,7 @@ extern "C" {
 typedef struct jup_stage jup_stage_t; /* opaque, host object */
 typedef struct jup_kv jup_kv_t;       /* opaque, host object */
 
-typedef enum { JUP_F32 = 0, JUP_BF16 = 1 } jup_dtype_t;
+typedef enum { JUP_F32 = 0, JUP_BF16 = 1, JUP_BF16_W4 = 2 } jup_dtype_t;
 
 typedef enum {
     JUP_OK = 0,
@@ -75,7 +82,7 @@ typedef enum {
 
 /*
  * Shape of a stage.  Requirements: d_model == n_heads * head_dim; head_dim even.
- * JUP_BF16 additionally requires head_dim == 128, d_model % 256 == 0 and
+ * JUP_BF16 and JUP_BF16_W4 additionally require head_dim == 128, d_model % 256 == 0, d_model <= 8192 and
  * d_ffn % 128 == 0 (the matrix-core tilings); JUP_F32 accepts any sizes.
  */
 typedef struct {
@@ -89,12 +96,17 @@ typedef struct {
     int32_t dtype;    /* jup_dtype_t */
 } jup_stage_config_t;
 
-/* One decoder layer's parameters; device pointers of the stage dtype. */
+/*
+ * One decoder layer's parameters; device pointers of the stage dtype (JUP_BF16_W4: the seven matrices are
+ * uint8 [out_features, in_features / 2] code pairs, the gains bfloat16).
+ */
 typedef struct {
     const void *wq, *wk, *wv, *wo; /* [d_model, d_model] */
     const void *w_gate, *w_up;     /* [d_ffn, d_model]   */
     const void *w_down;            /* [d_model, d_ffn]   */
     const void *g_attn, *g_mlp;    /* [d_model] RMSNorm gains before attention / before the FFN */
+    /* JUP_BF16_W4 only (ignored otherwise): fp32 scales [out_features, in_features / 128] of the matrices above */
+    const float *sq, *sk, *sv, *so, *s_gate, *s_up, *s_down;
 } jup_layer_weights_t;
 
 /* ---- stage ---------------------------------------------------------------------------------- */

@@ -10,7 +10,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libjupiter_stage.so")
 
-JUP_F32, JUP_BF16 = 0, 1
+JUP_F32, JUP_BF16, JUP_BF16_W4 = 0, 1, 2
 JUP_OK, JUP_EINVAL, JUP_EPOS, JUP_ECAP, JUP_EDEVICE, JUP_ENOMEM = 0, -1, -2, -3, -4, -5
 STATUS_NAMES = {0: "JUP_OK", -1: "JUP_EINVAL", -2: "JUP_EPOS", -3: "JUP_ECAP", -4: "JUP_EDEVICE", -5: "JUP_ENOMEM"}
 KERNEL_IDS = {"rmsnorm": 0, "gemm_qkv": 1, "attention": 2, "gemm_o": 3, "gemm_gate_up": 4, "gemm_down": 5}
@@ -23,8 +23,12 @@ class StageConfig(ctypes.Structure):
                 ("rope_theta", ctypes.c_float), ("dtype", ctypes.c_int32)]
 
 
+MATRIX_NAMES = WEIGHT_NAMES[:7]
+SCALE_FIELDS = ("sq", "sk", "sv", "so", "s_gate", "s_up", "s_down")  # jup_layer_weights_t, in MATRIX_NAMES order
+
+
 class LayerWeights(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_void_p) for n in WEIGHT_NAMES]
+    _fields_ = [(n, ctypes.c_void_p) for n in WEIGHT_NAMES + SCALE_FIELDS]
 
 
 class JupiterError(RuntimeError):
@@ -91,14 +95,15 @@ def _check(status):
 
 
 def make_config(cfg, dtype):
-    """cfg: dict with n_layers, d_model, n_heads, head_dim, d_ffn, rms_eps, rope_theta; dtype: 'f32' | 'bf16'."""
+    """cfg: dict with n_layers, d_model, n_heads, head_dim, d_ffn, rms_eps, rope_theta; dtype: 'f32' | 'bf16' |
+    'w4' (bf16 activations and cache, 4-bit projection matrices)."""
     return StageConfig(cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ffn"],
-                       cfg["rms_eps"], cfg["rope_theta"], {"f32": JUP_F32, "bf16": JUP_BF16}[dtype])
+                       cfg["rms_eps"], cfg["rope_theta"], {"f32": JUP_F32, "bf16": JUP_BF16, "w4": JUP_BF16_W4}[dtype])
 
 
 def _torch_dtype(dtype):
     import torch
-    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "w4": torch.bfloat16}[dtype]
 
 
 def _stream_handle(stream):
@@ -179,7 +184,9 @@ class Stage:
     """jup_stage_t plus the torch tensors that back its packed weights and workspace."""
 
     def __init__(self, cfg, dtype, layers, max_chunk_tokens, device="cuda:0", stream=None):
-        """layers: list of dicts keyed by WEIGHT_NAMES holding torch tensors of the stage dtype on `device`."""
+        """layers: list of dicts keyed by WEIGHT_NAMES holding torch tensors of the stage dtype on `device`; for
+        dtype 'w4' the seven matrices are uint8 code pairs and every matrix ``name`` comes with an fp32
+        ``name + '_scale'`` (see upload_w4_layers)."""
         import torch
         self.cfg, self.dtype, self.max_chunk_tokens = dict(cfg), dtype, int(max_chunk_tokens)
         L = lib()
@@ -197,8 +204,14 @@ class Stage:
         for i, w in enumerate(layers):
             for n in WEIGHT_NAMES:
                 t = w[n]
-                assert t.dtype == td and t.is_contiguous() and t.device.type == "cuda", n
+                want = torch.uint8 if dtype == "w4" and n in MATRIX_NAMES else td
+                assert t.dtype == want and t.is_contiguous() and t.device.type == "cuda", n
                 setattr(arr[i], n, t.data_ptr())
+            if dtype == "w4":
+                for n, field in zip(MATRIX_NAMES, SCALE_FIELDS):
+                    t = w[n + "_scale"]
+                    assert t.dtype == torch.float32 and t.is_contiguous() and t.device.type == "cuda", n
+                    setattr(arr[i], field, t.data_ptr())
         self.handle = ctypes.c_void_p()
         _check(L.jup_stage_create(ctypes.byref(ccfg), arr,
                                   ctypes.c_void_p(self.packed.data_ptr() if self.packed is not None else 0), pb,
@@ -296,3 +309,19 @@ def upload_layers(layers_np, dtype, device="cuda:0"):
     td = _torch_dtype(dtype)
     return [{n: torch.from_numpy(w[n]).to(device=device, dtype=td).contiguous() for n in WEIGHT_NAMES}
             for w in layers_np]
+
+
+def upload_w4_layers(layers_np, device="cuda:0"):
+    """Layer dicts of a 4-bit stage (uint8 code pairs, fp32 ``*_scale`` arrays, fp32 bf16-representable gains)
+    -> torch tensors on the GPU."""
+    import torch
+    out = []
+    for w in layers_np:
+        d = {}
+        for n in MATRIX_NAMES:
+            d[n] = torch.from_numpy(w[n]).to(device=device).contiguous()
+            d[n + "_scale"] = torch.from_numpy(w[n + "_scale"]).to(device=device, dtype=torch.float32).contiguous()
+        for n in ("g_attn", "g_mlp"):
+            d[n] = torch.from_numpy(w[n]).to(device=device, dtype=torch.bfloat16).contiguous()
+        out.append(d)
+    return out

@@ -82,7 +82,9 @@ enum { EPI_QKV = 0, EPI_PARTIAL = 1, EPI_SWIGLU = 2 };
 
 struct GemmArgs {
     const u16* A;  // [M, K] activations in the tiled layout (rows padded to a multiple of 32)
-    const u16* W;  // [N, K] weights in the tiled layout written by the pack kernels ([N/32][K/32][2 KB])
+    const u16* W;  // [N, K] weights in the tiled layout written by the pack kernels ([N/32][K/32][2 KB]);
+                   // 4-bit stages: the packed codes (w4_gemm.hip)
+    const float* w_scale;  // 4-bit stages only: packed scales
     int M, N, K;
     int m_tiles, n_tiles, splits;  // grid = m_tiles * n_tiles * splits workgroups
     int n_stride;                  // columns between consecutive N tiles (tile width actually owned)
@@ -110,6 +112,19 @@ hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s);
 hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s);
 hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s);
 hipError_t gemm_configure();  // raises the dynamic-LDS limit of every instantiation (once per process)
+
+// ---- projections of a 4-bit stage (w4_gemm.hip) ----------------------------------------------------
+// epi: EPI_QKV, EPI_SWIGLU or EPI_PARTIAL; the tiling fields of `a` are filled here.  EPI_PARTIAL writes
+// w4_plan_splits(N, K) partial buffers.
+int w4_plan_splits(int N, int K);
+hipError_t launch_gemm_w4(int epi, GemmArgs a, hipStream_t s);
+// dst / dst_scale: packed codes (N * K / 2 bytes) and packed scales (N * K / 128 floats) of one matrix
+void launch_pack_w4_qkv(unsigned char* dst, float* dst_scale, const void* cq, const void* ck, const void* cv,
+                        const float* sq, const float* sk, const float* sv, int d, hipStream_t s);
+void launch_pack_w4_gate_up(unsigned char* dst, float* dst_scale, const void* cg, const void* cu, const float* sg,
+                            const float* su, int d, int f, hipStream_t s);
+void launch_pack_w4_plain(unsigned char* dst, float* dst_scale, const void* c, const float* sc, int n_rows, int k,
+                          hipStream_t s);
 
 // ---- attention (bf16_attention.hip) ---------------------------------------------------------------
 // o is written in the tiled layout (it is the output projection's A operand)

@@ -31,6 +31,30 @@ hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* lay
     return hipGetLastError();
 }
 
+// 4-bit stage: codes and scales of the seven matrices go into their packed layouts (w4_gemm.hip); gains as above.
+hipError_t w4_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s) {
+    const jup_stage_config_t& c = st.cfg;
+    const size_t d = c.d_model;
+    hipError_t e = attention_configure();
+    if (e != hipSuccess) return e;
+    for (int l = 0; l < c.n_layers; ++l) {
+        char* base = (char*)st.packed + (size_t)l * st.pl.layer_bytes;
+        const jup_layer_weights_t& w = layers[l];
+        launch_pack_w4_qkv((unsigned char*)(base + st.pl.wqkv), (float*)(base + st.pl.sqkv), w.wq, w.wk, w.wv, w.sq, w.sk,
+                           w.sv, c.d_model, s);
+        launch_pack_w4_gate_up((unsigned char*)(base + st.pl.wgu), (float*)(base + st.pl.sgu), w.w_gate, w.w_up, w.s_gate,
+                               w.s_up, c.d_model, c.d_ffn, s);
+        launch_pack_w4_plain((unsigned char*)(base + st.pl.wo), (float*)(base + st.pl.so), w.wo, w.so, c.d_model,
+                             c.d_model, s);
+        launch_pack_w4_plain((unsigned char*)(base + st.pl.wdown), (float*)(base + st.pl.sdown), w.w_down, w.s_down,
+                             c.d_model, c.d_ffn, s);
+        e = hipMemcpyAsync(base + st.pl.g_attn, w.g_attn, d * 2, hipMemcpyDeviceToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(base + st.pl.g_mlp, w.g_mlp, d * 2, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipGetLastError();
+}
+
 // bt == nullptr: one chunk of n tokens at position pos of cache kv.
 // bt != nullptr: bt->n_branches chunks of bt->n_tok tokens each, n = their total number of rows; the rows of
 // branch b are appended to and attend over cache bt->kv[b] from position bt->pos0[b] (pos and kv are unused).
@@ -70,7 +94,9 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
     }
 
     const bool shared = link != nullptr;  // other chunks' kernels run beside this chunk's
-    const int splits_o = gemm_plan_splits(n, d, d, shared), splits_down = gemm_plan_splits(n, d, f, shared);
+    const bool w4 = c.dtype == JUP_BF16_W4;  // the projections read 4-bit codes; everything else is the bf16 path
+    const int splits_o = w4 ? w4_plan_splits(d, d) : gemm_plan_splits(n, d, d, shared);
+    const int splits_down = w4 ? w4_plan_splits(d, f) : gemm_plan_splits(n, d, f, shared);
     hipError_t e = hipSuccess;
     for (int l = 0; l < c.n_layers && e == hipSuccess; ++l) {
         const char* wb = (const char*)st.packed + (size_t)l * st.pl.layer_bytes;
@@ -91,7 +117,8 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
             a.q_out = q; a.rope = rope; a.kv = kv; a.layer = l; a.n_heads = H; a.d_model = d; a.pos0 = pos;
             a.branches = bt_dev;
             a.shared_gpu = shared;
-            e = launch_gemm_qkv(a, s);
+            a.w_scale = (const float*)(wb + st.pl.sqkv);
+            e = w4 ? launch_gemm_w4(EPI_QKV, a, s) : launch_gemm_qkv(a, s);
         }
         // keys and values of this layer are in the cache: the next chunk may attend to them; this chunk needs
         // those of the chunk before it
@@ -106,7 +133,8 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
             TraceScope ts(st, JUP_K_GEMM_O, s);
             GemmArgs a{};
             a.A = o; a.W = (const u16*)(wb + st.pl.wo); a.M = n; a.N = d; a.K = d; a.partial = partial; a.shared_gpu = shared;
-            if (e == hipSuccess) e = launch_gemm_partial(a, s);
+            a.w_scale = (const float*)(wb + st.pl.so);
+            if (e == hipSuccess) e = w4 ? launch_gemm_w4(EPI_PARTIAL, a, s) : launch_gemm_partial(a, s);
         }
         {
             TraceScope ts(st, JUP_K_RMSNORM, s);
@@ -116,13 +144,15 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
             TraceScope ts(st, JUP_K_GEMM_GATE_UP, s);
             GemmArgs a{};
             a.A = xn; a.W = (const u16*)(wb + st.pl.wgu); a.M = n; a.N = 2 * f; a.K = d; a.act = act; a.shared_gpu = shared;
-            if (e == hipSuccess) e = launch_gemm_swiglu(a, s);
+            a.w_scale = (const float*)(wb + st.pl.sgu);
+            if (e == hipSuccess) e = w4 ? launch_gemm_w4(EPI_SWIGLU, a, s) : launch_gemm_swiglu(a, s);
         }
         {
             TraceScope ts(st, JUP_K_GEMM_DOWN, s);
             GemmArgs a{};
             a.A = act; a.W = (const u16*)(wb + st.pl.wdown); a.M = n; a.N = d; a.K = f; a.partial = partial; a.shared_gpu = shared;
-            if (e == hipSuccess) e = launch_gemm_partial(a, s);
+            a.w_scale = (const float*)(wb + st.pl.sdown);
+            if (e == hipSuccess) e = w4 ? launch_gemm_w4(EPI_PARTIAL, a, s) : launch_gemm_partial(a, s);
         }
     }
     if (e != hipSuccess) return e;

@@ -20,7 +20,8 @@ jup_status_t fail(jup_status_t code, const char* fmt, ...) {
     return code;
 }
 
-size_t elem_size(const jup_stage_config_t& c) { return c.dtype == JUP_BF16 ? 2 : 4; }
+// bytes of an activation, gain or cache element (a 4-bit stage keeps all of those in bf16)
+size_t elem_size(const jup_stage_config_t& c) { return c.dtype == JUP_F32 ? 4 : 2; }
 
 }  // namespace
 
@@ -40,7 +41,8 @@ namespace {
 // Empty string when the configuration is usable, otherwise the reason.
 const char* check_cfg(const jup_stage_config_t* c) {
     if (!c) return "cfg is NULL";
-    if (c->dtype != JUP_F32 && c->dtype != JUP_BF16) return "dtype must be JUP_F32 or JUP_BF16";
+    if (c->dtype != JUP_F32 && c->dtype != JUP_BF16 && c->dtype != JUP_BF16_W4)
+        return "dtype must be JUP_F32, JUP_BF16 or JUP_BF16_W4";
     if (c->n_layers < 0 || c->n_layers > 4096) return "n_layers out of range";
     if (c->d_model <= 0 || c->n_heads <= 0 || c->head_dim <= 0 || c->d_ffn <= 0) return "sizes must be positive";
     if ((int64_t)c->n_heads * c->head_dim != c->d_model) return "d_model must equal n_heads * head_dim";
@@ -48,7 +50,7 @@ const char* check_cfg(const jup_stage_config_t* c) {
     if (c->head_dim > 256) return "head_dim above 256 is not supported";
     if (!(c->rms_eps >= 0.0f)) return "rms_eps must be >= 0";
     if (!(c->rope_theta > 0.0f)) return "rope_theta must be > 0";
-    if (c->dtype == JUP_BF16) {
+    if (c->dtype != JUP_F32) {
         if (c->head_dim != 128) return "JUP_BF16 requires head_dim == 128";
         if (c->d_model % 256 || c->d_model > 8192) return "JUP_BF16 requires d_model % 256 == 0 and d_model <= 8192";
         if (c->d_ffn % 128) return "JUP_BF16 requires d_ffn % 128 == 0";
@@ -75,12 +77,20 @@ PackedLayout packed_layout(const jup_stage_config_t& c) {
     const size_t e = elem_size(c), d = c.d_model, f = c.d_ffn;
     PackedLayout p{};
     size_t off = 0;
-    p.wqkv = off;   off += align_up(3 * d * d * e);
-    p.wo = off;     off += align_up(d * d * e);
-    p.wgu = off;    off += align_up(2 * f * d * e);
-    p.wdown = off;  off += align_up(d * f * e);
+    const bool w4 = c.dtype == JUP_BF16_W4;
+    auto matrix = [&](size_t n_weights) { return align_up(w4 ? n_weights / 2 : n_weights * e); };
+    p.wqkv = off;   off += matrix(3 * d * d);
+    p.wo = off;     off += matrix(d * d);
+    p.wgu = off;    off += matrix(2 * f * d);
+    p.wdown = off;  off += matrix(d * f);
     p.g_attn = off; off += align_up(d * e);
     p.g_mlp = off;  off += align_up(d * e);
+    if (w4) {
+        p.sqkv = off;  off += align_up(3 * d * d / 128 * 4);
+        p.so = off;    off += align_up(d * d / 128 * 4);
+        p.sgu = off;   off += align_up(2 * f * d / 128 * 4);
+        p.sdown = off; off += align_up(d * f / 128 * 4);
+    }
     p.layer_bytes = off;
     return p;
 }
@@ -144,6 +154,8 @@ jup_status_t jup_stage_create(const jup_stage_config_t* cfg, const jup_layer_wei
         const jup_layer_weights_t& w = layers[l];
         if (!w.wq || !w.wk || !w.wv || !w.wo || !w.w_gate || !w.w_up || !w.w_down || !w.g_attn || !w.g_mlp)
             return fail(JUP_EINVAL, "jup_stage_create: layer %d has a NULL weight pointer", l);
+        if (cfg->dtype == JUP_BF16_W4 && (!w.sq || !w.sk || !w.sv || !w.so || !w.s_gate || !w.s_up || !w.s_down))
+            return fail(JUP_EINVAL, "jup_stage_create: layer %d has a NULL scale pointer", l);
     }
 
     jup_stage* st = new (std::nothrow) jup_stage();
@@ -181,6 +193,8 @@ jup_status_t jup_stage_create(const jup_stage_config_t* cfg, const jup_layer_wei
                 if (e != hipSuccess) break;
             }
         }
+    } else if (cfg->dtype == JUP_BF16_W4) {
+        e = jup::w4_pack_weights(*st, layers, s);
     } else {
         e = jup::bf16_pack_weights(*st, layers, s);
     }

@@ -22,6 +22,9 @@ struct PackedLayout {
     size_t wdown;  // [d, f]
     size_t g_attn; // [d]
     size_t g_mlp;  // [d]
+    // 4-bit stages: the four sections above hold packed codes (half a byte per weight) and these the packed fp32
+    // scales, one per 128 input features of an output row
+    size_t sqkv, so, sgu, sdown;
     size_t layer_bytes;
 };
 PackedLayout packed_layout(const jup_stage_config_t& c);
@@ -153,6 +156,7 @@ hipError_t f32_forward(const jup_stage& st, const float* hidden_in, int n, int p
 
 // ---- matrix-core (bf16) path: bf16_forward.hip (and bf16_gemm / bf16_attention / bf16_misc) ----------------------------------------------------
 hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s);
+hipError_t w4_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s);  // 4-bit stage
 // How one forward is tied to the forwards of the neighbouring chunks (jup_stage_prefill_chunks): which scratch
 // buffer it uses, the events it records after the cache append of every layer, and the events (of the chunk
 // before it, running on the other stream) it waits for before the attention of every layer.
