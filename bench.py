@@ -50,10 +50,13 @@ def flops_per_call(cfg, n, p):
     return L * (gemm + attn)
 
 
-def bytes_per_call(cfg, n, p):
+W4_BYTES_PER_WEIGHT = 0.5 + 4.0 / 128  # a 4-bit code plus one fp32 scale per 128 weights
+
+
+def bytes_per_call(cfg, n, p, bytes_per_weight=2.0):
     """Algorithmic HBM bytes of one chunk call: weights once, cached prefix read, new K/V written, hidden in/out."""
     d, f, L = cfg["d_model"], cfg["d_ffn"], cfg["n_layers"]
-    weights = 2.0 * L * (4 * d * d + 3 * d * f)
+    weights = bytes_per_weight * L * (4 * d * d + 3 * d * f)
     kv_read = L * 2.0 * (p + n) * d * 2
     kv_write = L * 2.0 * n * d * 2
     return weights + kv_read + kv_write + 2.0 * n * d * 2
@@ -68,6 +71,9 @@ def main():
     ap.add_argument("--chunk", type=int, default=512, help="chunk size of workload c3 (128, 256, 512 or 2048)")
     ap.add_argument("--batched", action="store_true",
                     help="workload c5: all 8 branches in one jup_stage_prefill_branches call per step")
+    ap.add_argument("--w4", action="store_true",
+                    help="workloads c5 and tree: the stage holds its projection matrices as 4-bit codes with "
+                         "group-wise scales (dtype JUP_BF16_W4), the precision the paper runs its models in")
     ap.add_argument("--no-overlap", action="store_true",
                     help="feed the chunks of a prompt one call after the other instead of one jup_stage_prefill_chunks "
                          "call whose consecutive chunks overlap on several streams (profiling runs use this, so that "
@@ -115,12 +121,20 @@ def main():
         what = ("configs[4]: 8-layer stage of Llama-2-7B shape, 8 branches sharing a 512-token prefix with 64 "
                 "private tokens each; a step = one 5-token chunk at position 576 on every branch")
     n_chunks = prompt // chunk
+    if args.w4 and wl not in ("c5", "tree"):
+        sys.exit("bench.py: --w4 goes with the decode-sized workloads c5 and tree")
+    sdt = "w4" if args.w4 else "bf16"
+    wbytes = W4_BYTES_PER_WEIGHT if args.w4 else 2.0
 
     t0 = time.time()
-    layers_np = si.make_layers(cfg, seed, bf16=True, n_threads=16)
     hidden_np = si.make_hidden(cfg, seed, prompt, bf16=True)
-    stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers_np, "bf16"), chunk)
-    kv = jb.KvCache(cfg, "bf16", prompt + (chunk if wl == "tree" else 0))
+    if args.w4:
+        what += "; projection matrices as 4-bit codes with one fp32 scale per 128 weights"
+        stage = jb.Stage(cfg, "w4", jb.upload_w4_layers(si.make_w4_layers(cfg, seed, n_threads=16)), chunk)
+    else:
+        layers_np = si.make_layers(cfg, seed, bf16=True, n_threads=16)
+        stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers_np, "bf16"), chunk)
+    kv = jb.KvCache(cfg, sdt, prompt + (chunk if wl == "tree" else 0))
     hidden = torch.from_numpy(hidden_np).to("cuda:0", torch.bfloat16)
     out = torch.empty_like(hidden)
 
@@ -215,10 +229,10 @@ def main():
     step_flops = sum(flops_per_call(cfg, n, p) for n, p in calls)
     if wl == "tree":  # pairs a query really has: prefix, ancestors, itself (not the causal triangle)
         step_flops += cfg["n_layers"] * 4.0 * cfg["d_model"] * (tree_pairs - (chunk * prompt + chunk * (chunk + 1) / 2))
-    step_bytes = sum(bytes_per_call(cfg, n, p) for n, p in calls)
+    step_bytes = sum(bytes_per_call(cfg, n, p, wbytes) for n, p in calls)
     if wl == "c5" and args.batched:  # one pass over the weights serves every branch
         d_, f_, L_ = cfg["d_model"], cfg["d_ffn"], cfg["n_layers"]
-        step_bytes -= (len(calls) - 1) * 2.0 * L_ * (4 * d_ * d_ + 3 * d_ * f_)
+        step_bytes -= (len(calls) - 1) * wbytes * L_ * (4 * d_ * d_ + 3 * d_ * f_)
     step_tflops = step_flops / (ms_per_step * 1e-3) / 1e12
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
@@ -241,16 +255,17 @@ def main():
     n_call = calls[0][0] * (len(calls) if wl == "c5" and args.batched else 1)  # rows of one GEMM launch
     d, f = cfg["d_model"], cfg["d_ffn"]
     dom_flops = 2.0 * n_call * (2 * f) * d  # one launch: [n, d] x [2f, d]^T
-    dom_bytes = 2.0 * (2 * f * d + n_call * d + n_call * f)  # weights + activations in + activations out
+    dom_bytes = wbytes * 2 * f * d + 2.0 * (n_call * d + n_call * f)  # weights + activations in + activations out
+    dom_name = "gemm_w4<gate_up+swiglu>" if args.w4 else "gemm_bf16<gate_up+swiglu>"
     dom_s = dom["avg_us"] * 1e-6
     # which roof the dominant kernel sits under: the ridge of the chip is peak flop/s over peak byte/s
     if dom_flops / dom_bytes >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
         achieved = dom_flops / dom_s / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_bf16<gate_up+swiglu>", "achieved": round(achieved, 1),
+        roofline = {"bound": "mfma", "kernel": dom_name, "achieved": round(achieved, 1),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4)}
     else:
         achieved = dom_bytes / dom_s / 1e9
-        roofline = {"bound": "hbm", "kernel": "gemm_bf16<gate_up+swiglu>", "achieved": round(achieved, 1),
+        roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4)}
     roofline.update({"timed": "event pairs around each launch in a pass that feeds the chunks one call after the other "
                               "(in the overlapped call two chunks share the GPU and a launch waits for its share)",
@@ -287,7 +302,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "bf16 activations, 4-bit weights" if args.w4 else "bf16",
         "data": "synthetic",
         "config": {"workload": what, "tokens_per_step": tokens_per_step, "chunk_tokens": n_call},
         "tflops": round(step_tflops, 1),

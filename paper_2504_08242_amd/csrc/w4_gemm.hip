@@ -4,9 +4,10 @@
 // runs its models with INT4 weights).  The kernel streams the codes, a quarter of the bf16 bytes, straight from
 // global memory into registers and expands them there:
 //
-//   * A wave owns 16 rows x 64 columns and a range of K; the eight waves of a workgroup split the workgroup's K
-//     range, add their sums through LDS in a fixed order and run the epilogue.  No barrier inside the K loop and
-//     no LDS traffic for the operands: every wave streams on its own.
+//   * A wave owns 16 RG rows x 64 columns (RG = 1, 2 or 4 row groups: one expansion of the codes serves up to 64
+//     rows) and a range of K; the eight waves of a workgroup split the workgroup's K range, add their sums through
+//     LDS in a fixed order and run the epilogue.  No barrier inside the K loop and no LDS traffic for the operands:
+//     every wave streams on its own.
 //   * v_mfma_f32_16x16x32_bf16.  Operand layout (lane = 16 q + r): A: lane supplies A[m = r][k = 8 q + e], e < 8;
 //     B: lane supplies B[k = 8 q + e][n = r]; D: lane holds D[m = 4 q + i][n = r] in register i < 4, so a lane's
 //     four results share one column and take one scale.
@@ -88,19 +89,23 @@ __device__ inline bf16x8 w4_expand(unsigned w) {
     return __builtin_bit_cast(bf16x8, v);
 }
 
-// What a wave fetches for one K group: the codes of its four column blocks, their scales, and four A fragments.
-struct W4Group {
+// What a wave fetches for one K group: the codes of its four column blocks and their scales, and four A fragments
+// per row group.
+struct W4Codes {
     u32x4 w[4];
     float4 sc;
-    bf16x8 a[4];
+};
+template <int RG>
+struct W4Rows {
+    bf16x8 a[RG][4];
 };
 
-template <int EPI>
+template <int EPI, int RG>
 __global__ __launch_bounds__(64 * W4_WAVES) void gemm_w4(const GemmArgs a) {
     __shared__ float red[W4_WAVES][16][W4_TILE_N];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, q = lane >> 4;
-    const int tile = blockIdx.x % a.n_tiles, split = blockIdx.x / a.n_tiles, rg = blockIdx.y;
+    const int tile = blockIdx.x % a.n_tiles, split = blockIdx.x / a.n_tiles, rg0 = blockIdx.y * RG;
     const int G = a.K / W4_GROUP;
     // K groups of this workgroup, then of this wave (floor division: the shares differ by at most one group)
     const int ws0 = (int)((long)split * G / a.splits), ws1 = (int)((long)(split + 1) * G / a.splits);
@@ -108,105 +113,150 @@ __global__ __launch_bounds__(64 * W4_WAVES) void gemm_w4(const GemmArgs a) {
     const int g0 = ws0 + wave * cnt / W4_WAVES, g1 = ws0 + (wave + 1) * cnt / W4_WAVES;
 
     const int k_stages = a.K / 32;
-    const int a_row = 16 * rg + r;  // rows up to the next multiple of 32 exist in the tiled operand
+    // Row groups past the last one read the last one's rows again (memory that exists); their results are dropped.
+    const int last_rg = (a.M - 1) / 16;
+    int a_row[RG];  // rows up to the next multiple of 32 exist in the tiled operand
+#pragma unroll
+    for (int j = 0; j < RG; ++j) a_row[j] = 16 * min(rg0 + j, last_rg) + r;
     const unsigned char* wbase = (const unsigned char*)a.W + (size_t)tile * G * 4096 + lane * 16;
     const float* sbase = a.w_scale + ((size_t)tile * G * 16 + r) * 4;
-    auto fetch = [&](W4Group& d, int g) {
+    auto fetch_codes = [&](W4Codes& d, int g) {
 #pragma unroll
         for (int cg = 0; cg < 4; ++cg) d.w[cg] = *(const u32x4*)(wbase + ((size_t)g * 4 + cg) * 1024);
         d.sc = *(const float4*)(sbase + (size_t)g * 64);
+    };
+    auto fetch_rows = [&](W4Rows<RG>& d, int g) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            d.a[ks] = *(const bf16x8*)(a.A + tiled_offset(a_row, (4 * g + ks) * 4 + q, k_stages));
+        for (int j = 0; j < RG; ++j)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                d.a[j][ks] = *(const bf16x8*)(a.A + tiled_offset(a_row[j], (4 * g + ks) * 4 + q, k_stages));
     };
 
-    f32x4 acc[4];
+    f32x4 acc[RG][4];
 #pragma unroll
-    for (int cg = 0; cg < 4; ++cg) acc[cg] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < RG; ++j)
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg) acc[j][cg] = f32x4{0.f, 0.f, 0.f, 0.f};
     const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
 
-    auto compute = [&](const W4Group& d) {
-        f32x4 rs = {0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](const W4Codes& c, const W4Rows<RG>& d) {
+        f32x4 rs[RG];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) rs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d.a[ks], ones, rs, 0, 0, 0);
-        const float sc[4] = {d.sc.x, d.sc.y, d.sc.z, d.sc.w};
+        for (int j = 0; j < RG; ++j) {
+            rs[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) rs[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d.a[j][ks], ones, rs[j], 0, 0, 0);
+        }
+        const float sc[4] = {c.sc.x, c.sc.y, c.sc.z, c.sc.w};
 #pragma unroll
         for (int cg = 0; cg < 4; ++cg) {
-            f32x4 t = {0.f, 0.f, 0.f, 0.f};
+            bf16x8 b[4];  // one expansion of the codes serves every row group
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d.a[ks], w4_expand(d.w[cg][ks]), t, 0, 0, 0);
+            for (int ks = 0; ks < 4; ++ks) b[ks] = w4_expand(c.w[cg][ks]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[cg][i] += sc[cg] * (t[i] - 136.0f * rs[i]);
+            for (int j = 0; j < RG; ++j) {
+                f32x4 t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d.a[j][ks], b[ks], t, 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[j][cg][i] += sc[cg] * (t[i] - 136.0f * rs[j][i]);
+            }
         }
     };
 
-    // two groups in flight per wave: the next one is fetched before the current one is used
-    W4Group cur, nxt;
-    if (g0 < g1) fetch(cur, g0);
+    // Two groups of codes (from HBM) in flight per wave: the next one is fetched before the current one is used.  The
+    // rows of A (from L2) travel with them while the registers allow it (up to 32 rows); with 64 rows they are
+    // fetched when their group's turn comes, behind the prefetch of the next codes.
+    constexpr bool ROWS_AHEAD = RG <= 2;
+    W4Codes cur, nxt;
+    W4Rows<RG> rows, rows_nxt;
+    if (g0 < g1) {
+        fetch_codes(cur, g0);
+        if (ROWS_AHEAD) fetch_rows(rows, g0);
+    }
     for (int g = g0; g < g1; ++g) {
-        if (g + 1 < g1) fetch(nxt, g + 1);
-        compute(cur);
+        if (g + 1 < g1) {
+            fetch_codes(nxt, g + 1);
+            if (ROWS_AHEAD) fetch_rows(rows_nxt, g + 1);
+        }
+        if (!ROWS_AHEAD) fetch_rows(rows, g);
+        compute(cur, rows);
         cur = nxt;
+        if (ROWS_AHEAD) rows = rows_nxt;
     }
 
-    // ---- sum over the waves (fixed order), then the epilogue on 16 x 64 outputs, two per thread ---------------------
-#pragma unroll
-    for (int cg = 0; cg < 4; ++cg)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) red[wave][4 * q + i][16 * cg + r] = acc[cg][i];
-    __syncthreads();
-    const int n = tid & 63;
+    // ---- per row group: sum over the waves (fixed order), then the epilogue, one output row per wave and pass ----
+    static_assert(16 % W4_WAVES == 0, "the epilogue deals the 16 rows of a row group to the waves");
+    const int n = lane;                    // 64 lanes = the 64 columns of the tile
     const int col = tile * W4_TILE_N + n;  // packed column
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const int m = (tid >> 6) + 8 * half;
-        float v = 0.f;
+    for (int j = 0; j < RG; ++j) {
+        if (j > 0) __syncthreads();  // the sums of the row group before have been read
 #pragma unroll
-        for (int w = 0; w < W4_WAVES; ++w) v += red[w][m][n];
-        const int row = 16 * rg + m;
-        if (EPI == EPI_PARTIAL) {
-            if (row < a.M) a.partial[((size_t)split * a.M + row) * a.N + col] = v;
-        } else if (EPI == EPI_SWIGLU) {
-            const float up = __shfl_xor(v, 1, 64);  // the odd neighbour holds the up projection of the same output
-            if (!(n & 1) && row < a.M) {
-                const int j = col >> 1;
-                a.act[tiled_offset(row, j >> 3, (a.N >> 1) >> 5) + (j & 7)] = f2bf(v * __builtin_amdgcn_rcpf(1.0f + __expf(-v)) * up);
-            }
-        } else {  // EPI_QKV
-            const float other = __shfl_xor(v, 8, 64);  // rotary partner (lanes 0..7 <-> 8..15 of a 16-column block)
-            const int which = col / a.d_model;
-            const int in = col - which * a.d_model;
-            const int head = in >> 7, u = (in & 127) >> 4, rr = in & 15;
-            const int feature = rr < 8 ? 8 * u + rr : 64 + 8 * u + (rr - 8);
-            float out = v;
-            if (which != 2 && row < a.M) {
-                const float2 cs = a.rope[(size_t)row * 64 + (feature & 63)];
-                out = rr < 8 ? v * cs.x - other * cs.y : v * cs.x + other * cs.y;
-            }
-            if (row < a.M) {
-                u16* dst;
-                if (which == 0) {
-                    dst = a.q_out + (size_t)row * a.d_model + head * 128;
-                } else if (!a.branches) {
-                    dst = kv_slot_bf16(a.kv, a.layer, which - 1, head, a.n_heads, a.pos0 + row);
-                } else {
-                    const int b = row / a.branches->n_tok, t = row - b * a.branches->n_tok;
-                    dst = kv_slot_bf16(a.branches->kv[b], a.layer, which - 1, head, a.n_heads, a.branches->pos0[b] + t);
+        for (int cg = 0; cg < 4; ++cg)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[wave][4 * q + i][16 * cg + r] = acc[j][cg][i];
+        __syncthreads();
+#pragma unroll
+        for (int pass = 0; pass < 16 / W4_WAVES; ++pass) {
+            const int m = wave + W4_WAVES * pass;
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < W4_WAVES; ++w) v += red[w][m][n];
+            const int row = 16 * (rg0 + j) + m;
+            if (EPI == EPI_PARTIAL) {
+                if (row < a.M) a.partial[((size_t)split * a.M + row) * a.N + col] = v;
+            } else if (EPI == EPI_SWIGLU) {
+                const float up = __shfl_xor(v, 1, 64);  // the odd neighbour holds the up projection of the same output
+                if (!(n & 1) && row < a.M) {
+                    const int oc = col >> 1;  // output feature
+                    a.act[tiled_offset(row, oc >> 3, (a.N >> 1) >> 5) + (oc & 7)] =
+                        f2bf(v * __builtin_amdgcn_rcpf(1.0f + __expf(-v)) * up);
                 }
-                dst[feature] = f2bf(out);
+            } else {  // EPI_QKV
+                const float other = __shfl_xor(v, 8, 64);  // rotary partner (lanes 0..7 <-> 8..15 of a 16-column block)
+                const int which = col / a.d_model;
+                const int in = col - which * a.d_model;
+                const int head = in >> 7, u = (in & 127) >> 4, rr = in & 15;
+                const int feature = rr < 8 ? 8 * u + rr : 64 + 8 * u + (rr - 8);
+                float out = v;
+                if (which != 2 && row < a.M) {
+                    const float2 cs = a.rope[(size_t)row * 64 + (feature & 63)];
+                    out = rr < 8 ? v * cs.x - other * cs.y : v * cs.x + other * cs.y;
+                }
+                if (row < a.M) {
+                    u16* dst;
+                    if (which == 0) {
+                        dst = a.q_out + (size_t)row * a.d_model + head * 128;
+                    } else if (!a.branches) {
+                        dst = kv_slot_bf16(a.kv, a.layer, which - 1, head, a.n_heads, a.pos0 + row);
+                    } else {
+                        const int b = row / a.branches->n_tok, t = row - b * a.branches->n_tok;
+                        dst = kv_slot_bf16(a.branches->kv[b], a.layer, which - 1, head, a.n_heads,
+                                           a.branches->pos0[b] + t);
+                    }
+                    dst[feature] = f2bf(out);
+                }
             }
         }
     }
 }
 
+template <int EPI, int RG>
+hipError_t launch_rg(GemmArgs a, hipStream_t s) {
+    a.n_tiles = a.N / W4_TILE_N;
+    a.m_tiles = (a.M + 16 * RG - 1) / (16 * RG);
+    hipLaunchKernelGGL((gemm_w4<EPI, RG>), dim3(a.n_tiles * a.splits, a.m_tiles), dim3(64 * W4_WAVES), 0, s, a);
+    return hipGetLastError();
+}
+// Rows per pass over the codes: 16, 32 or 64 (a longer chunk takes several passes of 64).
 template <int EPI>
 hipError_t launch_one(GemmArgs a, hipStream_t s) {
-    a.n_tiles = a.N / W4_TILE_N;
-    a.m_tiles = (a.M + 15) / 16;
-    hipLaunchKernelGGL(gemm_w4<EPI>, dim3(a.n_tiles * a.splits, a.m_tiles), dim3(64 * W4_WAVES), 0, s, a);
-    return hipGetLastError();
+    if (a.M <= 16) return launch_rg<EPI, 1>(a, s);
+    if (a.M <= 32) return launch_rg<EPI, 2>(a, s);
+    return launch_rg<EPI, 4>(a, s);
 }
 
 }  // namespace

@@ -29,11 +29,18 @@ class Pair:
                  oracle_positions=None):
         import torch
         self.cfg, self.dtype, self.seed = dict(cfg), dtype, seed
-        bf16 = dtype == "bf16"
-        self.layers_np = layers_np if layers_np is not None else si.make_layers(cfg, seed, bf16=bf16,
-                                                                                weight_std=weight_std)
-        self.oracle = oracle.OracleStage(cfg, self.layers_np, oracle_positions or max_positions)
-        dev_layers = jb.upload_layers(self.layers_np, dtype)
+        bf16 = dtype != "f32"
+        if dtype == "w4":
+            # 4-bit stage: the GPU gets codes and scales, the oracle the matrices they expand to
+            from oracle import w4
+            self.layers_np = layers_np if layers_np is not None else si.make_w4_layers(cfg, seed, weight_std=weight_std)
+            self.oracle = oracle.OracleStage(cfg, w4.dequantize_layers(self.layers_np), oracle_positions or max_positions)
+            dev_layers = jb.upload_w4_layers(self.layers_np)
+        else:
+            self.layers_np = layers_np if layers_np is not None else si.make_layers(cfg, seed, bf16=bf16,
+                                                                                    weight_std=weight_std)
+            self.oracle = oracle.OracleStage(cfg, self.layers_np, oracle_positions or max_positions)
+            dev_layers = jb.upload_layers(self.layers_np, dtype)
         self.stage = jb.Stage(cfg, dtype, dev_layers, max_chunk_tokens)
         torch.cuda.synchronize()
         del dev_layers  # the stage keeps its own packed copy
@@ -41,7 +48,7 @@ class Pair:
         self.td = torch.float32 if dtype == "f32" else torch.bfloat16
 
     def hidden(self, n_tokens, tag=0):
-        return si.make_hidden(self.cfg, self.seed, n_tokens, tag=tag, bf16=self.dtype == "bf16")
+        return si.make_hidden(self.cfg, self.seed, n_tokens, tag=tag, bf16=self.dtype != "f32")
 
     def gpu_chunk(self, hidden_np, pos, kv=None):
         import torch

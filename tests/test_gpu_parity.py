@@ -791,3 +791,82 @@ def test_c5_all_eight_branches_in_one_call():
     """Config 5 with the 8 branches batched: 40 rows through the stage at once."""
     p = Pair(si.LLAMA7B_STAGE, "bf16", seed=50, max_positions=512, max_chunk_tokens=128, oracle_positions=581)
     run_batched_branches_case(p, n_prefix=512, n_privates=[64] * 8, n_chunk=5)
+
+
+# ------------------------------------------------------------------------------------------------
+# 4-bit stage (JUP_BF16_W4; the paper evaluates INT4 models, Sec. VI-A): the GPU reads codes and scales, the
+# oracle runs on the matrices they expand to.  Same bar as bf16: codes and scales are exact inputs on both sides.
+# ------------------------------------------------------------------------------------------------
+def test_w4_two_layer_7b_shape_decode_sized_chunks_tree_and_keep():
+    p = Pair(LLAMA7B_2L, "w4", seed=90, max_positions=300, max_chunk_tokens=128)
+    hidden = p.hidden(152)
+    # up to 16 rows: one row group; 32: two; 40 and 64: four (one pass over the codes each)
+    g, o = p.run_both(hidden, [16, 5, 1, 16, 7, 32, 40, 3, 32])
+    p.check(g, o, "chunk by chunk")
+    row = 0
+    for n in [16, 5, 1, 16, 7, 32, 40, 3, 32]:
+        p.check(g[row:row + n], o[row:row + n], f"chunk of {n} at {row}")
+        row += n
+    kv = p.kv_gpu()[:, :, :, :row]
+    for l in range(2):
+        assert rel_l2(kv[l], p.oracle.kv[l, :, :, :row]) <= BF16_REL_L2, l
+    run_tree_case(p, n_prefix=100, n_tree=64, seed=31)
+    run_tree_case(p, n_prefix=37, n_tree=12, seed=32)
+
+
+def test_w4_smallest_and_odd_widths():
+    for d_model, n_heads, d_ffn in ((256, 2, 128), (768, 6, 896)):
+        cfg = dict(si.LLAMA7B_STAGE, n_layers=2, d_model=d_model, n_heads=n_heads, d_ffn=d_ffn)
+        p = Pair(cfg, "w4", seed=91 + n_heads, max_positions=128, max_chunk_tokens=32)
+        hidden = p.hidden(62)
+        g, o = p.run_both(hidden, [16, 5, 32, 9])
+        p.check(g, o, f"d_model {d_model}")
+        run_tree_case(p, n_prefix=20, n_tree=26, seed=33)
+
+
+def test_w4_batched_branches_equal_one_call_per_branch_bitwise():
+    p = Pair(LLAMA7B_2L, "w4", seed=92, max_positions=70, max_chunk_tokens=64, oracle_positions=96)
+    run_batched_branches_case(p, n_prefix=70, n_privates=[9, 0, 17, 4, 11, 2, 8, 13], n_chunk=5)   # 40 rows
+    run_batched_branches_case(p, n_prefix=33, n_privates=[3, 12, 6], n_chunk=7)                   # 21 rows
+
+
+def test_w4_same_call_twice_is_bitwise_identical_and_zero_codes_give_zero():
+    torch = torch_mod()
+    cfg = dict(si.LLAMA7B_STAGE, n_layers=1, d_model=512, n_heads=4, d_ffn=640)
+    layers = si.make_w4_layers(cfg, seed=95)
+    for name in ("wo", "w_down"):           # code 8 everywhere: both projections back to d_model are zero
+        layers[0][name][:] = 0x88
+    p = Pair(cfg, "w4", seed=95, max_positions=64, max_chunk_tokens=16, layers_np=layers)
+    h = p.hidden(13)
+    y1 = p.gpu_chunk(h, 0)
+    bits1 = kv_bits(p.kv)
+    # zero up to fp32 rounding: the offset of the codes leaves as 136 * rowsum(A), summed in another order
+    assert np.max(np.abs(y1 - h)) <= 1e-4, "zero output projections must pass the input through"
+    p.kv.reset()
+    assert np.array_equal(y1, p.gpu_chunk(h, 0))
+    assert np.array_equal(bits1, kv_bits(p.kv))
+
+
+def test_w4_stage_creation_rejects_missing_scales():
+    torch = torch_mod()
+    cfg = dict(si.LLAMA7B_STAGE, n_layers=1, d_model=256, n_heads=2, d_ffn=128)
+    dev = jb.upload_w4_layers(si.make_w4_layers(cfg, seed=96))
+    stage = jb.Stage(cfg, "w4", dev, 16)     # complete layers: accepted
+    del stage
+    ccfg = jb.make_config(cfg, "w4")
+    import ctypes
+    L = jb.lib()
+    arr = (jb.LayerWeights * 1)()
+    for n in jb.WEIGHT_NAMES:
+        setattr(arr[0], n, dev[0][n].data_ptr())
+    for n, field in zip(jb.MATRIX_NAMES, jb.SCALE_FIELDS):
+        if field != "s_up":
+            setattr(arr[0], field, dev[0][n + "_scale"].data_ptr())
+    pb = L.jup_stage_packed_bytes(ctypes.byref(ccfg))
+    wb = L.jup_stage_workspace_bytes(ctypes.byref(ccfg), 16)
+    packed = torch.empty(pb, dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(wb, dtype=torch.uint8, device="cuda:0")
+    handle = ctypes.c_void_p()
+    rc = L.jup_stage_create(ctypes.byref(ccfg), arr, ctypes.c_void_p(packed.data_ptr()), pb,
+                            ctypes.c_void_p(ws.data_ptr()), wb, 16, None, ctypes.byref(handle))
+    assert rc == jb.JUP_EINVAL and "scale" in jb.last_error()
