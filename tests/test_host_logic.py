@@ -49,12 +49,22 @@ def test_size_queries():
     assert L.jup_stage_workspace_bytes(ctypes.byref(t), 128) > 128 * 256 * 4
     bad = cfg_of(dict(si.TINY, n_heads=3), "f32")
     assert L.jup_stage_packed_bytes(ctypes.byref(bad)) == 0 and L.jup_kv_bytes(ctypes.byref(bad), 8) == 0
+    # 4-bit stage: half a byte per weight plus one fp32 scale per 128 weights; activations and cache stay bf16
+    w = cfg_of(si.LLAMA7B_STAGE, "w4")
+    n_weights = 4 * 4096 * 4096 + 3 * 4096 * 11008
+    per_layer_w4 = n_weights // 2 + n_weights // 128 * 4 + 2 * 4096 * 2
+    assert 8 * per_layer_w4 <= L.jup_stage_packed_bytes(ctypes.byref(w)) < 8 * per_layer_w4 + (1 << 20)
+    assert L.jup_kv_bytes(ctypes.byref(w), 2048) == L.jup_kv_bytes(ctypes.byref(c), 2048)
+    assert L.jup_stage_workspace_bytes(ctypes.byref(w), 64) == L.jup_stage_workspace_bytes(ctypes.byref(c), 64)
+    w.dtype = 3
+    assert L.jup_stage_packed_bytes(ctypes.byref(w)) == 0
 
 
 @pytest.mark.parametrize("change,dtype", [
     (dict(n_heads=3), "f32"), (dict(head_dim=63, d_model=252), "f32"), (dict(d_ffn=0), "f32"),
     (dict(rope_theta=0.0), "f32"), (dict(n_layers=-1), "f32"),
     (dict(), "bf16"),  # the tiny shape (head_dim 64) is not a matrix-core shape
+    (dict(), "w4"),
 ])
 def test_stage_create_rejects_bad_configurations_before_touching_the_device(change, dtype):
     L = jb.lib()
