@@ -100,9 +100,9 @@ struct W4Rows {
     bf16x8 a[RG][4];
 };
 
-template <int EPI, int RG>
-__global__ __launch_bounds__(64 * W4_WAVES) void gemm_w4(const GemmArgs a) {
-    __shared__ float red[W4_WAVES][16][W4_TILE_N];
+template <int EPI, int RG, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void gemm_w4(const GemmArgs a) {
+    __shared__ float red[WAVES][16][W4_TILE_N];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, q = lane >> 4;
     const int tile = blockIdx.x % a.n_tiles, split = blockIdx.x / a.n_tiles, rg0 = blockIdx.y * RG;
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(64 * W4_WAVES) void gemm_w4(const GemmArgs a) {
     // K groups of this workgroup, then of this wave (floor division: the shares differ by at most one group)
     const int ws0 = (int)((long)split * G / a.splits), ws1 = (int)((long)(split + 1) * G / a.splits);
     const int cnt = ws1 - ws0;
-    const int g0 = ws0 + wave * cnt / W4_WAVES, g1 = ws0 + (wave + 1) * cnt / W4_WAVES;
+    const int g0 = ws0 + wave * cnt / WAVES, g1 = ws0 + (wave + 1) * cnt / WAVES;
 
     const int k_stages = a.K / 32;
     // Row groups past the last one read the last one's rows again (memory that exists); their results are dropped.
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(64 * W4_WAVES) void gemm_w4(const GemmArgs a) {
     }
 
     // ---- per row group: sum over the waves (fixed order), then the epilogue, one output row per wave and pass ----
-    static_assert(16 % W4_WAVES == 0, "the epilogue deals the 16 rows of a row group to the waves");
+    static_assert(16 % WAVES == 0, "the epilogue deals the 16 rows of a row group to the waves");
     const int n = lane;                    // 64 lanes = the 64 columns of the tile
     const int col = tile * W4_TILE_N + n;  // packed column
 #pragma unroll
@@ -200,11 +200,11 @@ __global__ __launch_bounds__(64 * W4_WAVES) void gemm_w4(const GemmArgs a) {
             for (int i = 0; i < 4; ++i) red[wave][4 * q + i][16 * cg + r] = acc[j][cg][i];
         __syncthreads();
 #pragma unroll
-        for (int pass = 0; pass < 16 / W4_WAVES; ++pass) {
-            const int m = wave + W4_WAVES * pass;
+        for (int pass = 0; pass < 16 / WAVES; ++pass) {
+            const int m = wave + WAVES * pass;
             float v = 0.f;
 #pragma unroll
-            for (int w = 0; w < W4_WAVES; ++w) v += red[w][m][n];
+            for (int w = 0; w < WAVES; ++w) v += red[w][m][n];
             const int row = 16 * (rg0 + j) + m;
             if (EPI == EPI_PARTIAL) {
                 if (row < a.M) a.partial[((size_t)split * a.M + row) * a.N + col] = v;
@@ -246,9 +246,13 @@ __global__ __launch_bounds__(64 * W4_WAVES) void gemm_w4(const GemmArgs a) {
 
 template <int EPI, int RG>
 hipError_t launch_rg(GemmArgs a, hipStream_t s) {
+    // Eight waves per workgroup split its K range.  Measured on the 7B shapes at 64 rows per pass (246 registers per
+    // lane, so eight waves per CU either way): two workgroups of four waves per CU run gate/up 5 % faster and QKV
+    // 40 % slower than one of eight; at 5 rows 4, 8 and 16 waves measured within 5 % of each other.
+    constexpr int WAVES = W4_WAVES;
     a.n_tiles = a.N / W4_TILE_N;
     a.m_tiles = (a.M + 16 * RG - 1) / (16 * RG);
-    hipLaunchKernelGGL((gemm_w4<EPI, RG>), dim3(a.n_tiles * a.splits, a.m_tiles), dim3(64 * W4_WAVES), 0, s, a);
+    hipLaunchKernelGGL((gemm_w4<EPI, RG, WAVES>), dim3(a.n_tiles * a.splits, a.m_tiles), dim3(64 * WAVES), 0, s, a);
     return hipGetLastError();
 }
 // Rows per pass over the codes: 16, 32 or 64 (a longer chunk takes several passes of 64).
