@@ -830,6 +830,17 @@ def test_w4_batched_branches_equal_one_call_per_branch_bitwise():
     run_batched_branches_case(p, n_prefix=33, n_privates=[3, 12, 6], n_chunk=7)                   # 21 rows
 
 
+def test_w4_overlapped_chunks_equal_one_call_per_chunk_bitwise():
+    """The 4-bit projections take the same tiles and splits whether or not chunks overlap: bit-identical results."""
+    p = Pair(LLAMA7B_2L, "w4", seed=93, max_positions=200, max_chunk_tokens=64)
+    p.stage.enable_overlap(4)
+    run_chunks_case(p, [16, 5, 64, 0, 33, 16, 1], pos0_chunks=(16, 9), exact=True)
+    y, h = run_chunks_case(p, [16, 16, 16, 16], exact=True)
+    p.oracle.reset()
+    o = np.concatenate([p.oracle.prefill_chunk(h[i:i + 16], i) for i in range(0, 64, 16)])
+    p.check(y, o, "overlapped call")
+
+
 def test_w4_same_call_twice_is_bitwise_identical_and_zero_codes_give_zero():
     torch = torch_mod()
     cfg = dict(si.LLAMA7B_STAGE, n_layers=1, d_model=512, n_heads=4, d_ffn=640)
