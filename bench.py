@@ -72,8 +72,9 @@ def main():
     ap.add_argument("--batched", action="store_true",
                     help="workload c5: all 8 branches in one jup_stage_prefill_branches call per step")
     ap.add_argument("--w4", action="store_true",
-                    help="workloads c5 and tree: the stage holds its projection matrices as 4-bit codes with "
-                         "group-wise scales (dtype JUP_BF16_W4), the precision the paper runs its models in")
+                    help="the stage holds its projection matrices as 4-bit codes with group-wise scales (dtype "
+                         "JUP_BF16_W4), the precision the paper runs its models in; its kernels are built for the "
+                         "decode-sized workloads c5 and tree (prefill-sized chunks run, 64 rows per pass)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="feed the chunks of a prompt one call after the other instead of one jup_stage_prefill_chunks "
                          "call whose consecutive chunks overlap on several streams (profiling runs use this, so that "
@@ -121,8 +122,6 @@ def main():
         what = ("configs[4]: 8-layer stage of Llama-2-7B shape, 8 branches sharing a 512-token prefix with 64 "
                 "private tokens each; a step = one 5-token chunk at position 576 on every branch")
     n_chunks = prompt // chunk
-    if args.w4 and wl not in ("c5", "tree"):
-        sys.exit("bench.py: --w4 goes with the decode-sized workloads c5 and tree")
     sdt = "w4" if args.w4 else "bf16"
     wbytes = W4_BYTES_PER_WEIGHT if args.w4 else 2.0
 
@@ -130,7 +129,8 @@ def main():
     hidden_np = si.make_hidden(cfg, seed, prompt, bf16=True)
     if args.w4:
         what += "; projection matrices as 4-bit codes with one fp32 scale per 128 weights"
-        stage = jb.Stage(cfg, "w4", jb.upload_w4_layers(si.make_w4_layers(cfg, seed, n_threads=16)), chunk)
+        layers_w4 = si.make_w4_layers(cfg, seed, n_threads=16)
+        stage = jb.Stage(cfg, "w4", jb.upload_w4_layers(layers_w4), chunk)
     else:
         layers_np = si.make_layers(cfg, seed, bf16=True, n_threads=16)
         stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers_np, "bf16"), chunk)
@@ -270,13 +270,16 @@ def main():
     roofline.update({"timed": "event pairs around each launch in a pass that feeds the chunks one call after the other "
                               "(in the overlapped call two chunks share the GPU and a launch waits for its share)",
                      "avg_launch_us": round(dom["avg_us"], 2), "flop_per_launch": dom_flops,
-                     "algorithmic_bytes": dom_bytes, "traffic": GATE_UP_TRAFFIC_BYTES.get((wl, chunk)),
+                     "algorithmic_bytes": dom_bytes, "traffic": None if args.w4 else GATE_UP_TRAFFIC_BYTES.get((wl, chunk)),
                      "traffic_unit": "bytes per launch (offline rocprofv3 counters)"})
 
     cpu_baseline = None
     if not args.no_cpu_baseline and wl not in ("c5", "tree"):
         import oracle
         ns = min(max(args.cpu_sample_tokens, 1), prompt)
+        if args.w4:  # the oracle of a 4-bit stage runs on the matrices the codes and scales expand to
+            from oracle import w4
+            layers_np = w4.dequantize_layers(layers_w4)
         ora = oracle.OracleStage(cfg, layers_np, ns)
         ref = np.empty((ns, cfg["d_model"]), np.float32)
         t0 = time.perf_counter()
