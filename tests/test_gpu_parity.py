@@ -858,6 +858,32 @@ def test_w4_same_call_twice_is_bitwise_identical_and_zero_codes_give_zero():
     assert np.array_equal(bits1, kv_bits(p.kv))
 
 
+def test_w4_stage_equals_the_bf16_stage_on_weights_both_can_hold():
+    """Scales that are powers of two make every expanded weight a bf16 number: the bf16 stage on the expanded
+    matrices and the 4-bit stage on the codes then compute the same products and differ by fp32 summation order
+    only (two independent GPU paths, same answer; both against the oracle as well)."""
+    from oracle import w4
+    cfg = LLAMA7B_2L
+    layers = si.make_w4_layers(cfg, seed=97)
+    rng = np.random.default_rng(97)
+    for w in layers:
+        for n in w4.MATRIX_NAMES:
+            w[n + "_scale"] = np.exp2(rng.integers(-9, -6, size=w[n + "_scale"].shape)).astype(np.float32)
+    full = w4.dequantize_layers(layers)
+    for w in full:
+        for n in w4.MATRIX_NAMES:
+            assert np.array_equal(si.round_to_bf16(w[n]), w[n]), n   # exactly representable
+    pq = Pair(cfg, "w4", seed=97, max_positions=80, max_chunk_tokens=16, layers_np=layers)
+    pb = Pair(cfg, "bf16", seed=97, max_positions=80, max_chunk_tokens=16, layers_np=full)
+    h = pq.hidden(53)
+    chunks = [16, 16, 5, 16]
+    gq, o = pq.run_both(h, chunks)
+    gb, _ = pb.run_both(h, chunks)
+    pq.check(gq, o, "4-bit stage")
+    assert rel_l2(gq, gb) <= 3e-3, rel_l2(gq, gb)
+    assert rel_l2(pq.kv_gpu()[:, :, :, :53], pb.kv_gpu()[:, :, :, :53]) <= 3e-3
+
+
 def test_w4_stage_creation_rejects_missing_scales():
     torch = torch_mod()
     cfg = dict(si.LLAMA7B_STAGE, n_layers=1, d_model=256, n_heads=2, d_ffn=128)
