@@ -59,8 +59,9 @@ const char* check_cfg(const jup_stage_config_t* c) {
 }
 
 bool same_shape(const jup_stage_config_t& a, const jup_stage_config_t& b) {
+    // a cache holds bf16 entries for JUP_BF16 and JUP_BF16_W4 stages alike: either kind of stage may use it
     return a.n_layers == b.n_layers && a.d_model == b.d_model && a.n_heads == b.n_heads &&
-           a.head_dim == b.head_dim && a.dtype == b.dtype;
+           a.head_dim == b.head_dim && elem_size(a) == elem_size(b);
 }
 
 size_t kv_bytes_for(const jup_stage_config_t& c, int64_t slots) {

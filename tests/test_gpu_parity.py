@@ -856,6 +856,10 @@ def test_w4_same_call_twice_is_bitwise_identical_and_zero_codes_give_zero():
     p.kv.reset()
     assert np.array_equal(y1, p.gpu_chunk(h, 0))
     assert np.array_equal(bits1, kv_bits(p.kv))
+    # the cache of a 4-bit stage holds bf16 entries: one made for the bf16 dtype serves as well
+    kvb = jb.KvCache(cfg, "bf16", 64)
+    assert np.array_equal(y1, p.gpu_chunk(h, 0, kv=kvb))
+    assert np.array_equal(bits1, kv_bits(kvb))
 
 
 def test_w4_stage_equals_the_bf16_stage_on_weights_both_can_hold():
