@@ -43,7 +43,8 @@
  *     4-bit codes with group-wise fp32 scales (the paper evaluates INT4 models, Sec. VI-A; it names no
  *     scheme, this is the library's): W[n][k] = scale[n][k / 128] * (code[n][k] - 8), codes 0..15 stored two
  *     per byte, row-major [out_features, in_features / 2], the low four bits of a byte holding the even k.
- *     Hidden states, gains and the KV cache stay bfloat16.  The kernels behind it are built for decode-sized
+ *     Hidden states, gains and the KV cache stay bfloat16 (a cache made for a JUP_BF16 configuration of the
+ *     same shape serves a JUP_BF16_W4 stage and vice versa).  The kernels behind it are built for decode-sized
  *     chunks (Sec. V), which are bound by streaming the weights: up to 16 tokens stream every matrix once;
  *     longer chunks are accepted and computed 16 rows at a time, re-reading the codes for every 16 rows.
  *   - Calls validate their arguments on the host before anything is enqueued;
