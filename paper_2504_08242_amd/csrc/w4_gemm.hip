@@ -113,11 +113,15 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_w4(const GemmArgs a) {
     const int g0 = ws0 + wave * cnt / WAVES, g1 = ws0 + (wave + 1) * cnt / WAVES;
 
     const int k_stages = a.K / 32;
-    // Row groups past the last one read the last one's rows again (memory that exists); their results are dropped.
-    const int last_rg = (a.M - 1) / 16;
-    int a_row[RG];  // rows up to the next multiple of 32 exist in the tiled operand
+    // Lanes whose row lies past the chunk fetch nothing (a 5-token chunk reads 5 of the 16 rows of its fragment) and
+    // multiply zeros; their results are dropped.
+    int a_row[RG];
+    bool a_live[RG];
 #pragma unroll
-    for (int j = 0; j < RG; ++j) a_row[j] = 16 * min(rg0 + j, last_rg) + r;
+    for (int j = 0; j < RG; ++j) {
+        a_row[j] = 16 * (rg0 + j) + r;
+        a_live[j] = a_row[j] < a.M;
+    }
     const unsigned char* wbase = (const unsigned char*)a.W + (size_t)tile * G * 4096 + lane * 16;
     const float* sbase = a.w_scale + ((size_t)tile * G * 16 + r) * 4;
     auto fetch_codes = [&](W4Codes& d, int g) {
@@ -125,12 +129,16 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_w4(const GemmArgs a) {
         for (int cg = 0; cg < 4; ++cg) d.w[cg] = *(const u32x4*)(wbase + ((size_t)g * 4 + cg) * 1024);
         d.sc = *(const float4*)(sbase + (size_t)g * 64);
     };
+    const u32x4 zero_bits = {0u, 0u, 0u, 0u};
+    const bf16x8 zero_frag = __builtin_bit_cast(bf16x8, zero_bits);
     auto fetch_rows = [&](W4Rows<RG>& d, int g) {
 #pragma unroll
         for (int j = 0; j < RG; ++j)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                d.a[j][ks] = *(const bf16x8*)(a.A + tiled_offset(a_row[j], (4 * g + ks) * 4 + q, k_stages));
+            for (int ks = 0; ks < 4; ++ks) {
+                d.a[j][ks] = zero_frag;
+                if (a_live[j]) d.a[j][ks] = *(const bf16x8*)(a.A + tiled_offset(a_row[j], (4 * g + ks) * 4 + q, k_stages));
+            }
     };
 
     f32x4 acc[RG][4];
