@@ -33,7 +33,9 @@
  *     The library never allocates or frees device memory: every buffer,
  *     including its own packed weights and workspace, is provided by the caller
  *     (normally through PyTorch) and is borrowed until the handle is destroyed.
- *   - Matrices are row-major.  Weights are [out_features, in_features].
+ *   - Matrices are row-major.  Weights are [out_features, in_features].  With the bfloat16 dtypes (JUP_BF16,
+ *     JUP_BF16_W4) every weight, gain and hidden-state pointer must be 16-byte aligned (rows are read and
+ *     written 16 bytes at a time); a misaligned one is JUP_EINVAL.
  *   - dtype JUP_BF16: hidden states, weights, gains and the KV cache are
  *     bfloat16; products accumulate in fp32 on the matrix cores and the residual
  *     stream is kept in fp32 inside a call.  dtype JUP_F32 ("check mode"): the

@@ -69,6 +69,8 @@ size_t kv_bytes_for(const jup_stage_config_t& c, int64_t slots) {
 }
 
 bool misaligned(const void* p) { return ((uintptr_t)p % jup::kAlign) != 0; }
+// the matrix-core kernels read and write rows of bf16 tensors 16 bytes at a time
+bool misaligned16(const void* p) { return ((uintptr_t)p % 16) != 0; }
 
 }  // namespace
 
@@ -157,6 +159,10 @@ jup_status_t jup_stage_create(const jup_stage_config_t* cfg, const jup_layer_wei
             return fail(JUP_EINVAL, "jup_stage_create: layer %d has a NULL weight pointer", l);
         if (cfg->dtype == JUP_BF16_W4 && (!w.sq || !w.sk || !w.sv || !w.so || !w.s_gate || !w.s_up || !w.s_down))
             return fail(JUP_EINVAL, "jup_stage_create: layer %d has a NULL scale pointer", l);
+        if (cfg->dtype != JUP_F32)
+            for (const void* ptr : {w.wq, w.wk, w.wv, w.wo, w.w_gate, w.w_up, w.w_down, w.g_attn, w.g_mlp})
+                if (misaligned16(ptr))
+                    return fail(JUP_EINVAL, "jup_stage_create: layer %d has a weight pointer that is not 16-byte aligned", l);
     }
 
     jup_stage* st = new (std::nothrow) jup_stage();
@@ -541,6 +547,8 @@ jup_status_t prefill_one(const char* me, jup_stage_t* stage, const void* hidden_
         return JUP_OK;
     }
     if (!hidden_in || !hidden_out) return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must not be NULL", me);
+    if (stage->cfg.dtype != JUP_F32 && (misaligned16(hidden_in) || misaligned16(hidden_out)))
+        return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must be 16-byte aligned", me);
 
     const jup::KvView view = view_of(kv);
     const jup::TreeTable* tt = is_tree ? &tree : nullptr;
@@ -599,6 +607,8 @@ jup_status_t jup_stage_prefill_chunks(jup_stage_t* stage, const void* hidden_in,
         return fail(JUP_EPOS, "%s: the parent cache holds %d positions, fewer than the %d shared", me, kv->parent->len,
                     kv->n_shared);
     if (total > 0 && (!hidden_in || !hidden_out)) return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must not be NULL", me);
+    if (stage->cfg.dtype != JUP_F32 && (misaligned16(hidden_in) || misaligned16(hidden_out)))
+        return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must be 16-byte aligned", me);
 
     const size_t row_bytes = (size_t)stage->cfg.d_model * elem_size(stage->cfg);
     jup_overlap* o = stage->cfg.dtype == JUP_BF16 && stage->cfg.n_layers > 0 ? stage->overlap : nullptr;
@@ -706,6 +716,8 @@ jup_status_t jup_stage_prefill_branches(jup_stage_t* stage, int32_t n_branches, 
         return JUP_OK;
     }
     if (!hidden_in || !hidden_out) return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must not be NULL", me);
+    if (stage->cfg.dtype != JUP_F32 && (misaligned16(hidden_in) || misaligned16(hidden_out)))
+        return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must be 16-byte aligned", me);
 
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;

@@ -604,6 +604,12 @@ def test_bf16_zero_output_projections_pass_input_through_bitwise():
     p = Pair(cfg, "bf16", seed=14, max_positions=70, max_chunk_tokens=70, layers_np=layers)
     hidden = p.hidden(70)
     assert np.array_equal(p.gpu_chunk(hidden, 0), hidden)
+    # rows are read 16 bytes at a time: a hidden-state pointer off by one element is refused on the host
+    torch = torch_mod()
+    flat = torch.zeros(4 * cfg["d_model"] + 1, device="cuda:0", dtype=torch.bfloat16)
+    with pytest.raises(jb.JupiterError) as e:
+        p.stage.prefill_chunk(flat[1:].view(4, cfg["d_model"]), 0, p.kv)
+    assert e.value.status == jb.JUP_EINVAL and "aligned" in str(e.value) and len(p.kv) == 70
 
 
 @pytest.mark.parametrize("d_model,n_heads,d_ffn,n_layers", [(256, 2, 128, 3), (768, 6, 896, 2), (1536, 12, 4224, 2)])

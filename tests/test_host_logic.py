@@ -96,6 +96,16 @@ def test_stage_create_rejects_null_and_small_buffers():
     assert L.jup_stage_create(ctypes.byref(c), layers, FAKE, pb, FAKE, wb, 32, None, ctypes.byref(out)) == jb.JUP_EINVAL
     assert "layer 1" in jb.last_error()
     assert L.jup_stage_create(None, layers, FAKE, pb, FAKE, wb, 32, None, ctypes.byref(out)) == jb.JUP_EINVAL
+    # bfloat16 dtypes: weight pointers must be 16-byte aligned (checked on the host, before any copy kernel)
+    b = cfg_of(dict(si.LLAMA7B_STAGE, n_layers=1), "bf16")
+    one = (jb.LayerWeights * 1)()
+    for n in jb.WEIGHT_NAMES:
+        setattr(one[0], n, FAKE.value)
+    one[0].wk = FAKE.value + 8
+    pb = L.jup_stage_packed_bytes(ctypes.byref(b))
+    wb = L.jup_stage_workspace_bytes(ctypes.byref(b), 32)
+    assert L.jup_stage_create(ctypes.byref(b), one, FAKE, pb, FAKE, wb, 32, None, ctypes.byref(out)) == jb.JUP_EINVAL
+    assert "16-byte aligned" in jb.last_error() and not out.value
 
 
 def make_kv(max_positions, dtype="f32", cfg=si.TINY):
