@@ -648,6 +648,38 @@ def test_bf16_small_and_odd_stage_shapes(d_model, n_heads, d_ffn, n_layers):
     assert len(p.kv) == pos
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "w4"])
+def test_decode_sized_call_captured_in_a_graph_replays_bit_identically(dtype):
+    """A call enqueues kernels only (its tables travel as kernel arguments), so it can be captured in a HIP graph.
+    Every replay, with eager work of the same stage between the replays, must give the eager call's bits."""
+    torch = torch_mod()
+    p = Pair(LLAMA7B_2L, dtype, seed=98, max_positions=128, max_chunk_tokens=64)
+    h = p.hidden(64 + 5 + 5)
+    p.gpu_chunk(h[:64], 0)
+    x = torch.from_numpy(h[64:69]).to(device="cuda:0", dtype=p.td)
+    other = torch.from_numpy(h[69:74]).to(device="cuda:0", dtype=p.td)
+    y = torch.empty_like(x)
+    p.stage.prefill_chunk(x, 64, p.kv, hidden_out=y)
+    torch.cuda.synchronize()
+    want, want_kv = y.clone(), kv_bits(p.kv)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        p.stage.prefill_chunk(x, 64, p.kv, hidden_out=y)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        # eager work in between: another chunk at the same position overwrites the slots and the scratch buffers
+        p.stage.prefill_chunk(other, 64, p.kv)
+        y.zero_()
+        torch.cuda.synchronize()
+        assert not np.array_equal(kv_bits(p.kv), want_kv)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want), rep
+        assert np.array_equal(kv_bits(p.kv), want_kv), rep
+
+
 def test_c2_7b_stage_512_tokens_in_8_chunks_of_64():
     """Config 2: 8 layers of Llama-2-7B shape, bf16, 512-token prompt as 8 chunks of 64."""
     p = Pair(si.LLAMA7B_STAGE, "bf16", seed=20, max_positions=512, max_chunk_tokens=64)
