@@ -20,7 +20,8 @@
 //     The row sums of a group come from one more MFMA per K step against a register of ones, and a group's
 //     result enters the fp32 accumulator as scale * (t - 136 * rowsum): 4 FMAs per lane, group and column block.
 //     Products of a bf16 value and an integer below 256 are exact in fp32, the sums round as any fp32 sum does.
-//   * A (16 rows of the tiled activation layout) is read from L2 with 16-byte loads, 1 KB per wave and K step.
+//   * A (16 rows of the tiled activation layout per row group) is read from L2 with 16-byte loads, up to 1 KB per
+//     wave and K step; lanes whose row lies past the chunk fetch nothing.
 #include "bf16_common.h"
 
 namespace jup {
