@@ -24,6 +24,8 @@ def main():
     ap.add_argument("--y", type=int, nargs="+", default=[0, 512, 1024, 2048, 4096, 8192])
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--csv", default="")
+    ap.add_argument("--w4", action="store_true",
+                    help="profile a stage that holds its projection matrices as 4-bit codes (dtype JUP_BF16_W4)")
     args = ap.parse_args()
 
     import torch
@@ -37,8 +39,11 @@ def main():
         cfg["n_layers"] = args.layers
     xs, ys = sorted(args.x), sorted(args.y)
     x_max, y_max = xs[-1], ys[-1]
-    layers_np = si.make_layers(cfg, 60, bf16=True, n_threads=16)
-    stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers_np, "bf16"), x_max)
+    if args.w4:
+        stage = jb.Stage(cfg, "w4", jb.upload_w4_layers(si.make_w4_layers(cfg, 60, n_threads=16)), x_max)
+    else:
+        layers_np = si.make_layers(cfg, 60, bf16=True, n_threads=16)
+        stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers_np, "bf16"), x_max)
     kv = jb.KvCache(cfg, "bf16", y_max + x_max)
     hidden = torch.from_numpy(si.make_hidden(cfg, 60, x_max, bf16=True)).to("cuda:0", torch.bfloat16)
     out = torch.empty_like(hidden)
@@ -68,7 +73,7 @@ def main():
             table[(x, y)] = (time.perf_counter() - t0) / args.reps * 1e3
         print(f"[qxy] x={x} done", file=sys.stderr, flush=True)
 
-    hdr = f"q(x,y) in ms: {args.model} stage of {cfg['n_layers']} layers, bf16, one MI355X; {args.reps} repetitions each"
+    hdr = f"q(x,y) in ms: {args.model} stage of {cfg['n_layers']} layers, {'bf16 activations and 4-bit weights' if args.w4 else 'bf16'}, one MI355X; {args.reps} repetitions each"
     lines = [hdr, "x \\ y   " + "".join(f"{y:>10d}" for y in ys) + "   tokens/s at y=0"]
     for x in xs:
         lines.append(f"{x:<8d}" + "".join(f"{table[(x, y)]:10.3f}" for y in ys) + f"   {x / table[(x, ys[0])] * 1e3:12.0f}")
