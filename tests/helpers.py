@@ -9,12 +9,45 @@ from paper_2504_08242_amd import synth_inputs as si
 # Tolerances of the parity bar.
 F32_MAX_ABS, F32_REL_L2 = 1e-3, 1e-4
 BF16_REL_L2 = 2e-2
+# bf16 / 4-bit stages, every row by itself (a row = the last axis: one token's hidden state, or one cached key or
+# value vector of one head): a whole-tensor norm over hundreds of rows would let a single wrong row through.
+BF16_ROW_REL_L2 = 3e-2
 
 
 def rel_l2(a, b):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def row_rel_l2(got, want):
+    """Relative L2 error of every row (last axis) by itself; shape = got.shape[:-1].  Rows of the expected tensor
+    that are (nearly) zero are measured against a hundredth of the mean row norm instead of their own."""
+    g = np.asarray(got, dtype=np.float64)
+    w = np.asarray(want, dtype=np.float64)
+    den = np.linalg.norm(w, axis=-1)
+    floor = 1e-2 * float(den.mean()) if den.size else 0.0
+    return np.linalg.norm(g - w, axis=-1) / np.maximum(den, max(floor, 1e-300))
+
+
+def assert_rows_close(got, want, bound=BF16_ROW_REL_L2, what=""):
+    """Every row within `bound`; the message names the worst row."""
+    got, want = np.asarray(got), np.asarray(want)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    if got.size == 0:
+        return 0.0
+    err = row_rel_l2(got, want)
+    worst = np.unravel_index(int(np.argmax(err)), err.shape) if err.ndim else ()
+    assert float(err.max()) <= bound, (what, "worst row", tuple(int(i) for i in worst), float(err.max()),
+                                       "rows above the bound", int((err > bound).sum()), "of", err.size)
+    LAST_WORST[0] = (float(err.max()), what, tuple(int(i) for i in worst), tuple(got.shape))
+    return float(err.max())
+
+
+# largest per-row errors seen by Pair.check in this process, per dtype: (error, what, row index, tensor shape), for
+# the summary line at the end of a test run
+WORST_ROW = {}
+LAST_WORST = [None]
 
 
 def to_numpy(t):
@@ -89,3 +122,7 @@ class Pair:
         else:
             assert np.all(np.isfinite(got)), what
             assert rel_l2(got, want) <= BF16_REL_L2, (what, rel_l2(got, want))
+            if np.ndim(got) >= 2:
+                assert_rows_close(got, want, BF16_ROW_REL_L2, what)
+                WORST_ROW.setdefault(self.dtype, []).append(LAST_WORST[0])
+                WORST_ROW[self.dtype] = sorted(WORST_ROW[self.dtype], reverse=True)[:5]

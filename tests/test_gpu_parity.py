@@ -1,7 +1,8 @@
 """GPU parity: the HIP library against the CPU oracle, through the C ABI, on the same seeded inputs.
 
-Bars: fp32 check mode max-abs <= 1e-3 and rel-L2 <= 1e-4; bf16 rel-L2 <= 2e-2 on hidden_out and on the
-cached K/V values; which cache slots are written, and nothing else, bit-exact.
+Bars: fp32 check mode max-abs <= 1e-3 and rel-L2 <= 1e-4; bf16 and 4-bit stages rel-L2 <= 2e-2 on hidden_out and on
+the cached K/V values as whole tensors AND <= 3e-2 for every row by itself (one token's hidden state, one cached key
+or value vector of one head; helpers.Pair.check does both); which cache slots are written, and nothing else, bit-exact.
 """
 import numpy as np
 import pytest
@@ -445,7 +446,7 @@ def test_bf16_two_layer_7b_shape_ragged_chunks_and_cache_slots():
     kv = p.kv_gpu()[:, :, :, :pos]
     for l in range(2):
         for which in range(2):
-            assert rel_l2(kv[l, which], p.oracle.kv[l, which, :, :pos]) <= BF16_REL_L2, (l, which)
+            p.check(kv[l, which], p.oracle.kv[l, which, :, :pos], f"cache layer {l} {'KV'[which]}")
 
 
 def test_bf16_layer0_cache_is_bit_identical_across_chunkings_and_runs():
@@ -634,7 +635,7 @@ def test_bf16_small_and_odd_stage_shapes(d_model, n_heads, d_ffn, n_layers):
     row += 26
     kv = p.kv_gpu()[:, :, :, :row]
     for l in range(n_layers):
-        assert rel_l2(kv[l], p.oracle.kv[l, :, :, :row]) <= BF16_REL_L2, l
+        p.check(kv[l], p.oracle.kv[l, :, :, :row], f"cache layer {l}")
     # the same prompt prefix again plus more, in one overlapped call behind the tree
     more = [100, 200, 37, 64]
     p.stage.enable_overlap(4)
@@ -690,7 +691,7 @@ def test_c2_7b_stage_512_tokens_in_8_chunks_of_64():
         p.check(g[c * 64:(c + 1) * 64], o[c * 64:(c + 1) * 64], f"chunk {c}")
     kv = p.kv_gpu()
     for l in range(8):
-        assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, l
+        p.check(kv[l], p.oracle.kv[l], f"cache layer {l}")
     p.check(assert_one_call_equals(p, hidden, [64] * 8, g), o, "one call, overlapped")
 
 
@@ -728,7 +729,7 @@ def test_c3_7b_stage_2048_tokens_chunk_sizes_128_to_2048():
         p.check(g[-size:], o[-size:], f"last chunk of size {size}")
         kv = p.kv_gpu()
         for l in range(8):
-            assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, (size, l)
+            p.check(kv[l], p.oracle.kv[l], f"cache layer {l}, chunk size {size}")
         if size == 512:
             g512 = g
     # the launch configuration of the benchmark: the whole prompt in one call, chunks overlapping on the GPU
@@ -743,7 +744,7 @@ def test_c3_7b_stage_2048_tokens_chunk_sizes_128_to_2048():
             assert rel_l2(y, g512) <= 1.2e-2, rel_l2(y, g512)   # fewer K splits: fp32 summation order differs
             kv1 = p.kv_gpu()
             for l in range(8):
-                assert rel_l2(kv1[l], p.oracle.kv[l]) <= BF16_REL_L2, l
+                p.check(kv1[l], p.oracle.kv[l], f"cache layer {l}, one call")
 
 
 @pytest.mark.slow
@@ -775,7 +776,7 @@ def test_bf16_long_prefix_8192_cached_positions():
     p.check(p.gpu_tree(h, pos, parents), p.oracle.prefill_tree(h, parents, pos), f"tree at {pos}")
     kv = p.kv_gpu()[0][:, :, :pos + 26]
     for which in range(2):
-        assert rel_l2(kv[which], p.oracle.kv[0, which, :, :pos + 26]) <= BF16_REL_L2, which
+        p.check(kv[which], p.oracle.kv[0, which, :, :pos + 26], f"cache {'KV'[which]}")
 
 
 @pytest.mark.slow
@@ -794,7 +795,7 @@ def test_bf16_widest_stage_d_model_8192():
         row += n
     kv = p.kv_gpu()[0][:, :, :row]
     for which in range(2):
-        assert rel_l2(kv[which], p.oracle.kv[0, which, :, :row]) <= BF16_REL_L2, which
+        p.check(kv[which], p.oracle.kv[0, which, :, :row], f"cache {'KV'[which]}")
 
 
 @pytest.mark.slow
@@ -812,7 +813,7 @@ def test_c4_13b_stage_1024_tokens_in_8_chunks_of_128():
     p.check(np.concatenate(g), np.concatenate(o), "hidden_out")
     kv = p.kv_gpu()
     for l in range(10):
-        assert rel_l2(kv[l], p.oracle.kv[l]) <= BF16_REL_L2, l
+        p.check(kv[l], p.oracle.kv[l], f"cache layer {l}")
     p.check(assert_one_call_equals(p, hidden, [128] * 8, np.concatenate(g)), np.concatenate(o), "one call, overlapped")
 
 
@@ -847,7 +848,7 @@ def test_w4_two_layer_7b_shape_decode_sized_chunks_tree_and_keep():
         row += n
     kv = p.kv_gpu()[:, :, :, :row]
     for l in range(2):
-        assert rel_l2(kv[l], p.oracle.kv[l, :, :, :row]) <= BF16_REL_L2, l
+        p.check(kv[l], p.oracle.kv[l, :, :, :row], f"cache layer {l}")
     run_tree_case(p, n_prefix=100, n_tree=64, seed=31)
     run_tree_case(p, n_prefix=37, n_tree=12, seed=32)
 
