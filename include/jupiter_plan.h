@@ -44,8 +44,10 @@ typedef struct jup_seq_plan jup_seq_plan_t; /* opaque: the solved tables for eve
  *   xs, ys   strictly increasing grids of profiled sub-sequence lengths (xs[0] >= 1) and cached lengths (ys[0] >= 0)
  *   q        [nx][ny] row-major: profiled latency at (xs[i], ys[j]), > 0
  * Between profiled points q is interpolated (the paper approximates unprofiled points by interpolation):
- * bilinear inside the grid; along y, and above xs[nx-1], the outermost segment is continued linearly; below
- * xs[0] the latency of xs[0] is used (a shorter sub-sequence is not faster once the device is under-used).
+ * bilinear inside the grid; above xs[nx-1] and above ys[ny-1] the outermost segment is continued linearly; below
+ * xs[0] the latency of xs[0] is used (a shorter sub-sequence is not faster once the device is under-used) and
+ * below ys[0] that of ys[0]; a continued value never falls below the smallest profiled latency, so q stays
+ * positive everywhere.
  * Cost: 2*n_devices*s_max^2 evaluations of q; s_max <= 16384, n_devices <= 64.
  * Errors: JUP_EINVAL, JUP_ENOMEM.
  */

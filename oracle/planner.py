@@ -13,9 +13,12 @@ with the library under test.
 * Choice of k (Eq. 4).  Latency = sum of the sub-sequences' latencies h_i = q(|s_i|, tokens before s_i)
   plus (|D| - 1) times the slowest one.
 * q(x, y) between profiled points (Sec. IV-B.2: results are approximated through interpolation):
-  bilinear on the grid; outside the grid along y, and above the largest profiled x, the outermost
+  bilinear on the grid; above the largest profiled x and above the largest profiled y the outermost
   segment is continued linearly; below the smallest profiled x the latency of that smallest x is used
-  (a shorter chunk is not faster once the accelerator is under-utilised).
+  (a shorter chunk is not faster once the accelerator is under-utilised), and below the smallest profiled
+  y that of the smallest y (the paper interpolates, it does not extrapolate: a segment continued downwards
+  can reach zero or below, and Eq. 2-4 mean nothing for a latency that is not positive).  For the same
+  reason a continued value never falls below the smallest profiled latency.
 
 Layers and tokens are numbered from 1 as in the paper; Python lists are 0-based, so layer i is t[i-1].
 """
@@ -46,12 +49,12 @@ def _segment(grid, v, clamp_low):
 def interp_q(xs, ys, table, x, y):
     """table[i][j] = profiled latency of a chunk of xs[i] tokens behind ys[j] cached ones."""
     i, wx = _segment(xs, x, clamp_low=True)
-    j, wy = _segment(ys, y, clamp_low=False)
+    j, wy = _segment(ys, y, clamp_low=True)
     i2 = min(i + 1, len(xs) - 1)
     j2 = min(j + 1, len(ys) - 1)
     lo = (1.0 - wy) * table[i][j] + wy * table[i][j2]
     hi = (1.0 - wy) * table[i2][j] + wy * table[i2][j2]
-    return (1.0 - wx) * lo + wx * hi
+    return max((1.0 - wx) * lo + wx * hi, min(min(row) for row in table))
 
 
 # ---- Eq. 1: layers onto devices ------------------------------------------------------------------------

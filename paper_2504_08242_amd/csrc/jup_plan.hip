@@ -14,15 +14,16 @@ namespace {
 constexpr double kInf = std::numeric_limits<double>::infinity();
 using jup::set_error;
 
-// Position of v on a strictly increasing grid: value(v) = (1 - w) f[i] + w f[i + 1].  Outside the grid the
-// outermost segment is continued (w < 0 or w > 1), except below the grid when hold_below is set.
+// Position of v on a strictly increasing grid: value(v) = (1 - w) f[i] + w f[i + 1].  Above the grid the
+// outermost segment is continued (w > 1); below it the first grid point's value is held (a segment continued
+// downwards can cross zero, and a latency that is not positive makes Eq. 2-4 meaningless).
 struct Seg {
     int32_t i;
     double w;
 };
-Seg locate(const std::vector<int32_t>& grid, int32_t v, bool hold_below) {
+Seg locate(const std::vector<int32_t>& grid, int32_t v) {
     const int n = (int)grid.size();
-    if (n == 1 || (hold_below && v <= grid[0])) return {0, 0.0};
+    if (n == 1 || v <= grid[0]) return {0, 0.0};
     int i = 0;
     while (i < n - 2 && grid[i + 1] <= v) ++i;
     return {i, (double)(v - grid[i]) / (double)(grid[i + 1] - grid[i])};
@@ -34,19 +35,20 @@ struct jup_seq_plan {
     int32_t b, n_devices, s_max, k_max;
     std::vector<int32_t> xs, ys;
     std::vector<double> q;      // [nx][ny]
+    double q_floor;             // smallest profiled latency: a value continued beyond the grid never falls below it
     std::vector<Seg> seg_x;     // for x = 0..s_max (entry 0 unused)
     std::vector<Seg> seg_y;     // for y = 0..s_max
     std::vector<double> W;      // [k_max + 1][s_max + 1], W[k][y]
     std::vector<int32_t> cut;   // [k_max + 1][s_max + 1]: the l of Eq. 2 that attains W[k][y] (0 for k = 1)
 
-    double q_at(int32_t x, int32_t y) const {
-        const Seg sx = seg_x[x], sy = seg_y[y];
+    double q_at(int32_t x, int32_t y) const { return q_on(seg_x[x], seg_y[y]); }
+    double q_on(const Seg sx, const Seg sy) const {
         const int ny = (int)ys.size();
         const int i2 = sx.i + 1 < (int)xs.size() ? sx.i + 1 : sx.i;
         const int j2 = sy.i + 1 < ny ? sy.i + 1 : sy.i;
         const double lo = (1.0 - sy.w) * q[(size_t)sx.i * ny + sy.i] + sy.w * q[(size_t)sx.i * ny + j2];
         const double hi = (1.0 - sy.w) * q[(size_t)i2 * ny + sy.i] + sy.w * q[(size_t)i2 * ny + j2];
-        return (1.0 - sx.w) * lo + sx.w * hi;
+        return std::fmax((1.0 - sx.w) * lo + sx.w * hi, q_floor);
     }
     double t_star(int32_t x, int32_t l) const { return x < b ? kInf : q_at(x, l); }
     size_t at(int32_t k, int32_t y) const { return (size_t)k * (s_max + 1) + y; }
@@ -136,11 +138,13 @@ jup_status_t jup_seq_plan_create(const int32_t* xs, int32_t nx, const int32_t* y
         p->xs.assign(xs, xs + nx);
         p->ys.assign(ys, ys + ny);
         p->q.assign(q, q + (size_t)nx * ny);
+        p->q_floor = q[0];
+        for (long i = 1; i < (long)nx * ny; ++i) p->q_floor = std::fmin(p->q_floor, q[i]);
         p->seg_x.resize(s_max + 1);
         p->seg_y.resize(s_max + 1);
         for (int v = 0; v <= s_max; ++v) {
-            p->seg_x[v] = locate(p->xs, v, true);
-            p->seg_y[v] = locate(p->ys, v, false);
+            p->seg_x[v] = locate(p->xs, v);
+            p->seg_y[v] = locate(p->ys, v);
         }
         const int K = p->k_max, S = s_max;
         p->W.assign((size_t)(K + 1) * (S + 1), kInf);
@@ -175,14 +179,7 @@ double jup_seq_plan_q(const jup_seq_plan_t* plan, int32_t x, int32_t y) {
     if (!plan || x < 1 || y < 0) return std::numeric_limits<double>::quiet_NaN();
     // lengths beyond s_max are located on the spot
     if (x <= plan->s_max && y <= plan->s_max) return plan->q_at(x, y);
-    const Seg sx = locate(plan->xs, x, true), sy = locate(plan->ys, y, false);
-    const int ny = (int)plan->ys.size();
-    const int i2 = sx.i + 1 < (int)plan->xs.size() ? sx.i + 1 : sx.i;
-    const int j2 = sy.i + 1 < ny ? sy.i + 1 : sy.i;
-    const std::vector<double>& q = plan->q;
-    const double lo = (1.0 - sy.w) * q[(size_t)sx.i * ny + sy.i] + sy.w * q[(size_t)sx.i * ny + j2];
-    const double hi = (1.0 - sy.w) * q[(size_t)i2 * ny + sy.i] + sy.w * q[(size_t)i2 * ny + j2];
-    return (1.0 - sx.w) * lo + sx.w * hi;
+    return plan->q_on(locate(plan->xs, x), locate(plan->ys, y));
 }
 
 jup_status_t jup_seq_plan_partition(const jup_seq_plan_t* plan, int32_t y, int32_t k, int32_t* lengths, double* slowest,

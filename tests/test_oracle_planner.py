@@ -140,7 +140,7 @@ def test_interpolation_reproduces_the_table_and_bilinear_functions():
         assert op.interp_q(xs, ys, tab, x, y) == pytest.approx(f(x, y), rel=1e-12)
     # midpoint of a cell = mean of its corners
     assert op.interp_q(xs, ys, tab, 40, 256) == pytest.approx((tab[0][0] + tab[0][1] + tab[1][0] + tab[1][1]) / 4)
-    # continued linearly above the largest x and outside the y range
+    # continued linearly above the largest x and above the largest y
     assert op.interp_q(xs, ys, tab, 768, 0) == pytest.approx(f(768, 0), rel=1e-12)
     assert op.interp_q(xs, ys, tab, 64, 4096) == pytest.approx(f(64, 4096), rel=1e-12)
     # below the smallest profiled chunk the latency stays that of the smallest
@@ -149,6 +149,14 @@ def test_interpolation_reproduces_the_table_and_bilinear_functions():
     col = [row[1] for row in tab]
     assert op.interp_q(xs, ys, tab, 200, 512) == pytest.approx(np.interp(200, xs, col), rel=1e-12)
     assert op.interp_q(xs, ys, tab, 256, 1234) == pytest.approx(np.interp(1234, ys, tab[2]), rel=1e-12)
+    # below the smallest profiled prefix the latency of that prefix is held: continued downwards the segment
+    # {512: 1 ms, 1024: 3 ms} would give -1 ms at y = 0, and Eq. 2-4 mean nothing for such a latency
+    assert op.interp_q([64], [512, 1024], [[1.0, 3.0]], 64, 0) == 1.0
+    assert op.interp_q([64], [512, 1024], [[1.0, 3.0]], 64, 768) == 2.0
+    assert op.interp_q([64], [512, 1024], [[1.0, 3.0]], 64, 2048) == 7.0
+    # a falling outermost segment continued upwards stops at the smallest profiled latency instead of crossing zero
+    assert op.interp_q([64], [0, 100], [[3.0, 1.0]], 64, 150) == 1.0
+    assert op.interp_q([10, 20], [0], [[5.0], [2.0]], 40, 0) == 2.0
     # a single profiled column or row
     assert op.interp_q([64], [0, 100], [[1.0, 3.0]], 500, 50) == 2.0
     assert op.interp_q([64, 128], [0], [[1.0], [3.0]], 96, 700) == 2.0

@@ -32,6 +32,20 @@ def test_interpolated_q_equals_the_oracle_rule():
     assert math.isnan(plan.q(0, 0)) and math.isnan(plan.q(3, -1))
 
 
+def test_q_stays_positive_outside_the_profiled_grid():
+    """A y grid that does not start at 0: the first column is held below it (continued it would be -1 ms at y = 0),
+    and no continued value falls below the smallest profiled latency."""
+    plan = jp.SeqPlan([64, 128], [512, 1024], [[1.0, 3.0], [2.0, 6.0]], b=1, n_devices=2, s_max=1500)
+    assert plan.q(64, 0) == 1.0 and plan.q(128, 100) == 2.0 and plan.q(96, 512) == 1.5
+    assert plan.q(64, 768) == 2.0 and plan.q(64, 2048) == 7.0           # inside, and continued upwards
+    falling = jp.SeqPlan([10, 20], [0, 100], [[5.0, 3.0], [2.0, 1.5]], b=1, n_devices=1, s_max=64)
+    assert falling.q(40, 0) == 1.5 and falling.q(10, 1000) == 1.5        # floored at the smallest table entry
+    for y in range(1, 1500, 37):
+        for k in (1, 2, 3):
+            lens, w, total = plan.partition(y, k) if y >= k else ([], 1.0, 1.0)
+            assert w > 0 and total > 0
+
+
 @pytest.mark.parametrize("b", [1, 3, 8])
 def test_sequence_tables_equal_the_oracle_for_every_length_and_count(b):
     rng = random.Random(6 + b)
