@@ -32,31 +32,11 @@
 // (r < 4) element (i & 3) of the 8 bytes addressed by lane 4r + (i >> 2) of the group.
 #include "bf16_common.h"
 
-// 1 = timing experiments only (the output is then overwritten with cycle counters): wave 0 of every
-// workgroup accumulates the cycles it spends in the parts of the tile loop.
-#ifndef ATT_TIMELINE
-#define ATT_TIMELINE 0
-#endif
-// Timing experiments only (results are garbage): bit 1 = no MFMA.
-#ifndef ATT_EXPERIMENT
-#define ATT_EXPERIMENT 0
-#endif
-#if ATT_TIMELINE
-#define ATT_T(var) const unsigned long long var = __builtin_amdgcn_s_memtime()
-#else
-#define ATT_T(var)
-#endif
-
 namespace jup {
 namespace {
 
 __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-#if ATT_EXPERIMENT & 2
-    c[0] += (float)a[0] * (float)b[0];
-    return c;
-#else
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-#endif
 }
 // Row of D held in accumulator register i by a lane of half hh.
 __device__ inline int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i & 3); }
@@ -224,18 +204,11 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
     // token tree: bit j = the query sees token j of the chunk (its ancestors and itself)
     const unsigned long long q_sees = tree ? tree->sees[min(q0 + qb * 32 + c, n - 1)] : 0ull;
 
-#if ATT_TIMELINE
-    unsigned long long tl[6] = {0, 0, 0, 0, 0, 0};
-    const unsigned long long tl_begin = __builtin_amdgcn_s_memtime();
-#endif
     for (int it = 0; it < max_cnt; ++it) {
-        ATT_T(ta);
         // One barrier per round: the loader arrives when the tile of this round has landed, the computing waves
         // when they are done with the other slot, which the loader then refills.
         __builtin_amdgcn_s_barrier();
-        ATT_T(tb);
         if (it >= cnt) continue;
-        ATT_T(t0);
         const int tile = g + KP * it, slot = it & 1;
         const unsigned char* k_base = grp + slot * kSlotBytes;
         const unsigned v_base = grp_addr + slot * kSlotBytes + kTileBytes;
@@ -254,10 +227,6 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
         }
 
         // ---- online softmax (a lane owns one query column) -------------------------------------------------------
-#if ATT_TIMELINE
-        asm volatile("s_nop 0" : "+v"(sacc));
-#endif
-        ATT_T(t1);
         float sv[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) sv[r] = sacc[r];
@@ -303,10 +272,6 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
         }
 
         // ---- O^T += V^T P^T ----------------------------------------------------------------------------------------
-#if ATT_TIMELINE
-        asm volatile("s_nop 0" : "+v"(pf[0]), "+v"(pf[1]));
-#endif
-        ATT_T(t2);
         u32x4 vf[8];
         [&]<int... F>(std::integer_sequence<int, F...>) {
             (([&] {
@@ -324,15 +289,7 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
              }()),
              ...);
         }(std::make_integer_sequence<int, 8>{});
-#if ATT_TIMELINE
-        asm volatile("s_nop 0" : "+v"(oacc[3]));
-        ATT_T(t3);
-        tl[0] += t1 - t0; tl[1] += t2 - t1; tl[2] += t3 - t2; tl[3] += tb - ta; tl[4] += t0 - tb; tl[5] += 1;
-#endif
     }
-#if ATT_TIMELINE
-    const unsigned long long tl_loop_end = __builtin_amdgcn_s_memtime();
-#endif
 
     // ---- merge the key partitions of every query block -------------------------------------------------------------
     constexpr int kORow = 132;
@@ -388,14 +345,6 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
         out[2] = pack_bf16x2(b.x, b.y); out[3] = pack_bf16x2(b.z, b.w);
         *(u32x4*)(o + tiled_offset(row0 + qrow, head * 16 + ch, d_model >> 5)) = out;
     }
-#if ATT_TIMELINE
-    __syncthreads();
-    if (tid == 0) {
-        unsigned long long* t = (unsigned long long*)o + (size_t)blockIdx.x * 8;
-        t[0] = tl[0]; t[1] = tl[1]; t[2] = tl[2]; t[3] = tl[3]; t[4] = tl_loop_end - tl_begin; t[5] = tl[5];
-        t[6] = tl[4]; t[7] = 0x1234;
-    }
-#endif
 }
 
 }  // namespace

@@ -100,7 +100,6 @@ struct GemmArgs {
     float* partial;  // [splits][M][N] fp32
     // EPI_SWIGLU
     u16* act;  // [M, N/2] in the tiled layout (it is the down projection's A operand)
-    unsigned long long* timeline;  // timing experiments only (GEMM_TIMELINE builds): 8 counters per workgroup
 };
 
 enum GemmKind { GEMM_QKV, GEMM_O, GEMM_GATE_UP, GEMM_DOWN };
@@ -111,6 +110,8 @@ int gemm_plan_splits(int M, int N, int K, bool shared);  // shared: see GemmArgs
 hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s);
 hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s);
 hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s);
+// name of the instantiation a projection of M rows runs as (benchmarks: which tiling a counter reading belongs to)
+void gemm_kernel_name(GemmKind kind, int M, int d_model, int d_ffn, bool shared_gpu, char* buf, size_t size);
 hipError_t gemm_configure();  // raises the dynamic-LDS limit of every instantiation (once per process)
 
 // ---- projections of a 4-bit stage (w4_gemm.hip) ----------------------------------------------------

@@ -28,22 +28,11 @@
 // MFMA 32x32x16 bf16 operand layout (lane = 32*hh + c):
 //   A: lane supplies A[m = c][k = 8*hh + e], e < 8;  B: lane supplies B[k = 8*hh + e][n = c];
 //   D: lane holds D[m = 8*(i/4) + 4*hh + (i%4)][n = c] in register i < 16.
+#include <cstdio>
 #include <type_traits>
 #include <utility>
 
 #include "bf16_common.h"
-
-// 0 = product code.  Timing experiments only (results are garbage): bit 0 = no refills of the LDS ring,
-// bit 1 = no MFMA, bit 2 = no fragment reads in the loop, bit 3 = no barrier in the loop, bit 4 = no rotary
-// table loads in the QKV epilogue.
-#ifndef GEMM_EXPERIMENT
-#define GEMM_EXPERIMENT 0
-#endif
-// 1 = every workgroup's wave 0 accumulates cycle counts of its stalls into GemmArgs::partial (timing
-// experiments only: the buffer is then not a result).
-#ifndef GEMM_TIMELINE
-#define GEMM_TIMELINE 0
-#endif
 
 namespace jup {
 namespace {
@@ -52,7 +41,7 @@ constexpr int G_BK = 32;
 
 constexpr int kLdsBudget = 160 * 1024;
 
-template <int BMB, int NB, int WM, int WN, int LW = 0>
+template <int BMB, int NB, int WM, int WN>
 struct Shape {
     static constexpr int BM = 32 * BMB;             // rows of the tile: 256 for prefill-sized chunks, 128 or 64 for
                                                     // short ones (a short chunk is bound by streaming the weights:
@@ -62,10 +51,8 @@ struct Shape {
     static constexpr int WAVES = WM * WN;
     static constexpr int ROWS = BM + 32 * NB;       // LDS rows per stage: A rows then W rows
     static constexpr int STAGE_BYTES = ROWS * 64;
-    // LW = 0: every wave fetches its share of a stage between its MFMAs.  LW > 0: LW extra waves do nothing but
-    // fetch, and the WAVES computing waves issue no vector-memory instruction inside the K loop.
-    static constexpr int LOADERS = LW > 0 ? LW : WAVES;  // waves that issue the global->LDS loads
-    static constexpr int THREADS = 64 * (WAVES + LW);
+    static constexpr int LOADERS = WAVES;           // every wave fetches its share of a stage between its MFMAs
+    static constexpr int THREADS = 64 * WAVES;
     static constexpr int NL = ROWS / 16;            // 1 KB load units (16 rows) per stage, dealt round-robin to the loading waves
     static constexpr int LPW = (NL + LOADERS - 1) / LOADERS;  // load instructions per stage of the waves that have the most
     static constexpr int REM = NL % LOADERS;        // loading waves below REM issue LPW loads, the others LPW - 1 (0: all LPW)
@@ -77,12 +64,7 @@ struct Shape {
 };
 
 __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-#if GEMM_EXPERIMENT & 2
-    c[0] += (float)a[0] * (float)b[0];
-    return c;
-#else
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-#endif
 }
 
 // s_waitcnt with only the vector-memory counter constrained.
@@ -137,16 +119,16 @@ struct Frags {
     bf16x8 b[NB];
 };
 
-template <int BMB, int NB, int WM, int WN, int EPI, int LW = 0>
-__global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs a) {
-    using S = Shape<BMB, NB, WM, WN, LW>;
+template <int BMB, int NB, int WM, int WN, int EPI>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
+    using S = Shape<BMB, NB, WM, WN>;
     constexpr int G_BM = S::BM;
     constexpr int NBW = S::NBW, MBW = S::MBW;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WM, wn = wave / WM;  // wave owns row blocks [wm MBW, +MBW) x column blocks [wn NBW, +NBW)
-    const int lw = LW > 0 ? wave - S::WAVES : wave;  // index among the loading waves (negative: a computing wave)
+    const int lw = wave;
 
     // ---- which tile ---------------------------------------------------------------------------------
     // Workgroup b runs on XCD b % 8.  Tiles are numbered so that each XCD owns one contiguous range of
@@ -175,7 +157,7 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
     const unsigned lane16 = lane * 16;
 #pragma unroll
     for (int q = 0; q < S::LPW; ++q) {
-        const int j = min(q * S::LOADERS + max(lw, 0), S::NL - 1);
+        const int j = min(q * S::LOADERS + lw, S::NL - 1);
         const u16* base;
         int blk;
         if (j < G_BM / 16) {
@@ -199,42 +181,7 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
         for (int q = 0; q < CNT; ++q) issue_one(q, stage, kt);
     };
 
-    // ---- loading waves (LW > 0) ----------------------------------------------------------------------------
-    // The whole life of a loading wave: fill the ring, then per stage wait for the loads of the NEXT stage,
-    // meet the computing waves at their barrier (which also tells that they are done with the stage before),
-    // and refill the slot that this frees.  Same barriers, in the same number, as the computing waves below.
-    // A global->LDS load holds the wave that issues it for about a hundred cycles; here that wave has
-    // nothing else to do, and the computing waves issue nothing but MFMAs and LDS reads.
-    if constexpr (LW > 0) {
-        if (lw >= 0) {
-            auto run = [&](auto has_last) {
-                constexpr int CNT = S::REM == 0 || decltype(has_last)::value ? S::LPW : S::LPW - 1;
-                constexpr int ST = S::STAGES;
-#pragma unroll
-                for (int s = 0; s < ST - 1; ++s)
-                    if (s < KT) issue(has_last, s, s);
-                if (KT >= ST - 1) wait_vmcnt<(ST - 2) * CNT>();
-                else wait_vmcnt<0>();
-                __builtin_amdgcn_s_barrier();
-                int stage = 0;
-                for (int kt = 0; kt + 1 < KT; ++kt) {  // every stage but the last starts with a barrier
-                    wait_groups<ST, CNT>(KT - 1 - (kt + 1));
-                    __builtin_amdgcn_s_barrier();
-                    if (kt + ST - 1 < KT) issue(has_last, stage == 0 ? ST - 1 : stage - 1, kt + ST - 1);
-                    stage = stage + 1 == ST ? 0 : stage + 1;
-                }
-            };
-            if constexpr (S::REM == 0) {
-                run(std::true_type{});
-            } else {
-                if (lw < S::REM) run(std::true_type{});
-                else run(std::false_type{});
-            }
-            if (EPI != EPI_PARTIAL) __builtin_amdgcn_s_barrier();  // the one barrier of the epilogue
-            return;
-        }
-    }
-    constexpr bool FETCH = LW == 0;  // the computing waves fetch their share themselves
+    constexpr bool FETCH = true;
 
     // ---- LDS -> register fragment addresses -------------------------------------------------------------
     // Fragment row = 32*block + c (c = lane & 31), chunk = 2*ks + hh.  Block bases are multiples of 32,
@@ -273,11 +220,6 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
     // ---- prologue: fill all but one slot of the ring, fetch the first fragments -----------------------------
     constexpr int ST = S::STAGES;
     Frags<MBW, NBW> f0, f1;
-#if GEMM_TIMELINE
-    unsigned long long tl_vm = 0, tl_bar = 0, tl_n = 0, tl_first = 0, tl_last = 0;
-    const unsigned long long tl_start = __builtin_amdgcn_s_memtime();
-    const unsigned long long tl_rstart = __builtin_amdgcn_s_memrealtime();
-#endif
     // The whole K loop exists once per load count (waves with and without the last load unit), so that no
     // load sits under a condition: a branch inside the loop would also cut it into scheduling regions.
     auto k_loop = [&](auto has_last) {
@@ -292,7 +234,6 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
     __builtin_amdgcn_s_barrier();
     load_frags(f0, 0, 0);
     wait_lgkmcnt0();
-    if (GEMM_EXPERIMENT & 4) f1 = f0;
 
     // Stage kt.  On entry f0 holds its sub-step 0.  The barrier at the top publishes stage kt+1 (whose
     // sub-step 0 is prefetched in the second half) and retires stage kt-1, which every wave finished
@@ -308,40 +249,28 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
     auto do_stage = [&](auto refill, auto last, int kt, int stage, int pstage, int nstage) {
         constexpr bool REFILL = decltype(refill)::value, LAST = decltype(last)::value;
         if (REFILL) {
-#if GEMM_TIMELINE
-            const unsigned long long t0 = __builtin_amdgcn_s_memtime();
             if (FETCH) wait_vmcnt<(ST - 3) * CNT>();
-            const unsigned long long t1 = __builtin_amdgcn_s_memtime();
             __builtin_amdgcn_s_barrier();
-            const unsigned long long t2 = __builtin_amdgcn_s_memtime();
-            tl_vm += t1 - t0; tl_bar += t2 - t1; tl_n += 1;
-            if (tl_first == 0) tl_first = t0;
-            tl_last = t2;
-#else
-            if (FETCH) wait_vmcnt<(ST - 3) * CNT>();
-            if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
-#endif
         } else if (!LAST) {
             if (FETCH) wait_groups<ST, CNT>(KT - 1 - (kt + 1));  // stages issued after kt+1 may stay in flight
-            if (!(GEMM_EXPERIMENT & 8)) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_s_barrier();
         }
         // Memory instructions are dealt out between the MFMAs, and the compiler's scheduler is fenced at
         // every step: a burst of LDS reads or global->LDS loads would hold the wave's issue port while the
         // matrix pipe runs dry.  Fragment reads come first in a half, the global->LDS loads after them
         // (spreading the loads among the reads, or keeping the last MFMAs free of both, measured slower).
         constexpr int NM = MBW * NBW;
-        constexpr int V1 = REFILL && FETCH && !(GEMM_EXPERIMENT & 1) ? (CNT + 1) / 2 : 0;
-        constexpr int V2 = REFILL && FETCH && !(GEMM_EXPERIMENT & 1) ? CNT - V1 : 0;
+        constexpr int V1 = REFILL && FETCH ? (CNT + 1) / 2 : 0;
+        constexpr int V2 = REFILL && FETCH ? CNT - V1 : 0;
         auto half = [&]<int... M>(std::integer_sequence<int, M...>, auto second) {
             constexpr bool SECOND = decltype(second)::value;
-            constexpr int RD = (GEMM_EXPERIMENT & 4) || (SECOND && LAST) ? 0 : MBW + NBW;
+            constexpr int RD = SECOND && LAST ? 0 : MBW + NBW;
             constexpr int V = SECOND ? V2 : V1;
             constexpr int TOT = RD + V;
             auto step = [&](auto mi) {
                 constexpr int m = decltype(mi)::value;
                 const Frags<MBW, NBW>& use = SECOND ? f1 : f0;
-                if (!(GEMM_EXPERIMENT & 2))
-                    acc[m % MBW][m / MBW] = mfma32(use.a[m % MBW], use.b[m / MBW], acc[m % MBW][m / MBW]);
+                acc[m % MBW][m / MBW] = mfma32(use.a[m % MBW], use.b[m / MBW], acc[m % MBW][m / MBW]);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (TOT > 0) {
 #pragma unroll
@@ -389,9 +318,6 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
         else k_loop(std::false_type{});
     }
 
-#if GEMM_TIMELINE
-    const unsigned long long tl_loop_end = __builtin_amdgcn_s_memtime();
-#endif
     // ---- epilogues ---------------------------------------------------------------------------------------
     // Lane (c, hh) holds, for block (mb, nb), column n0 + 32 nb + c and rows row0(mb) + 8*(i/4) + 4*hh + (i%4).
     const int n_end = min(n0 + a.n_stride, a.N);  // columns [n0, n_end) belong to this tile
@@ -518,7 +444,7 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
                     const float4* rp = (const float4*)(a.rope + (size_t)m * 64 + i_lo);  // 8 (cos, sin) pairs
 #pragma unroll
                     for (int e2 = 0; e2 < 4; ++e2) {
-                        const float4 cs = (GEMM_EXPERIMENT & 16) ? make_float4(1.f, 0.f, 1.f, 0.f) : rp[e2];  // (cos, sin) of indices 2*e2, 2*e2 + 1
+                        const float4 cs = rp[e2];  // (cos, sin) of indices 2*e2, 2*e2 + 1
                         // lo' = lo cos - hi sin ; hi' = hi cos + lo sin
                         v[2 * e2] = hi ? hv[2 * e2] * cs.x + lo[2 * e2] * cs.y : lo[2 * e2] * cs.x - hv[2 * e2] * cs.y;
                         v[2 * e2 + 1] = hi ? hv[2 * e2 + 1] * cs.z + lo[2 * e2 + 1] * cs.w
@@ -534,16 +460,6 @@ __global__ __launch_bounds__(64 * (WM * WN + LW)) void gemm_bf16(const GemmArgs 
         wait_lgkmcnt0();  // this block's strip reads have returned before the next block overwrites the strip
         }
     }
-#if GEMM_TIMELINE
-    {
-        const unsigned long long tl_end = __builtin_amdgcn_s_memtime();
-        if (tid == 0 && a.timeline) {
-            unsigned long long* t = a.timeline + (size_t)blockIdx.x * 8;
-            t[0] = tl_vm; t[1] = tl_bar; t[2] = tl_n; t[3] = tl_last - tl_first; t[4] = tl_first - tl_start;
-            t[5] = tl_loop_end - tl_last; t[6] = __builtin_amdgcn_s_memrealtime() - tl_rstart; t[7] = tl_end - tl_start;
-        }
-    }
-#endif
 }
 
 // ---- host side: tiling policy and launch -----------------------------------------------------------------
@@ -555,22 +471,22 @@ int div_up(int x, int y) { return (x + y - 1) / y; }
 // Row blocks of the tile for a chunk of M tokens.
 int pick_row_blocks(int M) { return M > 128 ? 8 : M > 64 ? 4 : 2; }
 
-template <int BMB, int NB, int WM, int WN, int EPI, int LW = 0>
+template <int BMB, int NB, int WM, int WN, int EPI>
 hipError_t launch(GemmArgs a, hipStream_t s) {
     a.n_stride = 32 * NB;
     a.n_tiles = div_up(a.N, a.n_stride);
     a.m_tiles = div_up(a.M, 32 * BMB);
     a.kt_per_split = a.K / G_BK / a.splits;
     const int grid = a.m_tiles * a.n_tiles * a.splits;
-    using S = Shape<BMB, NB, WM, WN, LW>;
-    hipLaunchKernelGGL((gemm_bf16<BMB, NB, WM, WN, EPI, LW>), dim3(grid), dim3(S::THREADS), S::LDS_BYTES, s, a);
+    using S = Shape<BMB, NB, WM, WN>;
+    hipLaunchKernelGGL((gemm_bf16<BMB, NB, WM, WN, EPI>), dim3(grid), dim3(S::THREADS), S::LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
-template <int BMB, int NB, int WM, int WN, int EPI, int LW = 0>
+template <int BMB, int NB, int WM, int WN, int EPI>
 hipError_t configure_one() {
-    return hipFuncSetAttribute((const void*)gemm_bf16<BMB, NB, WM, WN, EPI, LW>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, Shape<BMB, NB, WM, WN, LW>::LDS_BYTES);
+    return hipFuncSetAttribute((const void*)gemm_bf16<BMB, NB, WM, WN, EPI>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, Shape<BMB, NB, WM, WN>::LDS_BYTES);
 }
 
 }  // namespace
@@ -578,24 +494,17 @@ hipError_t configure_one() {
 // Instantiations: (row blocks, column blocks, wave grid) per epilogue.  256-row tiles for prefill-sized
 // chunks; 128- and 64-row tiles with narrow N for short chunks, where the grid must be wide enough to keep
 // every CU streaming weights.
-// Loading waves of the three shapes that carry a prefill-sized chunk (0 = the computing waves fetch).  Measured
-// with 4 (one per SIMD) at M = 512: gate/up 89.0 -> 92.5 us, QKV 61.6 -> 65.2 us, down 51.7 -> 54.5 us.  Unlike
-// in the attention kernel, taking the loads off the computing waves does not pay here: their issue slots were
-// not what the K loop waits for, and a third wave per SIMD costs more than it hides.  Kept for experiments.
-#ifndef GEMM_LW
-#define GEMM_LW 0
-#endif
 #define JUP_GEMM_SHAPES(X)                                                          \
-    X(8, 1, 4, 1, EPI_QKV, 0) X(8, 2, 4, 1, EPI_QKV, 0) X(8, 3, 8, 1, EPI_QKV, GEMM_LW) X(8, 6, 4, 2, EPI_QKV, 0)            \
-    X(4, 2, 4, 1, EPI_QKV, 0) X(2, 2, 2, 2, EPI_QKV, 0) X(4, 3, 4, 1, EPI_QKV, 0)                                                            \
-    X(8, 2, 4, 1, EPI_SWIGLU, 0) X(8, 3, 4, 1, EPI_SWIGLU, 0) X(8, 4, 4, 2, EPI_SWIGLU, 0) X(8, 6, 4, 2, EPI_SWIGLU, GEMM_LW) X(8, 8, 4, 2, EPI_SWIGLU, 0) \
-    X(4, 4, 4, 1, EPI_SWIGLU, 0) X(2, 4, 2, 2, EPI_SWIGLU, 0) X(4, 3, 4, 1, EPI_SWIGLU, 0) X(2, 3, 2, 3, EPI_SWIGLU, 0) X(4, 6, 4, 1, EPI_SWIGLU, 0) X(2, 6, 2, 3, EPI_SWIGLU, 0) \
-    X(8, 4, 4, 2, EPI_PARTIAL, GEMM_LW) X(8, 8, 4, 2, EPI_PARTIAL, 0) X(4, 4, 4, 1, EPI_PARTIAL, 0) X(2, 4, 2, 2, EPI_PARTIAL, 0) X(2, 2, 2, 2, EPI_PARTIAL, 0) X(4, 2, 4, 1, EPI_PARTIAL, 0)
+    X(8, 1, 4, 1, EPI_QKV) X(8, 2, 4, 1, EPI_QKV) X(8, 3, 8, 1, EPI_QKV) X(8, 6, 4, 2, EPI_QKV)            \
+    X(4, 2, 4, 1, EPI_QKV) X(2, 2, 2, 2, EPI_QKV) X(4, 3, 4, 1, EPI_QKV) \
+    X(8, 2, 4, 1, EPI_SWIGLU) X(8, 3, 4, 1, EPI_SWIGLU) X(8, 4, 4, 2, EPI_SWIGLU) X(8, 6, 4, 2, EPI_SWIGLU) X(8, 8, 4, 2, EPI_SWIGLU) \
+    X(4, 4, 4, 1, EPI_SWIGLU) X(2, 4, 2, 2, EPI_SWIGLU) X(4, 3, 4, 1, EPI_SWIGLU) X(2, 3, 2, 3, EPI_SWIGLU) X(4, 6, 4, 1, EPI_SWIGLU) X(2, 6, 2, 3, EPI_SWIGLU) \
+    X(8, 4, 4, 2, EPI_PARTIAL) X(8, 8, 4, 2, EPI_PARTIAL) X(4, 4, 4, 1, EPI_PARTIAL) X(2, 4, 2, 2, EPI_PARTIAL) X(2, 2, 2, 2, EPI_PARTIAL) X(4, 2, 4, 1, EPI_PARTIAL)
 
 hipError_t gemm_configure() {
     hipError_t e = hipSuccess;
     auto acc = [&](hipError_t r) { if (e == hipSuccess) e = r; };
-#define X(BMB, NB, WM, WN, EPI, LW) acc(configure_one<BMB, NB, WM, WN, EPI, LW>());
+#define X(BMB, NB, WM, WN, EPI) acc(configure_one<BMB, NB, WM, WN, EPI>());
     JUP_GEMM_SHAPES(X)
 #undef X
     return e;
@@ -661,60 +570,104 @@ int pick_blocks(int M, int N, const int* cands, int n_cands) {
 }
 }  // namespace
 
-hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s) {
-    a.splits = 1;
-    const int bmb = pick_row_blocks(a.M);
+// ---- which instantiation serves a launch ------------------------------------------------------------------
+struct TileShape {
+    int bmb, nb, wm, wn;  // row blocks, column blocks, waves along M, waves along N
+};
+
+namespace {
+
+TileShape pick_qkv(int M, int N, bool shared_gpu) {
+    const int bmb = pick_row_blocks(M);
     // 128-token chunks beside other chunks' kernels: 96-column tiles (half again as much work per workgroup; alone on
     // the chip 64 columns win, 24.0 vs 28.8 us at 64 rows).  Measured with four lanes: 13B shapes, 8 x 128 tokens
     // +2 %; 7B shapes, 16 x 128 tokens +0-1 %; 192 columns +4 % and -1 %; 64-token chunks no difference either way.
-    if (a.shared_gpu && bmb == 4) return launch<4, 3, 4, 1, EPI_QKV>(a, s);
-    if (bmb == 2) return launch<2, 2, 2, 2, EPI_QKV>(a, s);
-    if (bmb == 4) return launch<4, 2, 4, 1, EPI_QKV>(a, s);
+    if (shared_gpu && bmb == 4) return {4, 3, 4, 1};
+    if (bmb == 2) return {2, 2, 2, 2};
+    if (bmb == 4) return {4, 2, 4, 1};
     static const int cands[] = {1, 2, 3};
-    const int nb = pick_blocks(a.M, a.N, cands, 3);
+    const int nb = pick_blocks(M, N, cands, 3);
     // Beside another chunk's kernels (overlapped multi-chunk call) half as many tiles of twice the width do the
     // same work in a quarter less CU time, and the other chunk uses the CUs they leave free: 76 us instead of 59 us
     // for this launch alone, but +1.7 % for the 4 x 512 prompt.  Alone on the chip the narrow tile wins (-6 %).
-    if (nb == 3 && a.shared_gpu && a.M > 256) return launch<8, 6, 4, 2, EPI_QKV, 0>(a, s);
-    if (nb == 3) return launch<8, 3, 8, 1, EPI_QKV, GEMM_LW>(a, s);  // 8 waves of 32 x 96: measured 1.3 % faster than 4 of 64 x 96
-    if (nb == 2) return launch<8, 2, 4, 1, EPI_QKV>(a, s);
-    return launch<8, 1, 4, 1, EPI_QKV>(a, s);
+    if (nb == 3 && shared_gpu && M > 256) return {8, 6, 4, 2};
+    if (nb == 3) return {8, 3, 8, 1};  // 8 waves of 32 x 96: measured 1.3 % faster than 4 of 64 x 96
+    if (nb == 2) return {8, 2, 4, 1};
+    return {8, 1, 4, 1};
 }
 
-hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
-    a.splits = 1;
-    const int bmb = pick_row_blocks(a.M);
+TileShape pick_swiglu(int M, int N, bool shared_gpu) {
+    const int bmb = pick_row_blocks(M);
     // A short chunk is bound by streaming the weights, and every CU that streams adds bandwidth: the narrower
     // tile (96 columns) when its tiles still fit one round of workgroups (measured at 64 rows, N = 22016:
     // 230 workgroups 38.0 us, 172 workgroups of 128 columns 40.9 us, 344 of 64 columns 47.1 us).
     // Beside other chunks' kernels (overlapped multi-chunk call) the opposite holds: 192-column tiles, fewer and
     // longer-running workgroups, and the other chunks take the CUs they leave (64-token chunks +1.5 %, 128-token
     // chunks +2.5 %, the 13B shapes +4 % over 128 columns, which in turn beat 96 by 2-6 % there).
-    if (a.shared_gpu && bmb == 2) return launch<2, 6, 2, 3, EPI_SWIGLU>(a, s);
-    if (a.shared_gpu && bmb == 4) return launch<4, 6, 4, 1, EPI_SWIGLU>(a, s);
-    const bool narrow = div_up(a.N, 96) <= kCUs;
-    if (bmb == 2) return narrow ? launch<2, 3, 2, 3, EPI_SWIGLU>(a, s) : launch<2, 4, 2, 2, EPI_SWIGLU>(a, s);
-    if (bmb == 4) return narrow ? launch<4, 3, 4, 1, EPI_SWIGLU>(a, s) : launch<4, 4, 4, 1, EPI_SWIGLU>(a, s);
+    if (shared_gpu && bmb == 2) return {2, 6, 2, 3};
+    if (shared_gpu && bmb == 4) return {4, 6, 4, 1};
+    const bool narrow = div_up(N, 96) <= kCUs;
+    if (bmb == 2) return narrow ? TileShape{2, 3, 2, 3} : TileShape{2, 4, 2, 2};
+    if (bmb == 4) return narrow ? TileShape{4, 3, 4, 1} : TileShape{4, 4, 4, 1};
     static const int cands[] = {2, 3, 4, 6};
-    const int nb = pick_blocks(a.M, a.N, cands, 4);
-    // beside other chunks' kernels: the widest tile (see launch_gemm_qkv); 256 x 256 over 256 x 192: +1.9 %
-    if (nb == 6 && a.shared_gpu) return launch<8, 8, 4, 2, EPI_SWIGLU, 0>(a, s);
-    if (nb == 6) return launch<8, 6, 4, 2, EPI_SWIGLU, GEMM_LW>(a, s);
-    if (nb == 4) return launch<8, 4, 4, 2, EPI_SWIGLU>(a, s);
-    if (nb == 3) return launch<8, 3, 4, 1, EPI_SWIGLU>(a, s);
-    return launch<8, 2, 4, 1, EPI_SWIGLU>(a, s);
+    const int nb = pick_blocks(M, N, cands, 4);
+    // beside other chunks' kernels: the widest tile (see pick_qkv); 256 x 256 over 256 x 192: +1.9 %
+    if (nb == 6 && shared_gpu) return {8, 8, 4, 2};
+    if (nb == 6) return {8, 6, 4, 2};
+    if (nb == 4) return {8, 4, 4, 2};
+    if (nb == 3) return {8, 3, 4, 1};
+    return {8, 2, 4, 1};
+}
+
+TileShape pick_partial(int M, int N, int K, bool shared_gpu) {
+    const int bmb = pick_row_blocks(M);
+    // (short chunks beside other chunks' kernels keep the 128-column tile: 64-token chunks +3 %, 128-token +5 %)
+    const bool narrow = gemm_partial_col_blocks(M, N, K) == 2 && !shared_gpu;
+    if (bmb == 2) return narrow ? TileShape{2, 2, 2, 2} : TileShape{2, 4, 2, 2};
+    if (bmb == 4) return narrow ? TileShape{4, 2, 4, 1} : TileShape{4, 4, 4, 1};
+    // beside other chunks' kernels: the widest tile, as for QKV and gate/up (256 x 256 over 256 x 128: +2.4 %)
+    if (shared_gpu) return {8, 8, 4, 2};
+    return {8, 4, 4, 2};
+}
+
+template <int EPI>
+hipError_t dispatch(TileShape t, const GemmArgs& a, hipStream_t s) {
+#define X(BMB, NB, WM, WN, E)                                                         \
+    if constexpr (E == EPI)                                                           \
+        if (t.bmb == BMB && t.nb == NB && t.wm == WM && t.wn == WN) return launch<BMB, NB, WM, WN, EPI>(a, s);
+    JUP_GEMM_SHAPES(X)
+#undef X
+    return hipErrorInvalidConfiguration;  // a shape the pick functions name but the list above does not hold
+}
+
+}  // namespace
+
+hipError_t launch_gemm_qkv(GemmArgs a, hipStream_t s) {
+    a.splits = 1;
+    return dispatch<EPI_QKV>(pick_qkv(a.M, a.N, a.shared_gpu), a, s);
+}
+
+hipError_t launch_gemm_swiglu(GemmArgs a, hipStream_t s) {
+    a.splits = 1;
+    return dispatch<EPI_SWIGLU>(pick_swiglu(a.M, a.N, a.shared_gpu), a, s);
 }
 
 hipError_t launch_gemm_partial(GemmArgs a, hipStream_t s) {
     a.splits = gemm_plan_splits(a.M, a.N, a.K, a.shared_gpu);
-    const int bmb = pick_row_blocks(a.M);
-    // (short chunks beside other chunks' kernels keep the 128-column tile: 64-token chunks +3 %, 128-token +5 %)
-    const bool narrow = gemm_partial_col_blocks(a.M, a.N, a.K) == 2 && !a.shared_gpu;
-    if (bmb == 2) return narrow ? launch<2, 2, 2, 2, EPI_PARTIAL>(a, s) : launch<2, 4, 2, 2, EPI_PARTIAL>(a, s);
-    if (bmb == 4) return narrow ? launch<4, 2, 4, 1, EPI_PARTIAL>(a, s) : launch<4, 4, 4, 1, EPI_PARTIAL>(a, s);
-    // beside other chunks' kernels: the widest tile, as for QKV and gate/up (256 x 256 over 256 x 128: +2.4 %)
-    if (a.shared_gpu) return launch<8, 8, 4, 2, EPI_PARTIAL, 0>(a, s);
-    return launch<8, 4, 4, 2, EPI_PARTIAL, GEMM_LW>(a, s);
+    return dispatch<EPI_PARTIAL>(pick_partial(a.M, a.N, a.K, a.shared_gpu), a, s);
+}
+
+// "gemm_bf16<row blocks,column blocks,waves along M,waves along N,epilogue>" of the launch a projection of M rows takes
+void gemm_kernel_name(GemmKind kind, int M, int d_model, int d_ffn, bool shared_gpu, char* buf, size_t size) {
+    TileShape t{};
+    int epi = EPI_PARTIAL;
+    switch (kind) {
+        case GEMM_QKV: t = pick_qkv(M, 3 * d_model, shared_gpu); epi = EPI_QKV; break;
+        case GEMM_GATE_UP: t = pick_swiglu(M, 2 * d_ffn, shared_gpu); epi = EPI_SWIGLU; break;
+        case GEMM_O: t = pick_partial(M, d_model, d_model, shared_gpu); break;
+        case GEMM_DOWN: t = pick_partial(M, d_model, d_ffn, shared_gpu); break;
+    }
+    snprintf(buf, size, "gemm_bf16<%d,%d,%d,%d,%d>", t.bmb, t.nb, t.wm, t.wn, epi);
 }
 
 }  // namespace jup
