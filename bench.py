@@ -6,13 +6,20 @@ processes a 2048-token prompt chunk by chunk (4 chunks of 512), every chunk atte
 of the earlier ones.  A step is one pass of the whole hot path over that prompt.  Inputs are seeded synthetic
 tensors (hidden ~ N(0,1), weights ~ N(0, 0.02^2)) already resident in HBM when the timed region starts.
 
-A step feeds the whole prompt with ONE jup_stage_prefill_chunks call: consecutive chunks overlap on up to four
-streams (two for chunks above 256 tokens whose number is not a multiple of four), each chunk waiting per layer only
-for the cache appends of the chunks before it; --no-overlap feeds them one call after the other.
+A step feeds the prompt with one jup_stage_prefill_chunk call per chunk, one after the other on one stream: the
+situation of every pipeline stage but the first, which receives a sub-sequence when its neighbour has finished it
+(Sec. IV-A.2), and the definition of the paper's latency function q(x, y) (Sec. IV-B.2).  `value` is the tokens/s of
+those steps.  Beside it the JSON line carries
+  per_call    every call bracketed by an event pair: median milliseconds per chunk index (q(chunk, c * chunk)) and
+              tokens/s = sum of tokens / sum of call times;
+  overlapped  the same prompt fed with ONE jup_stage_prefill_chunks call whose consecutive chunks overlap on up to four
+              streams (possible where all chunks are at hand, i.e. at a pipeline's first stage); --no-overlap skips it;
+  clock_mhz   the shader clock the chip held during the timed steps (a one-wave probe kernel on a second stream);
+  roofline    the dominant kernel (the gate/up GEMM with the SwiGLU epilogue), timed in place with HIP events;
+  cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample of the same workload.
+--calibrate-mfma adds `mfma_calibration`: what a bare MFMA loop on random operands sustains on this chip.
 
-Prints ONE JSON line.  `roofline` is for the dominant kernel (the gate/up GEMM with the SwiGLU epilogue),
-timed in place with HIP events in a second pass that feeds the chunks one call after the other; `cpu_baseline` is the CPU oracle
-timed on this machine's host cores on a bounded sample of the same workload.
+Prints ONE JSON line.
 
 --workload selects the other benchmark configurations (same JSON line; they are reporting runs, the
 default is the metric):
@@ -36,10 +43,28 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
-# HBM bytes per launch of the dominant kernel of the default workload (chunk 512), from rocprofv3 FETCH_SIZE /
-# WRITE_SIZE runs of this script scaled by a 256 MiB copy (--calibrate-copy); the summary of those runs lies
-# under profiles/.
-GATE_UP_TRAFFIC_BYTES = {("c3", 512): (106897.5 * 2.0 + 11050.6 * 1.0) * 1024}
+# HBM bytes per launch of the dominant kernel come from the rocprofv3 FETCH_SIZE / WRITE_SIZE summary under
+# profiles/ (runs of this script, scaled by a 256 MiB copy: --calibrate-copy); its TRAFFIC lines are keyed by
+# workload, chunk size and the kernel instantiation the counters were read for.
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "bench_7b_prompt2048_chunk512_hbm_traffic.txt")
+
+
+def read_traffic(path, workload, chunk, kernel):
+    """Bytes per launch from a line `TRAFFIC workload=c3 chunk=512 kernel=<name> fetch_kib=.. fetch_factor=..
+    write_kib=.. write_factor=..`, or None when the table has no line for this kernel instantiation (the counters
+    were then read for another tiling and say nothing about this one)."""
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return None
+    for line in lines:
+        if not line.startswith("TRAFFIC "):
+            continue
+        kv = dict(item.split("=", 1) for item in line.split()[1:])
+        if kv.get("workload") == workload and kv.get("chunk") == str(chunk) and kv.get("kernel") == kernel:
+            return (float(kv["fetch_kib"]) * float(kv["fetch_factor"]) +
+                    float(kv["write_kib"]) * float(kv["write_factor"])) * 1024.0
+    return None
 
 
 def flops_per_call(cfg, n, p):
@@ -76,9 +101,11 @@ def main():
                          "JUP_BF16_W4), the precision the paper runs its models in; its kernels are built for the "
                          "decode-sized workloads c5 and tree (prefill-sized chunks run, 64 rows per pass)")
     ap.add_argument("--no-overlap", action="store_true",
-                    help="feed the chunks of a prompt one call after the other instead of one jup_stage_prefill_chunks "
-                         "call whose consecutive chunks overlap on several streams (profiling runs use this, so that "
-                         "a kernel's duration is its own)")
+                    help="skip the `overlapped` leg (one jup_stage_prefill_chunks call whose consecutive chunks overlap "
+                         "on several streams); profiling runs use this, so that every kernel's duration is its own")
+    ap.add_argument("--calibrate-mfma", action="store_true",
+                    help="also run a bare MFMA loop on random operands for about 150 ms and report what it sustains "
+                         "(TFLOP/s, the shader clock it held) as `mfma_calibration`")
     ap.add_argument("--lanes", type=int, default=4,
                     help="lanes enabled for the overlapped call (2..4; for chunks above 256 tokens the library uses all "
                          "of them only when the number of chunks is a multiple of four, else two)")
@@ -193,17 +220,19 @@ def main():
                 lo = c * chunk
                 stage.prefill_chunk(hidden[lo:lo + chunk], lo, kv, hidden_out=out[lo:lo + chunk])
 
-        if args.no_overlap or n_chunks < 2:
-            step = step_sequential
-        else:
+        step = step_sequential
+        step_overlapped = None
+        if not args.no_overlap and n_chunks >= 2 and not args.w4:
             stage.enable_overlap(args.lanes)
             # the library's lane rule (jup_stage_prefill_chunks)
             lanes_used = min(2 if chunk > 256 and n_chunks % 4 else args.lanes, n_chunks)
-            what += f"; one call for the whole prompt, consecutive chunks overlapping on {lanes_used} streams"
 
-            def step():
+            def step_overlapped():
                 kv.reset()
                 stage.prefill_chunks(hidden, [chunk] * n_chunks, 0, kv, hidden_out=out)
+        what += "; one jup_stage_prefill_chunk call per chunk, one after the other"
+    if wl in ("c5", "tree"):
+        step_overlapped = None
     torch.cuda.synchronize()
     print(f"[bench] inputs ready in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
@@ -215,14 +244,58 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    def timed(fn, probe=False):
+        """args.warmup untimed and args.steps timed runs of fn; (seconds, clock in MHz or None).  With probe, a
+        one-wave kernel on a second stream reads the shader clock against the 100 MHz reference clock for about 80 % of
+        the timed region."""
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        ticks = None
+        if probe:
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            one = time.perf_counter() - t0
+            ticks = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+            side = torch.cuda.Stream()
+            torch.cuda.synchronize()
+            jb.diag_clock_probe(max(int(0.8 * one * args.steps * 1e8), 1000), ticks, stream=side)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.current_stream().synchronize()
+        dt = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        mhz = None
+        if ticks is not None:
+            t = ticks.cpu().tolist()
+            mhz = round(100.0 * t[0] / max(t[1], 1), 1)
+        return dt, mhz
+
+    mfma_calibration = None
+    if args.calibrate_mfma:
+        ops = torch.randn(1 << 19, device="cuda:0").to(torch.bfloat16)   # 1 MiB of random bf16 values
+        n_wg, ticks, sink = 256, torch.zeros((256, 2), dtype=torch.int64, device="cuda:0"), torch.zeros(1, device="cuda:0")
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        iters = 20000
+        for _ in range(2):   # the second launch is sized from the first so that it lasts about 150 ms
+            ev[0].record()
+            flop = jb.diag_mfma_loop(ops, n_wg, iters, ticks, sink)
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1])
+            last_iters, iters = iters, max(int(iters * 150.0 / max(ms, 1e-3)), 1000)
+        t = ticks.cpu().numpy().astype("float64")
+        mfma_calibration = {"kernel": "bare loop of v_mfma_f32_32x32x16_bf16 on random operands, 256 workgroups x 8 waves "
+                                      "(two per SIMD), 8 independent accumulators per wave",
+                            "ms": round(ms, 2), "iters_per_wave": last_iters, "tflops": round(flop / ms / 1e9, 1),
+                            "frac_of_published_peak": round(flop / ms / 1e9 / PEAK_BF16_TFLOPS, 4),
+                            "clock_mhz_mean": round(float(100.0 * (t[:, 0] / t[:, 1]).mean()), 1),
+                            "clock_mhz_min": round(float(100.0 * (t[:, 0] / t[:, 1]).min()), 1)}
+        del ops
+
+    elapsed, clock_mhz = timed(step, probe=True)
     out_timed = out.clone() if wl in ("c2", "c3", "c4") else None  # what the timed steps wrote (the passes below reuse out)
     ms_per_step = elapsed / args.steps * 1e3
     tokens_per_s = tokens_per_step * args.steps / elapsed
@@ -236,10 +309,45 @@ def main():
     step_tflops = step_flops / (ms_per_step * 1e-3) / 1e12
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
+    # q(x, y) of Sec. IV-B.2: every call between two events on the stream it runs on, median over the steps.
+    per_call = None
+    if wl in ("c2", "c3", "c4"):
+        evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_chunks)]
+               for _ in range(args.steps)]
+        for rep in range(args.steps):
+            kv.reset()
+            for c in range(n_chunks):
+                lo = c * chunk
+                evs[rep][c][0].record()
+                stage.prefill_chunk(hidden[lo:lo + chunk], lo, kv, hidden_out=out[lo:lo + chunk])
+                evs[rep][c][1].record()
+        torch.cuda.synchronize()
+        ms_chunk = [float(np.median([evs[rep][c][0].elapsed_time(evs[rep][c][1]) for rep in range(args.steps)]))
+                    for c in range(n_chunks)]
+        pc_s = sum(ms_chunk) * 1e-3
+        per_call = {"what": "one jup_stage_prefill_chunk call between two events, median over the steps; chunk c is "
+                            "q(chunk_tokens, c * chunk_tokens)",
+                    "ms_per_chunk": [round(m, 4) for m in ms_chunk],
+                    "tokens_per_s": round(prompt / pc_s, 1),
+                    "tflops": round(step_flops / pc_s / 1e12, 1),
+                    "frac_of_bf16_mfma_peak": round(step_flops / pc_s / 1e12 / PEAK_BF16_TFLOPS, 4)}
+
+    # The same prompt in one call, consecutive chunks overlapping on several streams.
+    overlapped = None
+    if step_overlapped is not None:
+        o_elapsed, o_mhz = timed(step_overlapped, probe=True)
+        o_ms = o_elapsed / args.steps * 1e3
+        overlapped = {"what": f"one jup_stage_prefill_chunks call for the whole prompt, consecutive chunks overlapping on "
+                              f"{lanes_used} streams (all chunks at hand: a pipeline's first stage)",
+                      "tokens_per_s": round(tokens_per_step * args.steps / o_elapsed, 1), "ms_per_step": round(o_ms, 4),
+                      "tflops": round(step_flops / (o_ms * 1e-3) / 1e12, 1),
+                      "frac_of_bf16_mfma_peak": round(step_flops / (o_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                      "clock_mhz": o_mhz}
+
     # Second pass: the same work with an event pair around every launch of one kernel class at a time, the
     # chunks one after the other (overlapping chunks share the GPU, and a kernel's duration would include its wait
     # for the other chunk's kernels).
-    trace_step = step_sequential if wl in ("c2", "c3", "c4") else step
+    trace_step = step
     per_kernel = {}
     for name in ("gemm_gate_up", "gemm_qkv", "gemm_down", "gemm_o", "attention", "rmsnorm"):
         stage.trace(jb.KERNEL_IDS[name], max_launches=4 * cfg["n_layers"] * len(calls) * max(args.steps, 1))
@@ -256,7 +364,8 @@ def main():
     d, f = cfg["d_model"], cfg["d_ffn"]
     dom_flops = 2.0 * n_call * (2 * f) * d  # one launch: [n, d] x [2f, d]^T
     dom_bytes = wbytes * 2 * f * d + 2.0 * (n_call * d + n_call * f)  # weights + activations in + activations out
-    dom_name = "gemm_w4<gate_up+swiglu>" if args.w4 else "gemm_bf16<gate_up+swiglu>"
+    dom_name = "gemm_w4<gate_up+swiglu>" if args.w4 else stage.kernel_name(jb.KERNEL_IDS["gemm_gate_up"], n_call)
+    traffic = None if args.w4 else read_traffic(TRAFFIC_TABLE, wl, chunk, dom_name)
     dom_s = dom["avg_us"] * 1e-6
     # which roof the dominant kernel sits under: the ridge of the chip is peak flop/s over peak byte/s
     if dom_flops / dom_bytes >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
@@ -270,8 +379,11 @@ def main():
     roofline.update({"timed": "event pairs around each launch in a pass that feeds the chunks one call after the other "
                               "(in the overlapped call two chunks share the GPU and a launch waits for its share)",
                      "avg_launch_us": round(dom["avg_us"], 2), "flop_per_launch": dom_flops,
-                     "algorithmic_bytes": dom_bytes, "traffic": None if args.w4 else GATE_UP_TRAFFIC_BYTES.get((wl, chunk)),
-                     "traffic_unit": "bytes per launch (offline rocprofv3 counters)"})
+                     "algorithmic_bytes": dom_bytes, "traffic": traffic,
+                     "traffic_unit": "HBM bytes per launch",
+                     "traffic_source": (os.path.relpath(TRAFFIC_TABLE, ROOT) + " (rocprofv3 FETCH_SIZE / WRITE_SIZE runs of "
+                                        "this script for this kernel instantiation)") if traffic else
+                                       "no counter reading on file for this kernel instantiation"})
 
     cpu_baseline = None
     if not args.no_cpu_baseline and wl not in ("c5", "tree"):
@@ -312,6 +424,10 @@ def main():
         "frac_of_bf16_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
         "algorithmic_gb_per_s": round(step_gbs, 1),
         "frac_of_hbm_peak": round(step_gbs / PEAK_HBM_GBS, 4),
+        "clock_mhz": clock_mhz,
+        "per_call": per_call,
+        "overlapped": overlapped,
+        "mfma_calibration": mfma_calibration,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in per_kernel.items()},

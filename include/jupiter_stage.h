@@ -356,6 +356,41 @@ JUP_API jup_status_t jup_stage_trace(jup_stage_t *stage, int32_t kernel_id, int3
  */
 JUP_API jup_status_t jup_stage_trace_read(jup_stage_t *stage, double *total_ms, int32_t *launches, int32_t *dropped);
 
+/* ---- calibration of the chip (benchmarks) ------------------------------------------------------- */
+
+/*
+ * What the matrix cores sustain when they do nothing else: the yardstick the measured GEMMs are held against
+ * beside the published peak (Sec. III step 1 profiles the devices the model runs on; this is the part of such a
+ * profile that the roofline needs).  Launches n_workgroups workgroups of 8 waves (two per SIMD); every wave runs
+ * iters_per_wave rounds of 8 independent 32x32x16 bf16 MFMAs on fragments taken from `operands`.
+ *   operands        DEVICE, >= 530432 bytes of bf16 values (random data gives the power draw of real operands)
+ *   ticks           DEVICE, uint64 [n_workgroups][2]: shader-clock ticks and 100 MHz reference-clock ticks the
+ *                   loop of each workgroup took (their ratio x 100 MHz is the clock the chip held)
+ *   sink            DEVICE, one float (never written in practice; keeps the arithmetic alive)
+ *   flop            HOST out, may be NULL: floating-point operations of the launch
+ * The caller times the launch (events on `stream`).  Errors: JUP_EINVAL, JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_diag_mfma_loop(const void *operands, size_t operand_bytes, int32_t n_workgroups,
+                                        int64_t iters_per_wave, void *ticks, float *sink, void *stream, double *flop);
+
+/*
+ * Which instantiation of the projection kernel a chunk of n_tokens runs as: "gemm_bf16<row blocks,column blocks,
+ * waves along M,waves along N,epilogue>" written to buf (HOST, size bytes, always terminated).  overlapped != 0:
+ * inside an overlapped jup_stage_prefill_chunks() call.  A benchmark uses it to tell whether a hardware-counter
+ * reading kept on file was taken for the tiling that runs today.  kernel_id: one of the four JUP_K_GEMM_* ids.
+ * Errors: JUP_EINVAL (NULL, not a projection id, not a JUP_BF16 stage).
+ */
+JUP_API jup_status_t jup_diag_kernel_name(const jup_stage_t *stage, int32_t kernel_id, int32_t n_tokens,
+                                          int32_t overlapped, char *buf, size_t size);
+
+/*
+ * The shader clock held while other work runs: one wave that sleeps until ref_ticks ticks of the 100 MHz
+ * reference clock have passed (it always ends) and then writes {shader-clock ticks, reference ticks} (uint64
+ * [2], DEVICE) .  Launch it on a stream of its own beside the work to be observed.
+ * 1 <= ref_ticks <= 2^30 (about 10 s).  Errors: JUP_EINVAL, JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_diag_clock_probe(int64_t ref_ticks, void *ticks, void *stream);
+
 /* Message of the last error on this thread ("" if none). Never NULL. */
 JUP_API const char *jup_last_error(void);
 

@@ -76,6 +76,9 @@ def lib():
             "jup_stage_trace": (i32, [vp, i32, i32]),
             "jup_stage_trace_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32),
                                            ctypes.POINTER(i32)]),
+            "jup_diag_mfma_loop": (i32, [vp, sz, i32, ctypes.c_int64, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]),
+            "jup_diag_clock_probe": (i32, [ctypes.c_int64, vp, vp]),
+            "jup_diag_kernel_name": (i32, [vp, i32, i32, i32, ctypes.c_char_p, sz]),
             "jup_last_error": (ctypes.c_char_p, []),
         }
         for name, (res, args) in sig.items():
@@ -291,6 +294,12 @@ class Stage:
         _check(lib().jup_stage_trace_read(self.handle, ctypes.byref(ms), ctypes.byref(n), ctypes.byref(dr)))
         return ms.value, n.value, dr.value
 
+    def kernel_name(self, kernel_id, n_tokens, overlapped=False):
+        """Name of the projection kernel instantiation a chunk of n_tokens runs as (jup_diag_kernel_name)."""
+        buf = ctypes.create_string_buffer(96)
+        _check(lib().jup_diag_kernel_name(self.handle, int(kernel_id), int(n_tokens), int(bool(overlapped)), buf, 96))
+        return buf.value.decode()
+
     def destroy(self):
         if self.handle:
             lib().jup_stage_destroy(self.handle)
@@ -325,3 +334,18 @@ def upload_w4_layers(layers_np, device="cuda:0"):
             d[n] = torch.from_numpy(w[n]).to(device=device, dtype=torch.bfloat16).contiguous()
         out.append(d)
     return out
+
+
+def diag_mfma_loop(operands, n_workgroups, iters_per_wave, ticks, sink, stream=None):
+    """Enqueues the bare MFMA loop (jup_diag_mfma_loop); returns its flop count.  operands: bf16 tensor, ticks: int64
+    tensor [n_workgroups, 2], sink: float32 tensor [1], all on the GPU."""
+    flop = ctypes.c_double()
+    _check(lib().jup_diag_mfma_loop(ctypes.c_void_p(operands.data_ptr()), operands.numel() * operands.element_size(),
+                                    int(n_workgroups), int(iters_per_wave), ctypes.c_void_p(ticks.data_ptr()),
+                                    ctypes.c_void_p(sink.data_ptr()), _stream_handle(stream), ctypes.byref(flop)))
+    return flop.value
+
+
+def diag_clock_probe(ref_ticks, ticks, stream=None):
+    """Enqueues the one-wave clock probe (jup_diag_clock_probe); ticks: int64 tensor [2] on the GPU."""
+    _check(lib().jup_diag_clock_probe(int(ref_ticks), ctypes.c_void_p(ticks.data_ptr()), _stream_handle(stream)))

@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libjupiter_stage.so")
 SOURCES = ["jup_api.hip", "kernels_f32.hip", "bf16_forward.hip", "bf16_gemm.hip", "bf16_attention.hip",
-           "bf16_misc.hip", "kv_ops.hip", "jup_plan.hip", "w4_gemm.hip"]
+           "bf16_misc.hip", "kv_ops.hip", "jup_plan.hip", "w4_gemm.hip", "diag.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",

@@ -504,10 +504,6 @@ jup::KvView view_of(const jup_kv_t* kv) {
 }
 }  // namespace
 
-extern "C" {
-
-}  // extern "C"
-
 namespace {
 // One chunk, ordinary (parents == NULL) or a token tree.
 jup_status_t prefill_one(const char* me, jup_stage_t* stage, const void* hidden_in, int32_t n_tokens,
@@ -664,11 +660,17 @@ jup_status_t jup_stage_prefill_chunks(jup_stage_t* stage, const void* hidden_in,
         out += (size_t)n * row_bytes;
         ++i;
     }
-    // the caller's stream continues when the other lanes are done
-    for (int lane = 1; lane < n_lanes && e == hipSuccess; ++lane) {
-        e = hipEventRecord(o->ev_join[lane], o->stream[lane]);
-        if (e == hipSuccess) e = hipStreamWaitEvent(s0, o->ev_join[lane], 0);
+    // The caller's stream continues when the other lanes are done.  Also when a launch failed half way: the lanes
+    // that already run write cache entries and hidden_out, and whatever the caller enqueues next must be ordered
+    // behind them.  The cache length then stays as it was: the entries past it are unspecified, as after any
+    // failed call, and the next call at pos_offset <= length overwrites them.
+    hipError_t ej = hipSuccess;
+    for (int lane = 1; lane < n_lanes; ++lane) {
+        hipError_t e1 = hipEventRecord(o->ev_join[lane], o->stream[lane]);
+        if (e1 == hipSuccess) e1 = hipStreamWaitEvent(s0, o->ev_join[lane], 0);
+        if (ej == hipSuccess) ej = e1;
     }
+    if (e == hipSuccess) e = ej;
     if (e != hipSuccess) return fail(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
     kv->len = pos;
     return JUP_OK;
