@@ -11,7 +11,10 @@ F32_MAX_ABS, F32_REL_L2 = 1e-3, 1e-4
 BF16_REL_L2 = 2e-2
 # bf16 / 4-bit stages, every row by itself (a row = the last axis: one token's hidden state, or one cached key or
 # value vector of one head): a whole-tensor norm over hundreds of rows would let a single wrong row through.
-BF16_ROW_REL_L2 = 3e-2
+# Largest rows observed over all GPU parity tests: 2.2e-2 for a hidden-state row and 2.8e-2 for a cached key (layer 10
+# of the 13B-shaped stage, a key of small norm: rounding noise grows with depth and is measured against the row's
+# own norm); a row that is wrong in structure (a stale or misplaced tile, a wrong position) is off by tens of per cent.
+BF16_ROW_REL_L2 = 4e-2
 
 
 def rel_l2(a, b):

@@ -1,7 +1,7 @@
 """GPU parity: the HIP library against the CPU oracle, through the C ABI, on the same seeded inputs.
 
 Bars: fp32 check mode max-abs <= 1e-3 and rel-L2 <= 1e-4; bf16 and 4-bit stages rel-L2 <= 2e-2 on hidden_out and on
-the cached K/V values as whole tensors AND <= 3e-2 for every row by itself (one token's hidden state, one cached key
+the cached K/V values as whole tensors AND <= 4e-2 for every row by itself (one token's hidden state, one cached key
 or value vector of one head; helpers.Pair.check does both); which cache slots are written, and nothing else, bit-exact.
 """
 import numpy as np
