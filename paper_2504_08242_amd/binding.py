@@ -69,6 +69,7 @@ def lib():
             "jup_kv_check_append": (i32, [vp, i32, i32]),
             "jup_kv_destroy": (i32, [vp]),
             "jup_stage_prefill_chunk": (i32, [vp, vp, i32, i32, vp, vp, vp]),
+            "jup_stage_prefill_chunk_static": (i32, [vp, vp, i32, i32, vp, vp, vp]),
             "jup_stage_prefill_branches": (i32, [vp, i32, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), vp, vp]),
             "jup_stage_prefill_chunks": (i32, [vp, vp, i32, ctypes.POINTER(i32), i32, vp, vp, vp]),
             "jup_stage_enable_overlap": (i32, [vp, i32, vp, sz]),
@@ -231,6 +232,16 @@ class Stage:
         _check(lib().jup_stage_prefill_chunk(self.handle, ctypes.c_void_p(hidden_in.data_ptr()), n, int(pos_offset),
                                              kv.handle, ctypes.c_void_p(hidden_out.data_ptr()),
                                              _stream_handle(stream)))
+        return hidden_out
+
+    def prefill_chunk_static(self, hidden_in, pos_offset, kv, hidden_out, stream=None):
+        """jup_stage_prefill_chunk_static: the same call on the library's static scratch.  hidden_out is required (the
+        entry point exists for callers that cannot allocate, so the binding does not allocate for them either)."""
+        n = int(hidden_in.shape[0])
+        assert hidden_in.is_contiguous() and hidden_in.dtype == _torch_dtype(self.dtype)
+        _check(lib().jup_stage_prefill_chunk_static(self.handle, ctypes.c_void_p(hidden_in.data_ptr()), n,
+                                                    int(pos_offset), kv.handle, ctypes.c_void_p(hidden_out.data_ptr()),
+                                                    _stream_handle(stream)))
         return hidden_out
 
     def enable_overlap(self, n_lanes=2):

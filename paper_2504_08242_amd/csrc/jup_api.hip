@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "jup_internal.h"
@@ -566,6 +567,63 @@ jup_status_t jup_stage_prefill_chunk(jup_stage_t* stage, const void* hidden_in, 
                                      int32_t pos_offset, jup_kv_t* kv, void* hidden_out, void* stream) {
     return prefill_one("jup_stage_prefill_chunk", stage, hidden_in, n_tokens, pos_offset, nullptr, false, kv,
                        hidden_out, stream);
+}
+
+}  // extern "C"
+
+// ---- the entry point that allocates nothing ------------------------------------------------------------------
+// Scratch of jup_stage_prefill_chunk_static(): lives in the code object, one copy per GPU the library runs on, held
+// until the process ends.  In host code the name below is only a handle for hipGetSymbolAddress(); the device address
+// it yields (per device) is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[JUP_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device; looked up once per device.
+hipError_t static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
+extern "C" {
+
+jup_status_t jup_stage_prefill_chunk_static(jup_stage_t* stage, const void* hidden_in, int32_t n_tokens,
+                                            int32_t pos_offset, jup_kv_t* kv, void* hidden_out, void* stream) {
+    const char* me = "jup_stage_prefill_chunk_static";
+    if (!stage) return fail(JUP_EINVAL, "%s: stage is NULL", me);
+    if (n_tokens < 0) return fail(JUP_EINVAL, "%s: n_tokens=%d is negative", me, n_tokens);
+    // the same forward on a copy of the stage whose workspace is the static array, laid out for this chunk alone
+    jup_stage view = *stage;
+    view.overlap = nullptr;
+    if (n_tokens > 0) {
+        view.wl = jup::workspace_layout(stage->cfg, n_tokens);
+        if (view.wl.total > (size_t)JUP_STATIC_SCRATCH_BYTES)
+            return fail(JUP_ECAP, "%s: a chunk of %d tokens of this stage needs %zu bytes of scratch, the static buffer "
+                        "holds %d (use jup_stage_prefill_chunk with a caller-provided workspace)", me, n_tokens,
+                        view.wl.total, JUP_STATIC_SCRATCH_BYTES);
+        void* ptr = nullptr;
+        const hipError_t e = static_scratch(&ptr);
+        if (e != hipSuccess) return fail(JUP_EDEVICE, "%s: address of the static scratch: %s", me, hipGetErrorString(e));
+        view.workspace = ptr;
+        view.max_chunk_tokens = n_tokens;
+    }
+    return prefill_one(me, &view, hidden_in, n_tokens, pos_offset, nullptr, false, kv, hidden_out, stream);
 }
 
 jup_status_t jup_stage_prefill_tree(jup_stage_t* stage, const void* hidden_in, int32_t n_tokens, int32_t pos_offset,
