@@ -236,20 +236,21 @@ JUP_API jup_status_t jup_stage_prefill_chunk(jup_stage_t *stage, const void *hid
  * jup_stage_prefill_chunk() for callers that cannot allocate device memory or hold a workspace for the call: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
  * results bit for bit; the scratch of the call (residual stream, normalised rows, queries, attention output, SwiGLU
- * output, rotary table, K-split partial sums) lies in a static device array of JUP_STATIC_SCRATCH_BYTES inside the
+ * output, rotary table, K-split partial sums, key-split attention partials) lies in a static device array of JUP_STATIC_SCRATCH_BYTES inside the
  * library instead of the workspace given to jup_stage_create(), which this call does not touch.  The call
  * allocates nothing (no hipMalloc, hipFree or allocating library routine).
  *   - Every GPU the library runs on holds one copy of the array until the process ends; its address is looked up
  *     once per device, on the first call with that device current.
- *   - The chunk must fit: jup_stage_workspace_bytes(cfg, n_tokens) - 256 <= JUP_STATIC_SCRATCH_BYTES (a 7B-shaped
- *     stage: up to 160 tokens; 13B-shaped: 128; d_model 8192 with FFN 28672: 64), else JUP_ECAP and nothing is enqueued.  The
- *     stage's max_chunk_tokens does not limit this call.
+ *   - The chunk's scratch must fit the array (the scratch of ONE chunk of n_tokens, without the share that batched
+ *     branches add to a stage's workspace): a 7B-shaped stage runs up to 192 tokens, a 13B-shaped one 160, d_model
+ *     8192 with FFN 28672 and 64 heads 64; beyond that JUP_ECAP (the message names the bytes needed) and nothing is
+ *     enqueued.  The stage's max_chunk_tokens does not limit this call.
  *   - All calls on one GPU share the array, whatever their stage or stream: calls that overlap in time on one GPU
  *     race.  Issue them on one stream, or order them with events.  Nothing in the array has to survive between
  *     calls or start at zero.
  * Errors: as jup_stage_prefill_chunk(), plus JUP_ECAP as above and JUP_EDEVICE if the array's address cannot be found.
  */
-#define JUP_STATIC_SCRATCH_BYTES (32 << 20)
+#define JUP_STATIC_SCRATCH_BYTES (48 << 20)
 JUP_API jup_status_t jup_stage_prefill_chunk_static(jup_stage_t *stage, const void *hidden_in, int32_t n_tokens,
                                                     int32_t pos_offset, jup_kv_t *kv, void *hidden_out, void *stream);
 

@@ -21,6 +21,14 @@
 // units), so the accumulators are rescaled a few times per kernel instead of once per tile; the exponentials
 // stay below 2^8, far inside bf16/fp32 range, and the final normalisation removes the common factor.
 //
+// Key splits.  A decode-sized chunk behind a long cached sequence (Sec. V: a few tokens per step against the whole
+// prompt and everything generated so far) has one query block per head, far fewer workgroups than the chip has
+// CUs, and each would walk the whole cache alone.  Such a launch splits the key tiles of a query block into up to 8
+// contiguous ranges, one workgroup each (blockIdx.y).  Every workgroup leaves its un-normalised result and softmax
+// statistics in a scratch buffer and counts itself in; the one that finds all others counted merges the ranges IN
+// RANGE ORDER with the log-sum-exp weights and writes the output, so the result does not depend on which workgroup
+// came last (bitwise reproducible), no workgroup ever waits for another, and there is no second launch.
+//
 // MFMA 32x32x16 bf16 operand layout (lane = 32*hh + c):
 //   A: lane supplies A[m = c][k = 8*hh + e], e < 8;  B: lane supplies B[k = 8*hh + e][n = c];
 //   D: lane holds D[m = 8*(i/4) + 4*hh + (i%4)][n = c] in register i < 16.
@@ -86,7 +94,8 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
                                                                   int n, int d_model, int n_heads, int pos0_arg,
                                                                   KvView kv_arg, int layer, float scale_log2e,
                                                                   const BranchTable* __restrict__ branches,
-                                                                  const TreeTable* __restrict__ tree) {
+                                                                  const TreeTable* __restrict__ tree,
+                                                                  float* __restrict__ split_buf, int* __restrict__ split_count) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -125,8 +134,15 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
     const size_t plane_k = ((size_t)layer * 2 + 0) * n_heads + head;
     const size_t plane_v = ((size_t)layer * 2 + 1) * n_heads + head;
 
-    const int cnt = n_tiles > g ? (n_tiles - g + KP - 1) / KP : 0;  // tiles of this key partition
-    const int max_cnt = (n_tiles + KP - 1) / KP;                    // of partition 0: every wave runs that many rounds
+    // key splits over workgroups: this one owns the tiles [t_lo, t_hi) of the query block
+    // (never more than the launch provides: a launch that does not split has gridDim.y = 1)
+    const int n_splits = min(att_key_splits(n, n_tiles), (int)gridDim.y);
+    const int ks = blockIdx.y;
+    if (ks >= n_splits) return;  // (a branch or query block with fewer keys than the longest of the launch)
+    const int t_lo = (int)((long)ks * n_tiles / n_splits), t_hi = (int)((long)(ks + 1) * n_tiles / n_splits);
+    const int n_own = t_hi - t_lo;
+    const int cnt = n_own > g ? (n_own - g + KP - 1) / KP : 0;  // tiles of this key partition
+    const int max_cnt = (n_own + KP - 1) / KP;                  // of partition 0: every wave runs that many rounds
     if (loader) {
         // The whole life of a loader wave: one tile ahead of the computing waves, the same barriers as they.
         // Tile fill (loader waves).  Load j covers rows 4j..4j+3 (1 KB of LDS); lane i lands at
@@ -165,15 +181,19 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
             if (lpart != 1) fill_part(tile, slot, false);
             if (lpart != 0) fill_part(tile, slot, true);
         };
-        if (cnt > 0) fill(g, 0);
+        if (cnt > 0) fill(t_lo + g, 0);
         for (int it = 0; it < max_cnt; ++it) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the tile of this round has landed
             __builtin_amdgcn_s_barrier();                     // ... and the other slot is free
-            if (it + 1 < cnt) fill(g + KP * (it + 1), (it + 1) & 1);
+            if (it + 1 < cnt) fill(t_lo + g + KP * (it + 1), (it + 1) & 1);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();  // the two barriers of the merge
         __syncthreads();
+        if (n_splits > 1) {  // ... and the two of the merge across workgroups
+            __syncthreads();
+            __syncthreads();
+        }
         return;
     }
 
@@ -209,7 +229,7 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
         // when they are done with the other slot, which the loader then refills.
         __builtin_amdgcn_s_barrier();
         if (it >= cnt) continue;
-        const int tile = g + KP * it, slot = it & 1;
+        const int tile = t_lo + g + KP * it, slot = it & 1;
         const unsigned char* k_base = grp + slot * kSlotBytes;
         const unsigned v_base = grp_addr + slot * kSlotBytes + kTileBytes;
 
@@ -317,7 +337,8 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
             const float mw = stat_m[w * QR + qb * 32 + c];
             l_all += mw == -INFINITY ? 0.f : stat_l[w * QR + qb * 32 + c] * exp2f(mw - m_all);
         }
-        const float wscale = m_run == -INFINITY ? 0.f : exp2f(m_run - m_all) / l_all;
+        // one workgroup for all keys: normalised here; key splits: left un-normalised for the merge across workgroups
+        const float wscale = m_run == -INFINITY ? 0.f : exp2f(m_run - m_all) / (n_splits > 1 ? 1.0f : l_all);
         float* mine = obuf + g * kRegion + (qb * 32 + c) * kORow;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
@@ -326,6 +347,10 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
                 *(float4*)(mine + db * 32 + 8 * gg + 4 * hh) =
                     make_float4(oacc[db][4 * gg] * wscale, oacc[db][4 * gg + 1] * wscale,
                                 oacc[db][4 * gg + 2] * wscale, oacc[db][4 * gg + 3] * wscale);
+        if (n_splits > 1 && g == 0 && hh == 0) {  // statistics of this key range, one pair per query row
+            store_coherent2(split_buf + ((size_t)(blockIdx.x * gridDim.y + ks) * QR + qb * 32 + c) * kAttSplitRow + 128,
+                            m_all, l_all);
+        }
     }
     __syncthreads();
     for (int idx = tid; idx < QR * 16; idx += 64 * KP * NQ) {  // the computing threads (tid < 64 KP NQ)
@@ -340,9 +365,72 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
             a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
             b.x += b2.x; b.y += b2.y; b.z += b2.z; b.w += b2.w;
         }
+        if (n_splits > 1) {
+            float* dst = split_buf + ((size_t)(blockIdx.x * gridDim.y + ks) * QR + qr) * kAttSplitRow + ch * 8;
+            store_coherent2(dst, a.x, a.y);
+            store_coherent2(dst + 2, a.z, a.w);
+            store_coherent2(dst + 4, b.x, b.y);
+            store_coherent2(dst + 6, b.z, b.w);
+            continue;
+        }
         u32x4 out;
         out[0] = pack_bf16x2(a.x, a.y); out[1] = pack_bf16x2(a.z, a.w);
         out[2] = pack_bf16x2(b.x, b.y); out[3] = pack_bf16x2(b.z, b.w);
+        *(u32x4*)(o + tiled_offset(row0 + qrow, head * 16 + ch, d_model >> 5)) = out;
+    }
+    if (n_splits == 1) return;
+
+    // ---- merge the key ranges of the query block across workgroups ---------------------------------------------------
+    // Every wave waits until its (chip-coherent) stores have been performed, the workgroup counts itself in, and the
+    // workgroup that finds all others already counted does the merge.  Nobody waits for anybody.
+    wait_stores_performed();
+    __syncthreads();
+    int* flag = (int*)(lds + kStatOffset);  // (the statistics in LDS are no longer needed)
+    if (tid == 0) {
+        const int before = arrive_coherent(split_count + blockIdx.x);
+        *flag = before == n_splits - 1;
+        if (before == n_splits - 1) split_count[blockIdx.x] = 0;  // ready for the next launch on this stream
+    }
+    __syncthreads();
+    if (!*flag) return;
+    const float* base = split_buf + (size_t)blockIdx.x * gridDim.y * QR * kAttSplitRow;
+    for (int idx = tid; idx < QR * 16; idx += 64 * KP * NQ) {
+        const int qr = idx >> 4, ch = idx & 15;
+        const int qrow = q0 + qr;
+        if (qrow >= n) continue;
+        // (max, sum) of every key range: at most 8, loops unrolled under a condition so that the array stays in
+        // registers; all loads first, then the sums in range order, whoever came last
+        static_assert(att_max_splits(1) <= 8, "the merge holds at most 8 ranges");
+        float2 stat[8], val[8][4];  // every load is issued before the first is used: they come from memory, not L2
+#pragma unroll
+        for (int sp = 0; sp < 8; ++sp)
+            if (sp < n_splits) {
+                const float* row = base + ((size_t)sp * QR + qr) * kAttSplitRow;
+                stat[sp] = load_coherent2(row + 128);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) val[sp][e] = load_coherent2(row + ch * 8 + 2 * e);
+            }
+        float m_all = -INFINITY;
+#pragma unroll
+        for (int sp = 0; sp < 8; ++sp)
+            if (sp < n_splits) m_all = fmaxf(m_all, stat[sp].x);
+        float l_all = 0.f;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int sp = 0; sp < 8; ++sp)
+            if (sp < n_splits && stat[sp].x != -INFINITY) {  // (-inf: a range this query sees nothing of)
+                const float w = exp2f(stat[sp].x - m_all);
+                l_all += stat[sp].y * w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[2 * e] += val[sp][e].x * w;
+                    acc[2 * e + 1] += val[sp][e].y * w;
+                }
+            }
+        const float inv = 1.0f / l_all;
+        u32x4 out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = pack_bf16x2(acc[2 * e] * inv, acc[2 * e + 1] * inv);
         *(u32x4*)(o + tiled_offset(row0 + qrow, head * 16 + ch, d_model >> 5)) = out;
     }
 }
@@ -363,8 +451,15 @@ hipError_t attention_configure() {
 // Block sizes: 4 NQ computing waves + 4 loader waves per part loaded separately.  Chunks of up to 64 tokens run
 // one query block per workgroup with separate K and V loaders (decode-sized attention is a chain of short
 // rounds, each as long as its tile fill); longer chunks two query blocks sharing every tile.
-void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
-                            int layer, hipStream_t s, const TreeTable* tree, bool shared_gpu) {
+namespace {
+// a split launch must fit the scratch the workspace reserves for it (it does by construction: see att_split_rows)
+bool split_fits(const AttScratch& sc, int wgs, int splits, int query_rows) {
+    return splits == 1 || ((size_t)wgs * splits * query_rows <= sc.rows && (size_t)wgs <= sc.counters);
+}
+}  // namespace
+
+hipError_t launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
+                                  int layer, hipStream_t s, AttScratch sc, const TreeTable* tree, bool shared_gpu) {
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
     const BranchTable* none = nullptr;
     // Beside other chunks' kernels (overlapped multi-chunk call): 128 queries per workgroup against two key halves,
@@ -373,28 +468,43 @@ void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_head
     // CU time: 4 x 512 tokens +2.4 %, no difference at 256-token chunks.
     if (shared_gpu && n > 256) {
         hipLaunchKernelGGL((chunk_attention_bf16<4, 2, 2>), dim3((n + 127) / 128 * n_heads), dim3(768), kAttLds, s, q, o,
-                           n, d_model, n_heads, pos0, kv, layer, scale_log2e, none, tree);
-        return;
+                           n, d_model, n_heads, pos0, kv, layer, scale_log2e, none, tree, sc.split_buf, sc.split_count);
+        return hipGetLastError();
     }
-    if (n <= 64)
-        hipLaunchKernelGGL((chunk_attention_bf16<1, 2>), dim3((n + 31) / 32 * n_heads), dim3(768), kAttLds, s, q, o, n,
-                           d_model, n_heads, pos0, kv, layer, scale_log2e, none, tree);
-    else
-        hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3((n + 63) / 64 * n_heads), dim3(768), kAttLds, s, q, o, n,
-                           d_model, n_heads, pos0, kv, layer, scale_log2e, none, tree);
+    // chunks of up to 256 tokens behind a long cached sequence: several workgroups per query block (key splits)
+    const int splits = att_key_splits(n, (pos0 + n + kKT - 1) / kKT);
+    if (n <= 64) {
+        const int wgs = (n + 31) / 32 * n_heads;
+        if (!split_fits(sc, wgs, splits, 32)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((chunk_attention_bf16<1, 2>), dim3(wgs, splits), dim3(768), kAttLds, s, q, o, n, d_model,
+                           n_heads, pos0, kv, layer, scale_log2e, none, tree, sc.split_buf, sc.split_count);
+    } else {
+        const int wgs = (n + 63) / 64 * n_heads;
+        if (!split_fits(sc, wgs, splits, 64)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3(wgs, splits), dim3(768), kAttLds, s, q, o, n, d_model, n_heads,
+                           pos0, kv, layer, scale_log2e, none, tree, sc.split_buf, sc.split_count);
+    }
+    return hipGetLastError();
 }
 
-void launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_model, int n_heads,
-                             const BranchTable* branches, int layer, hipStream_t s) {
+hipError_t launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_model, int n_heads,
+                                   const BranchTable* branches, int max_keys, int layer, hipStream_t s, AttScratch sc) {
     const float scale_log2e = 1.4426950408889634f / sqrtf(128.0f);
     const KvView none{};
     const TreeTable* no_tree = nullptr;
-    if (n <= 64)
-        hipLaunchKernelGGL((chunk_attention_bf16<1, 2>), dim3(n_branches * ((n + 31) / 32) * n_heads), dim3(768), kAttLds,
-                           s, q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches, no_tree);
-    else
-        hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3(n_branches * ((n + 63) / 64) * n_heads), dim3(768), kAttLds,
-                           s, q, o, n, d_model, n_heads, 0, none, layer, scale_log2e, branches, no_tree);
+    const int splits = att_key_splits(n, (max_keys + kKT - 1) / kKT);  // of the branch with the most keys
+    if (n <= 64) {
+        const int wgs = n_branches * ((n + 31) / 32) * n_heads;
+        if (!split_fits(sc, wgs, splits, 32)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((chunk_attention_bf16<1, 2>), dim3(wgs, splits), dim3(768), kAttLds, s, q, o, n, d_model,
+                           n_heads, 0, none, layer, scale_log2e, branches, no_tree, sc.split_buf, sc.split_count);
+    } else {
+        const int wgs = n_branches * ((n + 63) / 64) * n_heads;
+        if (!split_fits(sc, wgs, splits, 64)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(chunk_attention_bf16<2>, dim3(wgs, splits), dim3(768), kAttLds, s, q, o, n, d_model, n_heads,
+                           0, none, layer, scale_log2e, branches, no_tree, sc.split_buf, sc.split_count);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace jup

@@ -50,6 +50,28 @@ __device__ inline unsigned lds_byte_address(const void* p) {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
 }
 
+// Exchange between workgroups inside one kernel (partial results merged by the workgroup that finishes last).  The
+// chip has one L2 per XCD, and ordinary stores of one XCD are not seen by loads of another before the kernel ends;
+// a device-scope fence would fix that by writing back and invalidating the WHOLE L2, once per wave that executes it,
+// under the feet of every other workgroup of the XCD (measured: a decode-sized attention launch got 25-90 us slower).
+// These accessors instead make each access coherent by itself: relaxed atomics at device scope, which the hardware
+// performs as write-through stores and L2-bypassing loads, 8 bytes at a time.
+__device__ inline void store_coherent2(float* p, float a, float b) {
+    const unsigned long long bits = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+    __hip_atomic_store((unsigned long long*)p, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float2 load_coherent2(const float* p) {
+    const unsigned long long bits = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((unsigned)bits), __uint_as_float((unsigned)(bits >> 32)));
+}
+// Counts this workgroup in (call from ONE thread, after a workgroup barrier that follows every thread's coherent
+// stores and a wait for their completion); returns how many were counted before it.
+__device__ inline int arrive_coherent(int* counter) {
+    return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Waits until this wave's stores have been performed (a coherent store is performed when it is visible chip-wide).
+__device__ inline void wait_stores_performed() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -128,22 +150,66 @@ void launch_pack_w4_plain(unsigned char* dst, float* dst_scale, const void* c, c
                           hipStream_t s);
 
 // ---- attention (bf16_attention.hip) ---------------------------------------------------------------
+// Key splits of a query block over workgroups.  A chunk of up to 256 tokens has few query blocks; behind a long
+// cached sequence each of them gets several workgroups, every one with a contiguous range of at least 16 tiles of
+// 32 keys.  The number of ranges is a function of the chunk's length and of the query
+// block's own key count and of nothing else, so a result never depends on what else is in the launch (a branch
+// computes the same bits alone and batched with others).  The same function sizes the grid on the host (with the
+// longest key range of the launch) and tells every workgroup on the device how many ranges ITS query block has.
+// Measured on the 8-layer 7B-shaped stage, 5-token chunk: 8192 cached positions 1.63 -> 1.02 ms per call, 2048
+// positions 1.01 -> 0.88 ms, 512 positions unchanged (no split below 16 tiles per range); 64-token chunk behind 8192
+// positions 1.70 -> 1.28 ms, 128-token 1.94 -> 1.57 ms.
+constexpr int kAttSplitRow = 132;  // floats per query row in the scratch of a split launch: 128 outputs, max, sum, pad
+// (257..512 tokens as 128-query workgroups against one of two key ranges: measured slower than 64-query workgroups
+// against all keys, 35 vs 22 us per launch at 512 tokens: the exchange between the two workgroups goes through memory
+// and costs more than the shared tile fills save)
+__host__ __device__ constexpr int att_max_splits(int n) { return n <= 64 ? 8 : n <= 128 ? 4 : n <= 256 ? 2 : 1; }
+__host__ __device__ inline int att_key_splits(int n, int n_tiles) {
+    // a range is worth a workgroup from 16 tiles on (64-query workgroups, 65..256 tokens: 32, they already share
+    // every tile among two query blocks)
+    const int cap = att_max_splits(n), s = n_tiles / (n <= 64 ? 16 : 32);
+    return s < 1 ? 1 : s > cap ? cap : s;
+}
+// Scratch of split launches (workspace): split_buf holds kAttSplitRow floats per (query row, range), split_count one
+// arrival counter per (query block, head), zero between launches.  Upper bounds for chunks of up to T tokens, as one
+// chunk or as up to kMaxBranches branches: padded query rows x ranges <= 512 for one chunk (64 x 8, 128 x 4, 256 x 2),
+// <= 8 (T + 31 min(T, kMaxBranches)) for branches.
+inline size_t att_split_rows(int T, int n_heads, bool branches) {
+    const size_t b = T < kMaxBranches ? T : kMaxBranches;
+    const size_t per_head = branches ? 8 * ((size_t)T + 31 * b) : 512;
+    return (per_head < 512 ? 512 : per_head) * (size_t)n_heads;
+}
+inline size_t att_split_counters(int T, int n_heads, bool branches) {
+    const size_t b = T < kMaxBranches ? T : kMaxBranches;
+    return ((size_t)(T + 31) / 32 + (branches ? b : 0)) * (size_t)n_heads;
+}
+struct AttScratch {
+    float* split_buf;
+    int* split_count;
+    size_t rows;      // capacity of split_buf in query rows x ranges
+    size_t counters;  // capacity of split_count
+};
 // o is written in the tiled layout (it is the output projection's A operand)
 hipError_t attention_configure();  // raises the dynamic-LDS limit (once per process)
 // tree (device pointer, may be null): inside the chunk a query sees the tokens of its row of the table only
-void launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
-                            int layer, hipStream_t s, const TreeTable* tree = nullptr, bool shared_gpu = false);
-// n_branches chunks of n tokens each (rows b*n .. b*n+n-1 of q and o), every one against its own cache
-void launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_model, int n_heads,
-                             const BranchTable* branches, int layer, hipStream_t s);
+hipError_t launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int n_heads, int pos0, const KvView& kv,
+                            int layer, hipStream_t s, AttScratch scratch, const TreeTable* tree = nullptr,
+                            bool shared_gpu = false);
+// n_branches chunks of n tokens each (rows b*n .. b*n+n-1 of q and o), every one against its own cache;
+// max_keys: the longest pos0 + n among the branches
+hipError_t launch_branch_attention(const u16* q, u16* o, int n, int n_branches, int d_model, int n_heads,
+                             const BranchTable* branches, int max_keys, int layer, hipStream_t s, AttScratch scratch);
 
 // ---- packing, rotary table, reduce + norm (bf16_misc.hip) -------------------------------------------
 void launch_pack_qkv(u16* dst, const u16* wq, const u16* wk, const u16* wv, int d, hipStream_t s);
 void launch_pack_gate_up(u16* dst, const u16* wg, const u16* wu, int d, int f, hipStream_t s);
 void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s);
-void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s);
-void launch_rope_table_tree(float2* tab, int n, int pos0, const TreeTable* tree, float theta, hipStream_t s);
-void launch_rope_table_branches(float2* tab, int n_rows, const BranchTable* branches, float theta, hipStream_t s);
+// (the rotary-table kernel is the first of every call; it also clears the call's arrival counters: zero[0 .. n_zero))
+void launch_rope_table(float2* tab, int n, int pos0, float theta, int* zero, int n_zero, hipStream_t s);
+void launch_rope_table_tree(float2* tab, int n, int pos0, const TreeTable* tree, float theta, int* zero, int n_zero,
+                            hipStream_t s);
+void launch_rope_table_branches(float2* tab, int n_rows, const BranchTable* branches, float theta, int* zero, int n_zero,
+                                hipStream_t s);
 void launch_write_branch_table(const BranchTable& host_table, BranchTable* dst, hipStream_t s);
 // x32 <- (hidden_in ? hidden_in : x32) + sum_s partial[s];  xn <- rmsnorm(x32) * g (if g), tiled layout;
 // out <- bf16(x32) (if out), row-major

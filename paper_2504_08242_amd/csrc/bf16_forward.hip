@@ -81,16 +81,22 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
     if (c.n_layers == 0) return hipMemcpyAsync(hidden_out, hidden_in, (size_t)n * d * 2, hipMemcpyDeviceToDevice, s);
     const BranchTable* bt_dev = nullptr;
     const TreeTable* tree_dev = nullptr;
+    // the first kernel of the call builds the rotary table and clears the arrival counters of the call's split launches
+    const AttScratch att{(float*)(ws + st.wl.att_split), (int*)(ws + st.wl.att_count), st.wl.att_split_rows,
+                         st.wl.att_count_n};
+    const int n_zero = (int)att.counters;
+    int max_keys = 0;  // batched branches: the longest key range
     if (bt) {
         bt_dev = (const BranchTable*)(ws + st.wl.branches);
         launch_write_branch_table(*bt, (BranchTable*)(ws + st.wl.branches), s);
-        launch_rope_table_branches(rope, n, bt_dev, c.rope_theta, s);
+        launch_rope_table_branches(rope, n, bt_dev, c.rope_theta, att.split_count, n_zero, s);
+        for (int b = 0; b < bt->n_branches; ++b) max_keys = bt->pos0[b] + bt->n_tok > max_keys ? bt->pos0[b] + bt->n_tok : max_keys;
     } else if (tree) {
         tree_dev = (const TreeTable*)(ws + st.wl.tree);
         launch_write_tree_table(*tree, (TreeTable*)(ws + st.wl.tree), s);
-        launch_rope_table_tree(rope, n, pos, tree_dev, c.rope_theta, s);
+        launch_rope_table_tree(rope, n, pos, tree_dev, c.rope_theta, att.split_count, n_zero, s);
     } else {
-        launch_rope_table(rope, n, pos, c.rope_theta, s);
+        launch_rope_table(rope, n, pos, c.rope_theta, att.split_count, n_zero, s);
     }
 
     const bool shared = link != nullptr;  // other chunks' kernels run beside this chunk's
@@ -126,8 +132,9 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         for (int w = 0; link && w < link->n_wait && e == hipSuccess; ++w) e = hipStreamWaitEvent(s, link->wait_qkv[w][l], 0);
         {
             TraceScope ts(st, JUP_K_ATTENTION, s);
-            if (bt) launch_branch_attention(q, o, bt->n_tok, bt->n_branches, d, H, bt_dev, l, s);
-            else launch_chunk_attention(q, o, n, d, H, pos, kv, l, s, tree_dev, shared);
+            if (e != hipSuccess) break;
+            if (bt) e = launch_branch_attention(q, o, bt->n_tok, bt->n_branches, d, H, bt_dev, max_keys, l, s, att);
+            else e = launch_chunk_attention(q, o, n, d, H, pos, kv, l, s, att, tree_dev, shared);
         }
         {
             TraceScope ts(st, JUP_K_GEMM_O, s);

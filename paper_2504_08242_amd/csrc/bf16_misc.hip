@@ -37,8 +37,15 @@ __global__ void pack_tiled(u16* __restrict__ dst, const u16* __restrict__ s0, co
         *(u32x4*)(dst + tiled_offset(n, ck, k_stages)) = *(const u32x4*)(src + ck * 8);
 }
 
+// The first kernel of a call also clears the arrival counters its later kernels count in (a fill by a kernel, not a
+// memset: the call may be captured in a graph).
+__device__ inline void clear_counters(int* zero, int n_zero) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_zero; i += gridDim.x * blockDim.x) zero[i] = 0;
+}
+
 // tab[t][i] = (cos, sin)((pos0 + t) * theta^(-2i/128)); angles in fp64 so that large positions stay exact.
-__global__ void rope_table(float2* __restrict__ tab, int n, int pos0, float theta) {
+__global__ void rope_table(float2* __restrict__ tab, int n, int pos0, float theta, int* __restrict__ zero, int n_zero) {
+    clear_counters(zero, n_zero);
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= n * 64) return;
     const int i = gid & 63, t = gid >> 6;
@@ -48,7 +55,8 @@ __global__ void rope_table(float2* __restrict__ tab, int n, int pos0, float thet
 
 // Token-tree call: token t sits tree->depth[t] positions behind the cached sequence.
 __global__ void rope_table_tree(float2* __restrict__ tab, int n, int pos0, const TreeTable* __restrict__ tree,
-                                float theta) {
+                                float theta, int* __restrict__ zero, int n_zero) {
+    clear_counters(zero, n_zero);
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= n * 64) return;
     const int i = gid & 63, t = gid >> 6;
@@ -58,7 +66,8 @@ __global__ void rope_table_tree(float2* __restrict__ tab, int n, int pos0, const
 
 // Batched-branch call: row r is token r % n_tok of branch r / n_tok.
 __global__ void rope_table_branches(float2* __restrict__ tab, int n_rows, const BranchTable* __restrict__ bt,
-                                    float theta) {
+                                    float theta, int* __restrict__ zero, int n_zero) {
+    clear_counters(zero, n_zero);
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= n_rows * 64) return;
     const int i = gid & 63, r = gid >> 6;
@@ -156,15 +165,18 @@ void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s)
     hipLaunchKernelGGL(pack_tiled, dim3(n_rows), dim3(256), 0, s, dst, w, (const u16*)nullptr, (const u16*)nullptr, k,
                        0, (int)PACK_PLAIN);
 }
-void launch_rope_table(float2* tab, int n, int pos0, float theta, hipStream_t s) {
-    hipLaunchKernelGGL(rope_table, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, theta);
+void launch_rope_table(float2* tab, int n, int pos0, float theta, int* zero, int n_zero, hipStream_t s) {
+    hipLaunchKernelGGL(rope_table, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, theta, zero, n_zero);
 }
-void launch_rope_table_tree(float2* tab, int n, int pos0, const TreeTable* tree, float theta, hipStream_t s) {
-    hipLaunchKernelGGL(rope_table_tree, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, tree, theta);
+void launch_rope_table_tree(float2* tab, int n, int pos0, const TreeTable* tree, float theta, int* zero, int n_zero,
+                            hipStream_t s) {
+    hipLaunchKernelGGL(rope_table_tree, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, tree, theta, zero,
+                       n_zero);
 }
-void launch_rope_table_branches(float2* tab, int n_rows, const BranchTable* branches, float theta, hipStream_t s) {
+void launch_rope_table_branches(float2* tab, int n_rows, const BranchTable* branches, float theta, int* zero, int n_zero,
+                                hipStream_t s) {
     hipLaunchKernelGGL(rope_table_branches, dim3((n_rows * 64 + 255) / 256), dim3(256), 0, s, tab, n_rows, branches,
-                       theta);
+                       theta, zero, n_zero);
 }
 void launch_write_branch_table(const BranchTable& host_table, BranchTable* dst, hipStream_t s) {
     hipLaunchKernelGGL(write_branch_table, dim3(1), dim3(64), 0, s, host_table, dst);

@@ -7,7 +7,7 @@
 #include <mutex>
 #include <new>
 
-#include "jup_internal.h"
+#include "bf16_common.h"
 
 namespace {
 
@@ -99,7 +99,7 @@ PackedLayout packed_layout(const jup_stage_config_t& c) {
     return p;
 }
 
-WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T) {
+WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T, bool branches) {
     const size_t e = elem_size(c), d = c.d_model, f = c.d_ffn;
     const bool f32 = c.dtype == JUP_F32;
     // the matrix-core path stores GEMM operands in 32-row blocks
@@ -116,6 +116,10 @@ WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T) {
     w.partial = off; off += f32 ? 0 : align_up(8 * t * d * 4);
     w.branches = off; off += f32 ? 0 : align_up(sizeof(BranchTable));
     w.tree = off; off += align_up(sizeof(TreeTable));
+    w.att_split_rows = f32 ? 0 : att_split_rows(T, c.n_heads, branches);
+    w.att_count_n = f32 ? 0 : att_split_counters(T, c.n_heads, branches);
+    w.att_split = off; off += align_up(w.att_split_rows * kAttSplitRow * 4);
+    w.att_count = off; off += align_up(w.att_count_n * 4);
     w.total = off;
     return w;
 }
@@ -612,7 +616,7 @@ jup_status_t jup_stage_prefill_chunk_static(jup_stage_t* stage, const void* hidd
     jup_stage view = *stage;
     view.overlap = nullptr;
     if (n_tokens > 0) {
-        view.wl = jup::workspace_layout(stage->cfg, n_tokens);
+        view.wl = jup::workspace_layout(stage->cfg, n_tokens, false);  // one chunk, no branches
         if (view.wl.total > (size_t)JUP_STATIC_SCRATCH_BYTES)
             return fail(JUP_ECAP, "%s: a chunk of %d tokens of this stage needs %zu bytes of scratch, the static buffer "
                         "holds %d (use jup_stage_prefill_chunk with a caller-provided workspace)", me, n_tokens,

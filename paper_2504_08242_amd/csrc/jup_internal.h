@@ -41,9 +41,14 @@ struct WorkspaceLayout {
     size_t partial;  // bf16 only: [8][T, d] fp32 K-split partial sums of the O / down projections
     size_t branches; // bf16 only: BranchTable of a batched-branch call
     size_t tree;     // TreeTable of a token-tree call
+    // bf16 only: scratch of attention launches that split the keys of a query block over workgroups
+    size_t att_split;      // [att_split_rows][132] fp32: un-normalised outputs and softmax statistics per key range
+    size_t att_count;      // [att_count_n] int32 arrival counters, zero between launches
+    size_t att_split_rows, att_count_n;
     size_t total;
 };
-WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T);
+// branches: the workspace also serves jup_stage_prefill_branches (more query blocks per launch: more scratch)
+WorkspaceLayout workspace_layout(const jup_stage_config_t& c, int32_t T, bool branches = true);
 
 // Where the attention and append kernels find a cache: positions < n_shared live in the parent's
 // buffer (stride parent_cap), the rest in the own buffer at slot (position - n_shared).

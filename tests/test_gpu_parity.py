@@ -507,6 +507,48 @@ def test_bf16_tree_node_equals_the_ordinary_call_on_its_path():
         assert rel_l2(g[t], ref[-1]) <= 1e-2, t   # same values, other tile shapes and summation orders
 
 
+def test_bf16_short_chunks_behind_a_long_cache_split_their_keys_over_workgroups():
+    """Chunks of up to 256 tokens behind 1000+ cached positions: the key tiles of a query block are split over several
+    workgroups and merged by the last one to finish (decoding steps of Sec. V against a long sequence).  Against the
+    oracle row by row, and twice: the merge order is fixed, so the bits must not depend on which workgroup came last."""
+    p = Pair(LLAMA7B_2L, "bf16", seed=15, max_positions=1600, max_chunk_tokens=300)
+    sizes = [5, 1, 37, 64, 100, 200, 31]          # 1-2 query blocks of 32, then 64-query blocks with 2 or 4 key ranges
+    hidden = p.hidden(1100 + sum(sizes) + 26)
+    p.run_both(hidden[:1100], [275] * 4)
+    pos = 1100
+    for n in sizes:
+        h = hidden[pos:pos + n]
+        want = p.oracle.prefill_chunk(h, pos)
+        got = p.gpu_chunk(h, pos)
+        p.check(got, want, f"chunk of {n} at {pos}")
+        bits = kv_bits(p.kv)
+        for rep in range(3):
+            assert np.array_equal(p.gpu_chunk(h, pos), got), (n, rep)      # pos < length: overwrite from there
+            assert np.array_equal(kv_bits(p.kv), bits), (n, rep)
+        pos += n
+    parents = si.make_token_tree(26, 15)
+    h = hidden[pos:pos + 26]
+    got = p.gpu_tree(h, pos, parents)
+    p.check(got, p.oracle.prefill_tree(h, parents, pos), f"tree at {pos}")
+    p.kv.truncate(pos)
+    assert np.array_equal(p.gpu_tree(h, pos, parents), got)
+    kv = p.kv_gpu()[:, :, :, :pos + 26]
+    for l in range(2):
+        p.check(kv[l], p.oracle.kv[l, :, :, :pos + 26], f"cache layer {l}")
+    # a chain-shaped tree is the ordinary chunk, bit for bit, with split keys too
+    p.kv.truncate(pos)
+    a = p.gpu_chunk(h, pos)
+    p.kv.truncate(pos)
+    assert np.array_equal(p.gpu_tree(h, pos, list(range(-1, 25))), a)
+
+
+def test_bf16_batched_branches_with_split_keys_equal_one_call_per_branch_bitwise():
+    """Branches whose caches straddle the length at which a query block gets a second key range: alone or batched, a
+    branch takes the same ranges and merges them in the same order."""
+    p = Pair(LLAMA7B_2L, "bf16", seed=16, max_positions=975, max_chunk_tokens=325, oracle_positions=1100)
+    run_batched_branches_case(p, n_prefix=975, n_privates=[9, 33, 12, 1], n_chunk=5)   # 989, 1013, 992, 981 keys
+
+
 def assert_same_cache_entries(got_bits, want_bits, sentinel_bits):
     """The same entries were written (everything else still holds the sentinel), whatever their values."""
     assert np.array_equal(got_bits == sentinel_bits, want_bits == sentinel_bits)
@@ -756,7 +798,7 @@ def test_bf16_long_prefix_8192_cached_positions():
     cfg = dict(si.LLAMA7B_STAGE, n_layers=1)
     n_prefix = 8192
     p = Pair(cfg, "bf16", seed=60, max_positions=n_prefix + 640, max_chunk_tokens=2048)
-    hidden = p.hidden(n_prefix + 512 + 37 + 26)
+    hidden = p.hidden(n_prefix + 512 + 37 + 1 + 5 + 26)
     o = []
     for s in range(0, n_prefix, 1024):
         o.append(p.oracle.prefill_chunk(hidden[s:s + 1024], s))
@@ -767,10 +809,25 @@ def test_bf16_long_prefix_8192_cached_positions():
     p.check(g, np.concatenate(o), "prefix")
     p.check(g[-2048:], np.concatenate(o)[-2048:], "last prefix chunk")
     pos = n_prefix
-    for n in (512, 37):
+    for n in (512, 37, 1, 5):           # the short ones split their 260+ key tiles over 8 workgroups per query block
         h = hidden[pos:pos + n]
-        p.check(p.gpu_chunk(h, pos), p.oracle.prefill_chunk(h, pos), f"chunk of {n} at {pos}")
+        got = p.gpu_chunk(h, pos)
+        p.check(got, p.oracle.prefill_chunk(h, pos), f"chunk of {n} at {pos}")
+        for rep in range(2):             # the merge order is fixed: same bits whichever workgroup finishes last
+            assert np.array_equal(p.gpu_chunk(h, pos), got), (n, rep)
         pos += n
+    # a branch forked at the end of the prompt (Sec. V-B): its 5-token chunk reads 8192+ shared positions and its own
+    fork = p.kv.fork(pos, pos + 16)
+    h = p.hidden(5 + 5, tag=7)
+    keep = p.oracle.kv.copy()
+    for lo in (0, 5):
+        got = p.gpu_chunk(h[lo:lo + 5], pos + lo, kv=fork)
+        p.check(got, p.oracle.prefill_chunk(h[lo:lo + 5], pos + lo), f"forked branch, chunk at {pos + lo}")
+    assert np.array_equal(p.gpu_chunk(h[5:], pos + 5, kv=fork), got)
+    p.check(to_numpy(fork.view())[0][:, :, :10], p.oracle.kv[0, :, :, pos:pos + 10], "fork cache")
+    fork.destroy()
+    p.oracle.kv[...] = keep
+    p.oracle.kv_len = pos
     parents = si.make_token_tree(26, 60)
     h = hidden[pos:pos + 26]
     p.check(p.gpu_tree(h, pos, parents), p.oracle.prefill_tree(h, parents, pos), f"tree at {pos}")

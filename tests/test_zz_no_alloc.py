@@ -55,20 +55,43 @@ def test_static_scratch_call_equals_the_ordinary_call_twice_in_a_row(dtype, cfg,
     assert np.array_equal(bits(y1), bits(want1))
 
 
+def test_static_scratch_call_behind_a_long_cache_equals_the_ordinary_call():
+    """Key-split attention keeps partial results and arrival counters in the scratch: the static array must serve them
+    as the workspace does, on two calls in a row (the second smaller)."""
+    import torch
+    cfg = dict(si.LLAMA7B_STAGE, n_layers=2)
+    p = Pair(cfg, "bf16", seed=122, max_positions=1200, max_chunk_tokens=300)
+    h = p.hidden(1100 + 48 + 5)
+    x = torch.from_numpy(h).to("cuda:0", p.td)
+    for c in range(4):
+        p.stage.prefill_chunk(x[c * 275:(c + 1) * 275], c * 275, p.kv)
+    want1 = p.stage.prefill_chunk(x[1100:1148], 1100, p.kv)
+    want2 = p.stage.prefill_chunk(x[1148:], 1148, p.kv)
+    torch.cuda.synchronize()
+    want_kv = bits(p.kv.buf)
+    p.kv.truncate(1100)
+    y1, y2 = torch.empty_like(want1), torch.empty_like(want2)
+    p.stage.prefill_chunk_static(x[1100:1148], 1100, p.kv, y1)
+    p.stage.prefill_chunk_static(x[1148:], 1148, p.kv, y2)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(y1), bits(want1)) and np.array_equal(bits(y2), bits(want2))
+    assert np.array_equal(bits(p.kv.buf), want_kv)
+
+
 def test_static_scratch_call_rejects_what_does_not_fit_and_validates_like_the_ordinary_call():
     import torch
     cfg = dict(si.LLAMA7B_STAGE, n_layers=1)
     p = Pair(cfg, "bf16", seed=121, max_positions=400, max_chunk_tokens=16)
-    x = torch.zeros((192, cfg["d_model"]), device="cuda:0", dtype=torch.bfloat16)
+    x = torch.zeros((224, cfg["d_model"]), device="cuda:0", dtype=torch.bfloat16)
     y = torch.empty_like(x)
-    with pytest.raises(jb.JupiterError) as e:                 # 192 tokens of a 7B-shaped stage need more than 32 MiB
+    with pytest.raises(jb.JupiterError) as e:                 # 224 tokens of a 7B-shaped stage need more than 48 MiB
         p.stage.prefill_chunk_static(x, 0, p.kv, y)
     assert e.value.status == jb.JUP_ECAP and "static" in str(e.value) and len(p.kv) == 0
-    p.stage.prefill_chunk_static(x[:160], 0, p.kv, y[:160])   # the largest that fits; above the stage's max_chunk_tokens
-    assert len(p.kv) == 160
+    p.stage.prefill_chunk_static(x[:192], 0, p.kv, y[:192])   # the largest that fits; above the stage's max_chunk_tokens
+    assert len(p.kv) == 192
     with pytest.raises(jb.JupiterError) as e:                 # a hole
-        p.stage.prefill_chunk_static(x[:4], 170, p.kv, y[:4])
-    assert e.value.status == jb.JUP_EPOS and len(p.kv) == 160
-    p.stage.prefill_chunk_static(x[:0], 160, p.kv, y[:0])     # empty chunk: no-op
+        p.stage.prefill_chunk_static(x[:4], 200, p.kv, y[:4])
+    assert e.value.status == jb.JUP_EPOS and len(p.kv) == 192
+    p.stage.prefill_chunk_static(x[:0], 192, p.kv, y[:0])     # empty chunk: no-op
     torch.cuda.synchronize()
-    assert len(p.kv) == 160
+    assert len(p.kv) == 192
