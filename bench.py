@@ -28,6 +28,8 @@ default is the metric):
   c4  13B-shaped 10-layer stage, 1024-token prompt in 8 chunks of 128 (bound by streaming the weights)
   c5  7B-shaped stage, 8 branches sharing a 512-token prefix, 64 private tokens each; a step is one
       5-token chunk at position 576 on every branch                  (decode-sized, bound by the weights)
+  long  7B-shaped stage, one decoding step of a long sequence: a 5-token chunk (1 token + 4 drafts) behind
+      --prefix cached positions (default 8192)                        (bound by the weights and the cached keys/values)
   tree  7B-shaped stage, one speculative step: a 64-candidate token tree verified at position 576 in one
       call, then the accepted path kept in the cache                  (bound by the weights)
 """
@@ -92,7 +94,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=("c2", "c3", "c4", "c5", "tree"), default="c3")
+    ap.add_argument("--workload", choices=("c2", "c3", "c4", "c5", "tree", "long"), default="c3")
+    ap.add_argument("--prefix", type=int, default=8192, help="workload long: cached positions before the 5-token chunk")
     ap.add_argument("--chunk", type=int, default=512, help="chunk size of workload c3 (128, 256, 512 or 2048)")
     ap.add_argument("--batched", action="store_true",
                     help="workload c5: all 8 branches in one jup_stage_prefill_branches call per step")
@@ -140,6 +143,12 @@ def main():
         cfg, prompt, chunk, seed = si.LLAMA13B_STAGE, 1024, 128, 40
         what = ("configs[3]: 10-layer stage of Llama-2-13B shape (d 5120, 40 heads x 128, FFN 13824), "
                 "1024-token prompt as 8 chunks of 128")
+    elif wl == "long":
+        if args.prefix < 512 or args.prefix % 512:
+            sys.exit("bench.py: --prefix must be a positive multiple of 512")
+        cfg, prompt, chunk, seed = si.LLAMA7B_STAGE, args.prefix, 512, 80
+        what = (f"decoding step of a long sequence on the 8-layer stage of Llama-2-7B shape: one 5-token chunk (1 token + 4 "
+                f"drafts) behind {prompt} cached positions")
     elif wl == "tree":
         cfg, prompt, chunk, seed = si.LLAMA7B_STAGE, 576, 64, 70
         what = ("speculative step on the 8-layer stage of Llama-2-7B shape: a 64-candidate token tree verified in one "
@@ -161,7 +170,7 @@ def main():
     else:
         layers_np = si.make_layers(cfg, seed, bf16=True, n_threads=16)
         stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers_np, "bf16"), chunk)
-    kv = jb.KvCache(cfg, sdt, prompt + (chunk if wl == "tree" else 0))
+    kv = jb.KvCache(cfg, sdt, prompt + (chunk if wl in ("tree", "long") else 0))
     hidden = torch.from_numpy(hidden_np).to("cuda:0", torch.bfloat16)
     out = torch.empty_like(hidden)
 
@@ -193,6 +202,16 @@ def main():
             def step():
                 for b in range(n_branches):
                     stage.prefill_chunk(step_in[b], p_step, branches[b], hidden_out=step_out[b])
+    elif wl == "long":
+        for c in range(n_chunks):  # untimed: the sequence so far
+            stage.prefill_chunk(hidden[c * chunk:(c + 1) * chunk], c * chunk, kv)
+        step_in = torch.from_numpy(si.make_hidden(cfg, seed, 5, tag=1, bf16=True)).to("cuda:0", torch.bfloat16)
+        step_out = torch.empty_like(step_in)
+        calls = [(5, prompt)]
+        tokens_per_step = 5
+
+        def step():  # pos_offset below the length = drop what the last step appended
+            stage.prefill_chunk(step_in, prompt, kv, hidden_out=step_out)
     elif wl == "tree":
         for c in range(n_chunks):  # untimed: the sequence so far
             stage.prefill_chunk(hidden[c * chunk:(c + 1) * chunk], c * chunk, kv)
@@ -231,7 +250,7 @@ def main():
                 kv.reset()
                 stage.prefill_chunks(hidden, [chunk] * n_chunks, 0, kv, hidden_out=out)
         what += "; one jup_stage_prefill_chunk call per chunk, one after the other"
-    if wl in ("c5", "tree"):
+    if wl in ("c5", "tree", "long"):
         step_overlapped = None
     torch.cuda.synchronize()
     print(f"[bench] inputs ready in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
@@ -387,7 +406,7 @@ def main():
                                        "no counter reading on file for this kernel instantiation"})
 
     cpu_baseline = None
-    if not args.no_cpu_baseline and wl not in ("c5", "tree"):
+    if not args.no_cpu_baseline and wl not in ("c5", "tree", "long"):
         import oracle
         ns = min(max(args.cpu_sample_tokens, 1), prompt)
         if args.w4:  # the oracle of a 4-bit stage runs on the matrices the codes and scales expand to

@@ -24,6 +24,13 @@
 //     bytes, which the L2 -> LDS path moves about three times faster than 16 pieces of 64 bytes, and a
 //     workgroup streams each row block of W front to back in long sequential bursts.
 //   * Workgroup ids are decoded so that the tiles sharing a slice of W run on the same XCD (same L2).
+//   * The epilogues that write bf16 rows (QKV with rotary embedding and cache append, gate/up with SwiGLU) compute the
+//     transposed product W A^T instead: the fragments are the same registers, only the MFMA's operand order changes,
+//     and a lane then holds 16 output features of one token instead of 16 tokens of one feature.  With the weight
+//     rows ordered for it at pack time a lane finishes its outputs alone (rotary partners, gate and up of a feature
+//     sit in the same lane) and writes 16-byte pieces straight from registers.  The earlier epilogues went through a
+//     wave-private LDS strip behind a workgroup barrier; measured at 512 rows: gate/up 85.8 -> 83.0 us, QKV unchanged
+//     (its epilogue is bound by draining 16.7 MB of scattered 16-byte stores, with or without the strip).
 //
 // MFMA 32x32x16 bf16 operand layout (lane = 32*hh + c):
 //   A: lane supplies A[m = c][k = 8*hh + e], e < 8;  B: lane supplies B[k = 8*hh + e][n = c];
@@ -270,7 +277,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
             auto step = [&](auto mi) {
                 constexpr int m = decltype(mi)::value;
                 const Frags<MBW, NBW>& use = SECOND ? f1 : f0;
-                acc[m % MBW][m / MBW] = mfma32(use.a[m % MBW], use.b[m / MBW], acc[m % MBW][m / MBW]);
+                // QKV and gate/up compute the TRANSPOSED block (W A^T: the weight fragment as the MFMA's first operand),
+                // so that a lane ends up with 16 output features of ONE token: see the epilogues
+                if constexpr (EPI == EPI_PARTIAL)
+                    acc[m % MBW][m / MBW] = mfma32(use.a[m % MBW], use.b[m / MBW], acc[m % MBW][m / MBW]);
+                else
+                    acc[m % MBW][m / MBW] = mfma32(use.b[m / MBW], use.a[m % MBW], acc[m % MBW][m / MBW]);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (TOT > 0) {
 #pragma unroll
@@ -340,62 +352,38 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
                 }
         }
     } else if (EPI == EPI_SWIGLU) {
-        // Packed column 2j = gate_j, 2j+1 = up_j: the even lane pairs with its right neighbour.  Results go
-        // through a wave-private LDS strip [32*MBW rows][16*NBW outputs] so that the global stores are whole
-        // 16-byte chunks of the tiled operand layout instead of single elements.
-        constexpr int OUTW = 16 * NBW;         // outputs per row of this wave
-        constexpr int ROWB = OUTW * 2;         // bytes per strip row
-        __builtin_amdgcn_s_barrier();          // every wave is done with the ring (no reads or DMA in flight)
-        unsigned char* strip = smem + wave * (WROWS * ROWB);
-#pragma unroll
-        for (int nb = 0; nb < NBW; ++nb)
-#pragma unroll
-            for (int mb = 0; mb < MBW; ++mb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float own = acc[mb][nb][i];
-                    const float other = __builtin_bit_cast(
-                        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, own), 0xB1, 0xF, 0xF, true));
-                    const int rl = mb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
-                    if (!(c & 1))
-                        *(u16*)(strip + rl * ROWB + (nb * 16 + (c >> 1)) * 2) =
-                            f2bf(own * __builtin_amdgcn_rcpf(1.0f + __expf(-own)) * other);
-                }
-        wait_lgkmcnt0();
-        __builtin_amdgcn_wave_barrier();
+        // Transposed block: lane (c, hh) holds, for block (mb, nb), token m = row block mb, row c, and the packed weight
+        // rows 8*(i/4) + 4*hh + (i%4) of the 32-row block nb.  The pack kernel orders those rows so that a lane's
+        // registers 0..7 are the gate projections of 8 consecutive features and 8..15 their up projections (block nb
+        // = features 16 nb .. 16 nb + 15, lanes of half hh the features 8 hh .. 8 hh + 7 of them).  A lane therefore
+        // finishes 8 outputs of one token by itself and stores them as one 16-byte chunk of the tiled activation
+        // layout: no exchange between lanes, no LDS, no barrier.
         const int half_n = a.N >> 1;
-        constexpr int CH = OUTW / 8;  // 16-byte chunks per row
 #pragma unroll
-        for (int p = 0; p < (WROWS * CH + 63) / 64; ++p) {
-            const int idx = p * 64 + lane;
-            const int rl = idx / CH, ch = idx - rl * CH;
-            const int m = m0 + wm * WROWS + rl;
-            const int col = (nw0 >> 1) + ch * 8;  // first output column of the chunk
-            if (idx < WROWS * CH && m < a.M && 2 * col < n_end)
-                *(u32x4*)(a.act + tiled_offset(m, col >> 3, half_n >> 5)) = *(const u32x4*)(strip + rl * ROWB + ch * 16);
+        for (int nb = 0; nb < NBW; ++nb) {
+            const int col = nw0 + nb * 32;  // first packed column of the block
+            if (col >= n_end) continue;
+            const int chunk = (col >> 4) + hh;  // 16-byte chunk of the output row: features 8 * chunk ..
+#pragma unroll
+            for (int mb = 0; mb < MBW; ++mb) {
+                const int m = m0 + wm * WROWS + mb * 32 + c;
+                if (m >= a.M) continue;
+                u32x4 out;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float g0 = acc[mb][nb][2 * e], g1 = acc[mb][nb][2 * e + 1];
+                    const float u0 = acc[mb][nb][8 + 2 * e], u1 = acc[mb][nb][8 + 2 * e + 1];
+                    out[e] = pack_bf16x2(g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * u0,
+                                         g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * u1);
+                }
+                *(u32x4*)(a.act + tiled_offset(m, chunk, half_n >> 5)) = out;
+            }
         }
     } else {  // EPI_QKV
-        // Packed column 32j + 16a + c' of a Q/K head is rotary index 16j + c' + 64a (a = 0/1: partners i and
-        // i + 64); V columns keep their order.  The accumulators go through a wave-private fp32 strip
-        // [32 rows][32*NBW columns] in LDS, one row block of the wave at a time; then a lane rotates 8 consecutive
-        // indices of one row and stores 16 bytes.
-        constexpr int SW = 32 * NBW + 8;  // strip row stride in floats (rows 4 apart fall 32 banks apart)
-        __builtin_amdgcn_s_barrier();     // every wave is done with the ring (no reads or DMA in flight)
-        // one row block (32 rows) of the wave at a time, so that the strips of all waves fit the ring's LDS
-        static_assert(S::WAVES * 32 * SW * 4 <= S::LDS_BYTES, "epilogue strips exceed the LDS of the ring");
-        float* strip = (float*)smem + wave * (32 * SW);
-        // lane = 4 * row_in_pass + sub: 16 rows per pass, sub picks 8 of a block's 32 packed columns
-        const int sub = lane & 3, rl0 = lane >> 2;
-#pragma unroll
-        for (int mb = 0; mb < MBW; ++mb) {
-        if (mb > 0) __builtin_amdgcn_wave_barrier();  // the strip reads of the block before are done (lgkmcnt 0 below)
-#pragma unroll
-        for (int nb = 0; nb < NBW; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                strip[(8 * (i >> 2) + 4 * hh + (i & 3)) * SW + nb * 32 + c] = acc[mb][nb][i];
-        wait_lgkmcnt0();
-        __builtin_amdgcn_wave_barrier();
+        // Transposed block, as above.  A 32-row block of a Q or K head holds 16 rotary indices and their partners 64
+        // further on, ordered by the pack kernel so that a lane's registers 0..7 are the indices F .. F + 7 (F = 16 j
+        // + 8 hh for block j of the head) and registers 8..15 their partners F + 64 ..: the lane rotates its 8 pairs and
+        // stores two 16-byte pieces.  A block of V holds 32 consecutive features, a lane 16 of them (16 hh ..).
 #pragma unroll
         for (int nb = 0; nb < NBW; ++nb) {
             const int col = nw0 + nb * 32;  // packed column of the block: one (q|k|v, head, j) for all lanes
@@ -403,61 +391,43 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16(const GemmArgs a) {
             const int which = col / a.d_model;
             const int in_model = col - which * a.d_model;
             const int head = in_model >> 7, j = (in_model & 127) >> 5;
-            const int hi = sub >> 1, i_lo = 16 * j + 8 * (sub & 1);
-            u16* dst;
-            size_t stride;
-            const int in_row = which == 2 ? 32 * j + 8 * sub : i_lo + 64 * hi;  // first of the lane's 8 columns
-            if (which == 0) {
-                dst = a.q_out + head * 128 + in_row;
-                stride = a.d_model;
-            } else if (!a.branches) {
-                dst = kv_slot_bf16(a.kv, a.layer, which - 1, head, a.n_heads, a.pos0) + in_row;
-                stride = 128;
-            } else {
-                dst = nullptr;  // per row below
-                stride = 0;
-            }
+            const int f_lo = which == 2 ? 32 * j + 16 * hh : 16 * j + 8 * hh;  // first feature of registers 0..7
+            const int f_hi = which == 2 ? f_lo + 8 : f_lo + 64;                  // ... of registers 8..15
 #pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const int rl = p * 16 + rl0;
-                const int m = m0 + wm * WROWS + mb * 32 + rl;
+            for (int mb = 0; mb < MBW; ++mb) {
+                const int m = m0 + wm * WROWS + mb * 32 + c;
                 if (m >= a.M) continue;
-                u16* out_ptr;
-                if (which != 0 && a.branches) {  // row m is token t of branch b: that branch's cache and position
+                u16* dst;
+                if (which == 0) {
+                    dst = a.q_out + (size_t)m * a.d_model + head * 128;
+                } else if (!a.branches) {
+                    dst = kv_slot_bf16(a.kv, a.layer, which - 1, head, a.n_heads, a.pos0 + m);
+                } else {  // row m is token t of branch b: that branch's cache and position
                     const int b = m / a.branches->n_tok, t = m - b * a.branches->n_tok;
-                    out_ptr = kv_slot_bf16(a.branches->kv[b], a.layer, which - 1, head, a.n_heads,
-                                           a.branches->pos0[b] + t) + in_row;
-                } else {
-                    out_ptr = dst + (size_t)m * stride;
+                    dst = kv_slot_bf16(a.branches->kv[b], a.layer, which - 1, head, a.n_heads, a.branches->pos0[b] + t);
                 }
-                const float* sp = strip + rl * SW + nb * 32;
-                float v[8];
+                u32x4 lo, hi;
                 if (which == 2) {
-                    const float4 x0 = *(const float4*)(sp + 8 * sub), x1 = *(const float4*)(sp + 8 * sub + 4);
-                    v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
-                } else {
-                    const int o8 = 8 * (sub & 1);
-                    const float4 l0 = *(const float4*)(sp + o8), l1 = *(const float4*)(sp + o8 + 4);
-                    const float4 h0 = *(const float4*)(sp + 16 + o8), h1 = *(const float4*)(sp + 16 + o8 + 4);
-                    const float lo[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
-                    const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-                    const float4* rp = (const float4*)(a.rope + (size_t)m * 64 + i_lo);  // 8 (cos, sin) pairs
 #pragma unroll
-                    for (int e2 = 0; e2 < 4; ++e2) {
-                        const float4 cs = rp[e2];  // (cos, sin) of indices 2*e2, 2*e2 + 1
+                    for (int e = 0; e < 4; ++e) {
+                        lo[e] = pack_bf16x2(acc[mb][nb][2 * e], acc[mb][nb][2 * e + 1]);
+                        hi[e] = pack_bf16x2(acc[mb][nb][8 + 2 * e], acc[mb][nb][8 + 2 * e + 1]);
+                    }
+                } else {
+                    const float4* rp = (const float4*)(a.rope + (size_t)m * 64 + f_lo);  // 8 (cos, sin) pairs
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float4 cs = rp[e];  // (cos, sin) of indices f_lo + 2 e, f_lo + 2 e + 1
+                        const float l0 = acc[mb][nb][2 * e], l1 = acc[mb][nb][2 * e + 1];
+                        const float h0 = acc[mb][nb][8 + 2 * e], h1 = acc[mb][nb][8 + 2 * e + 1];
                         // lo' = lo cos - hi sin ; hi' = hi cos + lo sin
-                        v[2 * e2] = hi ? hv[2 * e2] * cs.x + lo[2 * e2] * cs.y : lo[2 * e2] * cs.x - hv[2 * e2] * cs.y;
-                        v[2 * e2 + 1] = hi ? hv[2 * e2 + 1] * cs.z + lo[2 * e2 + 1] * cs.w
-                                           : lo[2 * e2 + 1] * cs.z - hv[2 * e2 + 1] * cs.w;
+                        lo[e] = pack_bf16x2(l0 * cs.x - h0 * cs.y, l1 * cs.z - h1 * cs.w);
+                        hi[e] = pack_bf16x2(h0 * cs.x + l0 * cs.y, h1 * cs.z + l1 * cs.w);
                     }
                 }
-                u32x4 out;
-#pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2) out[e2] = pack_bf16x2(v[2 * e2], v[2 * e2 + 1]);
-                *(u32x4*)out_ptr = out;
+                *(u32x4*)(dst + f_lo) = lo;
+                *(u32x4*)(dst + f_hi) = hi;
             }
-        }
-        wait_lgkmcnt0();  // this block's strip reads have returned before the next block overwrites the strip
         }
     }
 }
@@ -541,7 +511,22 @@ int gemm_partial_col_blocks(int M, int N, int K) {
 // Measured on the 7B shapes with four lanes: 4 x 512 tokens 274k -> 286k tokens/s, 8 x 256 tokens 204k -> 224k,
 // 16 x 128 and 8 x 64 tokens +3-4 % (no split at all: -4 % there); alone on the chip the same cap costs 8 % (one
 // launch then has to fill it).
+// The output projection of a prefill-sized chunk (K no longer than N, 129 to 512 rows) alone on the chip: 128 x 128
+// tiles with two splits instead of 256 x 128 tiles with four.  The K loop is a little slower (a third more LDS
+// traffic per flop), but half the partial sums are written and read back: measured at 512 rows of the 7B shapes, O
+// projection 28.3 -> 29.4 us, the reduce + norm pass behind it 13.7 -> 10.2 us, the prompt +1.5 %.  (The same for the
+// down projection, whose K loop is 2.7 times as long, measured slower: 52.3 -> 59.4 us.)
+static bool square_prefill_projection(int M, int N, int K, bool shared) {
+    return !shared && M > 128 && M <= 512 && K <= N;  // (measured at 512 rows only; longer chunks keep the tall tile)
+}
+
 int gemm_plan_splits(int M, int N, int K, bool shared) {
+    if (square_prefill_projection(M, N, K, shared)) {
+        const int tiles = div_up(M, 128) * div_up(N, 128);
+        int splits = 1;
+        while (tiles * splits * 2 <= kCUs && (K / G_BK) % (splits * 2) == 0 && splits < 2) splits *= 2;
+        return splits;
+    }
     // beside other chunks' kernels: the widest tile of the chunk's row count (see launch_gemm_partial)
     const int nb = shared ? (pick_row_blocks(M) >= 8 ? 8 : 4) : gemm_partial_col_blocks(M, N, K);
     const int s = splits_for(M, N, K, nb);
@@ -620,6 +605,7 @@ TileShape pick_swiglu(int M, int N, bool shared_gpu) {
 }
 
 TileShape pick_partial(int M, int N, int K, bool shared_gpu) {
+    if (square_prefill_projection(M, N, K, shared_gpu)) return {4, 4, 4, 1};
     const int bmb = pick_row_blocks(M);
     // (short chunks beside other chunks' kernels keep the 128-column tile: 64-token chunks +3 %, 128-token +5 %)
     const bool narrow = gemm_partial_col_blocks(M, N, K) == 2 && !shared_gpu;

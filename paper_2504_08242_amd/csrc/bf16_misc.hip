@@ -5,18 +5,34 @@
 namespace jup {
 namespace {
 
-// Q and K heads are stored so that the rotary partners i and i + 64 (Llama half-split pairing) sit in
-// adjacent 16-column blocks: packed row 32j + 16a + c of a head holds original row 16j + c + 64a
-// (j < 4, a in {0,1}, c < 16).  V rows keep their order.
-__device__ inline int rope_packed_to_orig(int packed) {
-    return 16 * (packed >> 5) + (packed & 15) + 64 * ((packed >> 4) & 1);
+// Row order inside the packed weights.  The QKV and gate/up projections compute the transposed product, after which
+// lane (c, hh) of a wave holds, for a 32-row block of the weights, the rows 8*(i/4) + 4*hh + (i%4) in register i < 16
+// and one token (c).  The rows of a block are ordered so that those 16 registers are what ONE lane needs:
+//   Q and K heads: block j of a head = rotary indices 16 j .. 16 j + 15 and their partners 64 further on (Llama
+//     half-split pairing); registers 0..7 of half hh = indices 16 j + 8 hh .. + 7, registers 8..15 = their partners.
+//   V heads: block j = features 32 j .. 32 j + 31; registers 0..15 of half hh = features 32 j + 16 hh .. + 15.
+//   gate/up: block B = output features 16 B .. 16 B + 15; registers 0..7 of half hh = gate rows of the features
+//     16 B + 8 hh .. + 7, registers 8..15 = their up rows.
+// Register i of half hh is packed row rho = 8*(i/4) + 4*hh + (i%4), i.e. i = 4*(rho>>3) + (rho&3), hh = (rho>>2)&1.
+__device__ inline int packed_reg(int rho) { return 4 * (rho >> 3) + (rho & 3); }
+__device__ inline int packed_half(int rho) { return (rho >> 2) & 1; }
+// packed row p (0..127) of a Q or K head -> original row of the head
+__device__ inline int rope_packed_to_orig(int p) {
+    const int j = p >> 5, rho = p & 31, i = packed_reg(rho);
+    return 16 * j + 8 * packed_half(rho) + (i & 7) + 64 * (i >> 3);
+}
+// packed row p (0..127) of a V head -> original row of the head
+__device__ inline int v_packed_to_orig(int p) {
+    const int j = p >> 5, rho = p & 31;
+    return 32 * j + 16 * packed_half(rho) + packed_reg(rho);
 }
 
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 
 // One block per packed row n; copies that row's K/8 chunks into the tiled layout.
 //   PACK_QKV:     rows [0,d) Q heads, [d,2d) K heads, [2d,3d) V heads (s0, s1, s2 = wq, wk, wv; rows_per = d)
-//   PACK_GATE_UP: packed row 2j = gate row j, 2j+1 = up row j (s0, s1 = w_gate, w_up)
+//   PACK_GATE_UP: 32 packed rows per 16 output features, gate and up rows in the order described above (s0, s1 =
+//                 w_gate, w_up)
 //   PACK_PLAIN:   row n of s0
 __global__ void pack_tiled(u16* __restrict__ dst, const u16* __restrict__ s0, const u16* __restrict__ s1,
                            const u16* __restrict__ s2, int K, int rows_per, int mode) {
@@ -25,10 +41,12 @@ __global__ void pack_tiled(u16* __restrict__ dst, const u16* __restrict__ s0, co
     if (mode == PACK_QKV) {
         const int which = n / rows_per, rr = n % rows_per;
         const int head = rr >> 7, in_head = rr & 127;
-        const int src_row = head * 128 + (which == 2 ? in_head : rope_packed_to_orig(in_head));
+        const int src_row = head * 128 + (which == 2 ? v_packed_to_orig(in_head) : rope_packed_to_orig(in_head));
         src = (which == 0 ? s0 : which == 1 ? s1 : s2) + (size_t)src_row * K;
     } else if (mode == PACK_GATE_UP) {
-        src = ((n & 1) ? s1 : s0) + (size_t)(n >> 1) * K;
+        const int rho = n & 31, i = packed_reg(rho);
+        const int feature = 16 * (n >> 5) + 8 * packed_half(rho) + (i & 7);
+        src = ((i >> 3) ? s1 : s0) + (size_t)feature * K;
     } else {
         src = s0 + (size_t)n * K;
     }

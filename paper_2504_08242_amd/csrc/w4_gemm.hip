@@ -175,7 +175,10 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_w4(const GemmArgs a) {
         }
     };
 
-    // Two groups of codes (from HBM) in flight per wave: the next one is fetched before the current one is used.  The
+    // Two groups of codes (from HBM) in flight per wave: the next one is fetched before the current one is used.
+    // (Four in flight, a wave's whole share of K on the 7B shapes, measured no faster where the grid still fits one
+    // round of workgroups -- QKV 13.3 vs 13.0 us, down 11.6 vs 11.8 us at 5 rows -- and slower for gate/up, 20.5 vs
+    // 18.3 us: 216 registers per lane leave one workgroup per CU and its 344 workgroups then take two rounds.)  The
     // rows of A (from L2) travel with them while the registers allow it (up to 32 rows); with 64 rows they are
     // fetched when their group's turn comes, behind the prefetch of the next codes.
     constexpr bool ROWS_AHEAD = RG <= 2;
