@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--no-overlap", action="store_true",
                     help="skip the `overlapped` leg (one jup_stage_prefill_chunks call whose consecutive chunks overlap "
                          "on several streams); profiling runs use this, so that every kernel's duration is its own")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="also time torch.matmul (the vendor GEMM library, no fused epilogue) on the four projection "
+                         "shapes of the workload's chunk and report it as `vendor_gemm`: context for the per-kernel times")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="also run a bare MFMA loop on random operands for about 150 ms and report what it sustains "
                          "(TFLOP/s, the shader clock it held) as `mfma_calibration`")
@@ -314,6 +317,27 @@ def main():
                             "clock_mhz_min": round(float(100.0 * (t[:, 0] / t[:, 1]).min()), 1)}
         del ops
 
+    vendor_gemm = None
+    if args.vendor_gemm:
+        d_, f_, m_ = cfg["d_model"], cfg["d_ffn"], calls[0][0]
+        vendor_gemm = {"what": "torch.matmul (vendor library) on bf16 random operands, plain product without any epilogue, "
+                               "average of 50 back-to-back launches between two events", "rows": m_}
+        for name, nn, kk in (("gemm_qkv", 3 * d_, d_), ("gemm_o", d_, d_), ("gemm_gate_up", 2 * f_, d_), ("gemm_down", d_, f_)):
+            xa = torch.randn(m_, kk, device="cuda:0").to(torch.bfloat16)
+            xw = (torch.randn(nn, kk, device="cuda:0") * 0.02).to(torch.bfloat16)
+            for _ in range(5):
+                xc = xa @ xw.t()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            torch.cuda.synchronize()
+            ev[0].record()
+            for _ in range(50):
+                xc = xa @ xw.t()
+            ev[1].record()
+            torch.cuda.synchronize()
+            us = ev[0].elapsed_time(ev[1]) / 50 * 1e3
+            vendor_gemm[name] = {"us": round(us, 2), "tflops": round(2.0 * m_ * nn * kk / us / 1e6, 1)}
+            del xa, xw, xc
+
     elapsed, clock_mhz = timed(step, probe=True)
     out_timed = out.clone() if wl in ("c2", "c3", "c4") else None  # what the timed steps wrote (the passes below reuse out)
     ms_per_step = elapsed / args.steps * 1e3
@@ -448,6 +472,7 @@ def main():
         "per_call": per_call,
         "overlapped": overlapped,
         "mfma_calibration": mfma_calibration,
+        "vendor_gemm": vendor_gemm,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in per_kernel.items()},

@@ -119,8 +119,15 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
     const int branch = bq / q_blocks;  // 0 without a branch table
     const int q0 = (q_blocks - 1 - bq % q_blocks) * (NQ * 32);
     const int row0 = branch * n;
-    const int pos0 = branches ? branches->pos0[branch] : pos0_arg;
-    const KvView kv = branches ? branches->kv[branch] : kv_arg;
+    // (the same for every lane; read out of the vector registers a table load leaves them in, which the tile loop
+    // cannot spare)
+    const int pos0 = __builtin_amdgcn_readfirstlane(branches ? branches->pos0[branch] : pos0_arg);
+    KvView kv = branches ? branches->kv[branch] : kv_arg;
+    kv.own = (void*)uniform_ptr((const char*)kv.own);
+    kv.parent = (const void*)uniform_ptr((const char*)kv.parent);
+    kv.n_shared = __builtin_amdgcn_readfirstlane(kv.n_shared);
+    kv.own_cap = __builtin_amdgcn_readfirstlane(kv.own_cap);
+    kv.parent_cap = __builtin_amdgcn_readfirstlane(kv.parent_cap);
     q += (size_t)row0 * d_model;
     const int q_last = min(q0 + NQ * 32, n) - 1;  // last real query of this workgroup
     const int n_keys = pos0 + q_last + 1;
@@ -316,44 +323,50 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
     constexpr int QR = 32 * NQ;                             // query rows of the workgroup
     constexpr int kRegion = QR * kORow;                     // floats per key partition: [QR queries][132]
     static_assert(KP * kRegion * 4 <= kStatOffset, "merge regions overlap the statistics");
+    // The lane indices of the merge are derived afresh from a copy of the thread id that the compiler cannot see through:
+    // nothing the merge needs is then computed (and kept in registers) before the tile loop, whose register budget
+    // is exhausted (one value too many there spills a Q fragment, reloaded in every round).
+    int tid_m = tid;
+    asm volatile("" : "+v"(tid_m));
+    const int c_m = tid_m & 31, hh_m = (tid_m >> 5) & 1;
     float* obuf = (float*)lds;
     float* stat_m = (float*)(lds + kStatOffset);            // [KP][QR]
     float* stat_l = stat_m + KP * QR;
     {
         const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-        if (hh == 0) {
-            stat_m[g * QR + qb * 32 + c] = m_run;
-            stat_l[g * QR + qb * 32 + c] = l_tot;
+        if (hh_m == 0) {
+            stat_m[g * QR + qb * 32 + c_m] = m_run;
+            stat_l[g * QR + qb * 32 + c_m] = l_tot;
         }
     }
     __syncthreads();  // statistics visible; every wave is done with the tile slots
     {
         float m_all = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < KP; ++w) m_all = fmaxf(m_all, stat_m[w * QR + qb * 32 + c]);
+        for (int w = 0; w < KP; ++w) m_all = fmaxf(m_all, stat_m[w * QR + qb * 32 + c_m]);
         float l_all = 0.f;
 #pragma unroll
         for (int w = 0; w < KP; ++w) {
-            const float mw = stat_m[w * QR + qb * 32 + c];
-            l_all += mw == -INFINITY ? 0.f : stat_l[w * QR + qb * 32 + c] * exp2f(mw - m_all);
+            const float mw = stat_m[w * QR + qb * 32 + c_m];
+            l_all += mw == -INFINITY ? 0.f : stat_l[w * QR + qb * 32 + c_m] * exp2f(mw - m_all);
         }
         // one workgroup for all keys: normalised here; key splits: left un-normalised for the merge across workgroups
         const float wscale = m_run == -INFINITY ? 0.f : exp2f(m_run - m_all) / (n_splits > 1 ? 1.0f : l_all);
-        float* mine = obuf + g * kRegion + (qb * 32 + c) * kORow;
+        float* mine = obuf + g * kRegion + (qb * 32 + c_m) * kORow;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int gg = 0; gg < 4; ++gg)
-                *(float4*)(mine + db * 32 + 8 * gg + 4 * hh) =
+                *(float4*)(mine + db * 32 + 8 * gg + 4 * hh_m) =
                     make_float4(oacc[db][4 * gg] * wscale, oacc[db][4 * gg + 1] * wscale,
                                 oacc[db][4 * gg + 2] * wscale, oacc[db][4 * gg + 3] * wscale);
-        if (n_splits > 1 && g == 0 && hh == 0) {  // statistics of this key range, one pair per query row
-            store_coherent2(split_buf + ((size_t)(blockIdx.x * gridDim.y + ks) * QR + qb * 32 + c) * kAttSplitRow + 128,
+        if (n_splits > 1 && g == 0 && hh_m == 0) {  // statistics of this key range, one pair per query row
+            store_coherent2(split_buf + ((size_t)(blockIdx.x * gridDim.y + ks) * QR + qb * 32 + c_m) * kAttSplitRow + 128,
                             m_all, l_all);
         }
     }
     __syncthreads();
-    for (int idx = tid; idx < QR * 16; idx += 64 * KP * NQ) {  // the computing threads (tid < 64 KP NQ)
+    for (int idx = tid_m; idx < QR * 16; idx += 64 * KP * NQ) {  // the computing threads (tid < 64 KP NQ)
         const int qr = idx >> 4, ch = idx & 15;
         const int qrow = q0 + qr;
         if (qrow >= n) continue;
@@ -386,7 +399,7 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
     wait_stores_performed();
     __syncthreads();
     int* flag = (int*)(lds + kStatOffset);  // (the statistics in LDS are no longer needed)
-    if (tid == 0) {
+    if (tid_m == 0) {
         const int before = arrive_coherent(split_count + blockIdx.x);
         *flag = before == n_splits - 1;
         if (before == n_splits - 1) split_count[blockIdx.x] = 0;  // ready for the next launch on this stream
@@ -394,7 +407,7 @@ __global__ __launch_bounds__(64 * KP * (NQ + LPQ)) void chunk_attention_bf16(con
     __syncthreads();
     if (!*flag) return;
     const float* base = split_buf + (size_t)blockIdx.x * gridDim.y * QR * kAttSplitRow;
-    for (int idx = tid; idx < QR * 16; idx += 64 * KP * NQ) {
+    for (int idx = tid_m; idx < QR * 16; idx += 64 * KP * NQ) {
         const int qr = idx >> 4, ch = idx & 15;
         const int qrow = q0 + qr;
         if (qrow >= n) continue;
