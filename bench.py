@@ -101,8 +101,11 @@ def main():
                     help="workload c5: all 8 branches in one jup_stage_prefill_branches call per step")
     ap.add_argument("--w4", action="store_true",
                     help="the stage holds its projection matrices as 4-bit codes with group-wise scales (dtype "
-                         "JUP_BF16_W4), the precision the paper runs its models in; its kernels are built for the "
-                         "decode-sized workloads c5 and tree (prefill-sized chunks run, 64 rows per pass)")
+                         "JUP_BF16_W4), the precision the paper runs its models in.  Calls of up to 64 rows (workloads "
+                         "c5, tree, long) stream the codes; a stage made for longer chunks also keeps a bf16 copy of "
+                         "the matrices (jup_stage_config_t.w4_expanded) and runs the bf16 kernels on it")
+    ap.add_argument("--w4-codes-only", action="store_true",
+                    help="with --w4: no bf16 copy, chunks of more than 64 rows take one pass over the codes per 64 rows")
     ap.add_argument("--no-overlap", action="store_true",
                     help="skip the `overlapped` leg (one jup_stage_prefill_chunks call whose consecutive chunks overlap "
                          "on several streams); profiling runs use this, so that every kernel's duration is its own")
@@ -162,14 +165,19 @@ def main():
                 "private tokens each; a step = one 5-token chunk at position 576 on every branch")
     n_chunks = prompt // chunk
     sdt = "w4" if args.w4 else "bf16"
-    wbytes = W4_BYTES_PER_WEIGHT if args.w4 else 2.0
+    # rows of the longest call of the workload decide which copy of the weights a 4-bit stage reads
+    w4_expanded = args.w4 and not args.w4_codes_only and wl in ("c2", "c3", "c4") and chunk > 64
+    wbytes = W4_BYTES_PER_WEIGHT if args.w4 and not w4_expanded else 2.0
 
     t0 = time.time()
     hidden_np = si.make_hidden(cfg, seed, prompt, bf16=True)
     if args.w4:
         what += "; projection matrices as 4-bit codes with one fp32 scale per 128 weights"
+        if w4_expanded:
+            what += (", plus their bf16 expansion (2 more bytes per weight resident), which the bf16 kernels read for "
+                     "these chunks of more than 64 rows")
         layers_w4 = si.make_w4_layers(cfg, seed, n_threads=16)
-        stage = jb.Stage(cfg, "w4", jb.upload_w4_layers(layers_w4), chunk)
+        stage = jb.Stage(cfg, "w4", jb.upload_w4_layers(layers_w4), chunk, w4_expanded=w4_expanded)
     else:
         layers_np = si.make_layers(cfg, seed, bf16=True, n_threads=16)
         stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers_np, "bf16"), chunk)
@@ -244,7 +252,7 @@ def main():
 
         step = step_sequential
         step_overlapped = None
-        if not args.no_overlap and n_chunks >= 2 and not args.w4:
+        if not args.no_overlap and n_chunks >= 2 and not (args.w4 and not w4_expanded):
             stage.enable_overlap(args.lanes)
             # the library's lane rule (jup_stage_prefill_chunks)
             lanes_used = min(2 if chunk > 256 and n_chunks % 4 else args.lanes, n_chunks)
@@ -408,8 +416,9 @@ def main():
     d, f = cfg["d_model"], cfg["d_ffn"]
     dom_flops = 2.0 * n_call * (2 * f) * d  # one launch: [n, d] x [2f, d]^T
     dom_bytes = wbytes * 2 * f * d + 2.0 * (n_call * d + n_call * f)  # weights + activations in + activations out
-    dom_name = "gemm_w4<gate_up+swiglu>" if args.w4 else stage.kernel_name(jb.KERNEL_IDS["gemm_gate_up"], n_call)
-    traffic = None if args.w4 else read_traffic(TRAFFIC_TABLE, wl, chunk, dom_name)
+    codes = args.w4 and not w4_expanded  # the projections are the 4-bit kernels
+    dom_name = "gemm_w4<gate_up+swiglu>" if codes else stage.kernel_name(jb.KERNEL_IDS["gemm_gate_up"], n_call)
+    traffic = None if codes else read_traffic(TRAFFIC_TABLE, wl, chunk, dom_name)
     dom_s = dom["avg_us"] * 1e-6
     # which roof the dominant kernel sits under: the ridge of the chip is peak flop/s over peak byte/s
     if dom_flops / dom_bytes >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):

@@ -97,6 +97,14 @@ typedef struct {
     float rms_eps;    /* inside the square root: x / sqrt(mean(x^2) + eps) */
     float rope_theta; /* rotary base, 1e4 for Llama-2 */
     int32_t dtype;    /* jup_dtype_t */
+    /*
+     * JUP_BF16_W4 only (must be 0 otherwise): 1 = the stage also keeps bf16(scale * (code - 8)) of its seven
+     * matrices, 2 more bytes per weight in `packed`.  Chunks of more than 64 rows then run the bf16 kernels on that
+     * copy (they are bound by arithmetic, where 4-bit weights save nothing) and shorter ones stream the codes (they
+     * are bound by reading the weights, Sec. V); with 0 the stage holds codes only and a longer chunk takes one pass
+     * over the codes per 64 rows.  The expanded weights carry one more rounding to bf16 than the codes.
+     */
+    int32_t w4_expanded;
 } jup_stage_config_t;
 
 /*

@@ -20,7 +20,7 @@ WEIGHT_NAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g
 class StageConfig(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("d_model", ctypes.c_int32), ("n_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("d_ffn", ctypes.c_int32), ("rms_eps", ctypes.c_float),
-                ("rope_theta", ctypes.c_float), ("dtype", ctypes.c_int32)]
+                ("rope_theta", ctypes.c_float), ("dtype", ctypes.c_int32), ("w4_expanded", ctypes.c_int32)]
 
 
 MATRIX_NAMES = WEIGHT_NAMES[:7]
@@ -98,11 +98,12 @@ def _check(status):
         raise JupiterError(status, last_error())
 
 
-def make_config(cfg, dtype):
+def make_config(cfg, dtype, w4_expanded=False):
     """cfg: dict with n_layers, d_model, n_heads, head_dim, d_ffn, rms_eps, rope_theta; dtype: 'f32' | 'bf16' |
-    'w4' (bf16 activations and cache, 4-bit projection matrices)."""
+    'w4' (bf16 activations and cache, 4-bit projection matrices); w4_expanded: jup_stage_config_t.w4_expanded."""
     return StageConfig(cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ffn"],
-                       cfg["rms_eps"], cfg["rope_theta"], {"f32": JUP_F32, "bf16": JUP_BF16, "w4": JUP_BF16_W4}[dtype])
+                       cfg["rms_eps"], cfg["rope_theta"], {"f32": JUP_F32, "bf16": JUP_BF16, "w4": JUP_BF16_W4}[dtype],
+                       int(bool(w4_expanded)))
 
 
 def _torch_dtype(dtype):
@@ -187,14 +188,15 @@ class KvCache:
 class Stage:
     """jup_stage_t plus the torch tensors that back its packed weights and workspace."""
 
-    def __init__(self, cfg, dtype, layers, max_chunk_tokens, device="cuda:0", stream=None):
+    def __init__(self, cfg, dtype, layers, max_chunk_tokens, device="cuda:0", stream=None, w4_expanded=False):
         """layers: list of dicts keyed by WEIGHT_NAMES holding torch tensors of the stage dtype on `device`; for
         dtype 'w4' the seven matrices are uint8 code pairs and every matrix ``name`` comes with an fp32
-        ``name + '_scale'`` (see upload_w4_layers)."""
+        ``name + '_scale'`` (see upload_w4_layers).  w4_expanded: a 'w4' stage also keeps a bf16 copy of its matrices
+        for chunks of more than 64 rows (jup_stage_config_t.w4_expanded)."""
         import torch
         self.cfg, self.dtype, self.max_chunk_tokens = dict(cfg), dtype, int(max_chunk_tokens)
         L = lib()
-        ccfg = make_config(cfg, dtype)
+        ccfg = make_config(cfg, dtype, w4_expanded)
         pb = L.jup_stage_packed_bytes(ctypes.byref(ccfg))
         wb = L.jup_stage_workspace_bytes(ctypes.byref(ccfg), self.max_chunk_tokens)
         if pb == 0 or wb == 0:

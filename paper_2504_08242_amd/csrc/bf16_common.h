@@ -204,6 +204,12 @@ hipError_t launch_branch_attention(const u16* q, u16* o, int n, int n_branches, 
 void launch_pack_qkv(u16* dst, const u16* wq, const u16* wk, const u16* wv, int d, hipStream_t s);
 void launch_pack_gate_up(u16* dst, const u16* wg, const u16* wu, int d, int f, hipStream_t s);
 void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s);
+// the same layouts filled with bf16(scale * (code - 8)) of 4-bit matrices
+void launch_expand_qkv(u16* dst, const void* cq, const void* ck, const void* cv, const float* sq, const float* sk,
+                       const float* sv, int d, hipStream_t s);
+void launch_expand_gate_up(u16* dst, const void* cg, const void* cu, const float* sg, const float* su, int d, int f,
+                           hipStream_t s);
+void launch_expand_plain(u16* dst, const void* c, const float* sc, int n_rows, int k, hipStream_t s);
 // (the rotary-table kernel is the first of every call; it also clears the call's arrival counters: zero[0 .. n_zero))
 void launch_rope_table(float2* tab, int n, int pos0, float theta, int* zero, int n_zero, hipStream_t s);
 void launch_rope_table_tree(float2* tab, int n, int pos0, const TreeTable* tree, float theta, int* zero, int n_zero,

@@ -32,10 +32,12 @@ hipError_t bf16_pack_weights(const jup_stage& st, const jup_layer_weights_t* lay
 }
 
 // 4-bit stage: codes and scales of the seven matrices go into their packed layouts (w4_gemm.hip); gains as above.
+// A stage created with w4_expanded also gets their bf16 values in the layouts of the bf16 stage.
 hipError_t w4_pack_weights(const jup_stage& st, const jup_layer_weights_t* layers, hipStream_t s) {
     const jup_stage_config_t& c = st.cfg;
     const size_t d = c.d_model;
     hipError_t e = attention_configure();
+    if (e == hipSuccess && c.w4_expanded) e = gemm_configure();
     if (e != hipSuccess) return e;
     for (int l = 0; l < c.n_layers; ++l) {
         char* base = (char*)st.packed + (size_t)l * st.pl.layer_bytes;
@@ -48,6 +50,12 @@ hipError_t w4_pack_weights(const jup_stage& st, const jup_layer_weights_t* layer
                              c.d_model, s);
         launch_pack_w4_plain((unsigned char*)(base + st.pl.wdown), (float*)(base + st.pl.sdown), w.w_down, w.s_down,
                              c.d_model, c.d_ffn, s);
+        if (c.w4_expanded) {
+            launch_expand_qkv((u16*)(base + st.pl.xqkv), w.wq, w.wk, w.wv, w.sq, w.sk, w.sv, c.d_model, s);
+            launch_expand_gate_up((u16*)(base + st.pl.xgu), w.w_gate, w.w_up, w.s_gate, w.s_up, c.d_model, c.d_ffn, s);
+            launch_expand_plain((u16*)(base + st.pl.xo), w.wo, w.so, c.d_model, c.d_model, s);
+            launch_expand_plain((u16*)(base + st.pl.xdown), w.w_down, w.s_down, c.d_model, c.d_ffn, s);
+        }
         e = hipMemcpyAsync(base + st.pl.g_attn, w.g_attn, d * 2, hipMemcpyDeviceToDevice, s);
         if (e == hipSuccess) e = hipMemcpyAsync(base + st.pl.g_mlp, w.g_mlp, d * 2, hipMemcpyDeviceToDevice, s);
         if (e != hipSuccess) return e;
@@ -100,7 +108,12 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
     }
 
     const bool shared = link != nullptr;  // other chunks' kernels run beside this chunk's
-    const bool w4 = c.dtype == JUP_BF16_W4;  // the projections read 4-bit codes; everything else is the bf16 path
+    // 4-bit stage: the projections read codes, everything else is the bf16 path.  With the expanded copy at hand,
+    // chunks beyond one pass of the 4-bit kernels (64 rows) take the bf16 projections on it.
+    const bool expanded = c.dtype == JUP_BF16_W4 && c.w4_expanded && n > 64;
+    const bool w4 = c.dtype == JUP_BF16_W4 && !expanded;
+    const size_t wqkv = expanded ? st.pl.xqkv : st.pl.wqkv, wo = expanded ? st.pl.xo : st.pl.wo;
+    const size_t wgu = expanded ? st.pl.xgu : st.pl.wgu, wdown = expanded ? st.pl.xdown : st.pl.wdown;
     const int splits_o = w4 ? w4_plan_splits(d, d) : gemm_plan_splits(n, d, d, shared);
     const int splits_down = w4 ? w4_plan_splits(d, f) : gemm_plan_splits(n, d, f, shared);
     hipError_t e = hipSuccess;
@@ -119,7 +132,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         {
             TraceScope ts(st, JUP_K_GEMM_QKV, s);
             GemmArgs a{};
-            a.A = xn; a.W = (const u16*)(wb + st.pl.wqkv); a.M = n; a.N = 3 * d; a.K = d;
+            a.A = xn; a.W = (const u16*)(wb + wqkv); a.M = n; a.N = 3 * d; a.K = d;
             a.q_out = q; a.rope = rope; a.kv = kv; a.layer = l; a.n_heads = H; a.d_model = d; a.pos0 = pos;
             a.branches = bt_dev;
             a.shared_gpu = shared;
@@ -139,7 +152,7 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         {
             TraceScope ts(st, JUP_K_GEMM_O, s);
             GemmArgs a{};
-            a.A = o; a.W = (const u16*)(wb + st.pl.wo); a.M = n; a.N = d; a.K = d; a.partial = partial; a.shared_gpu = shared;
+            a.A = o; a.W = (const u16*)(wb + wo); a.M = n; a.N = d; a.K = d; a.partial = partial; a.shared_gpu = shared;
             a.w_scale = (const float*)(wb + st.pl.so);
             if (e == hipSuccess) e = w4 ? launch_gemm_w4(EPI_PARTIAL, a, s) : launch_gemm_partial(a, s);
         }
@@ -150,14 +163,14 @@ hipError_t bf16_forward(const jup_stage& st, const void* hidden_in, int n, int p
         {
             TraceScope ts(st, JUP_K_GEMM_GATE_UP, s);
             GemmArgs a{};
-            a.A = xn; a.W = (const u16*)(wb + st.pl.wgu); a.M = n; a.N = 2 * f; a.K = d; a.act = act; a.shared_gpu = shared;
+            a.A = xn; a.W = (const u16*)(wb + wgu); a.M = n; a.N = 2 * f; a.K = d; a.act = act; a.shared_gpu = shared;
             a.w_scale = (const float*)(wb + st.pl.sgu);
             if (e == hipSuccess) e = w4 ? launch_gemm_w4(EPI_SWIGLU, a, s) : launch_gemm_swiglu(a, s);
         }
         {
             TraceScope ts(st, JUP_K_GEMM_DOWN, s);
             GemmArgs a{};
-            a.A = act; a.W = (const u16*)(wb + st.pl.wdown); a.M = n; a.N = d; a.K = f; a.partial = partial; a.shared_gpu = shared;
+            a.A = act; a.W = (const u16*)(wb + wdown); a.M = n; a.N = d; a.K = f; a.partial = partial; a.shared_gpu = shared;
             a.w_scale = (const float*)(wb + st.pl.sdown);
             if (e == hipSuccess) e = w4 ? launch_gemm_w4(EPI_PARTIAL, a, s) : launch_gemm_partial(a, s);
         }

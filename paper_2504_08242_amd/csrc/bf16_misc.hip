@@ -34,25 +34,44 @@ enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 //   PACK_GATE_UP: 32 packed rows per 16 output features, gate and up rows in the order described above (s0, s1 =
 //                 w_gate, w_up)
 //   PACK_PLAIN:   row n of s0
-__global__ void pack_tiled(u16* __restrict__ dst, const u16* __restrict__ s0, const u16* __restrict__ s1,
-                           const u16* __restrict__ s2, int K, int rows_per, int mode) {
+// W4: the sources are 4-bit codes ([rows, K/2] bytes, low nibble = even input feature) with fp32 scales
+// ([rows, K/128]); the packed row holds bf16(scale * (code - 8)), the value the 4-bit kernels multiply by.
+template <bool W4>
+__global__ void pack_tiled(u16* __restrict__ dst, const void* __restrict__ s0, const void* __restrict__ s1,
+                           const void* __restrict__ s2, const float* __restrict__ sc0, const float* __restrict__ sc1,
+                           const float* __restrict__ sc2, int K, int rows_per, int mode) {
     const int n = blockIdx.x;
-    const u16* src;
+    int which = 0, src_row = n;
     if (mode == PACK_QKV) {
-        const int which = n / rows_per, rr = n % rows_per;
+        which = n / rows_per;
+        const int rr = n % rows_per;
         const int head = rr >> 7, in_head = rr & 127;
-        const int src_row = head * 128 + (which == 2 ? v_packed_to_orig(in_head) : rope_packed_to_orig(in_head));
-        src = (which == 0 ? s0 : which == 1 ? s1 : s2) + (size_t)src_row * K;
+        src_row = head * 128 + (which == 2 ? v_packed_to_orig(in_head) : rope_packed_to_orig(in_head));
     } else if (mode == PACK_GATE_UP) {
         const int rho = n & 31, i = packed_reg(rho);
-        const int feature = 16 * (n >> 5) + 8 * packed_half(rho) + (i & 7);
-        src = ((i >> 3) ? s1 : s0) + (size_t)feature * K;
-    } else {
-        src = s0 + (size_t)n * K;
+        which = i >> 3;
+        src_row = 16 * (n >> 5) + 8 * packed_half(rho) + (i & 7);
     }
+    const void* base = which == 0 ? s0 : which == 1 ? s1 : s2;
     const int k_stages = K / 32;
-    for (int ck = threadIdx.x; ck < K / 8; ck += blockDim.x)
-        *(u32x4*)(dst + tiled_offset(n, ck, k_stages)) = *(const u32x4*)(src + ck * 8);
+    if constexpr (W4) {
+        const unsigned char* codes = (const unsigned char*)base + (size_t)src_row * (K / 2);
+        const float* scales = (which == 0 ? sc0 : which == 1 ? sc1 : sc2) + (size_t)src_row * (K / 128);
+        for (int ck = threadIdx.x; ck < K / 8; ck += blockDim.x) {
+            const unsigned w = *(const unsigned*)(codes + ck * 4);  // eight codes, input features 8 ck .. 8 ck + 7
+            const float sc = scales[ck >> 4];
+            u32x4 out;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                out[j] = pack_bf16x2(sc * (float)((int)((w >> (8 * j)) & 0xFu) - 8),
+                                     sc * (float)((int)((w >> (8 * j + 4)) & 0xFu) - 8));
+            *(u32x4*)(dst + tiled_offset(n, ck, k_stages)) = out;
+        }
+    } else {
+        const u16* src = (const u16*)base + (size_t)src_row * K;
+        for (int ck = threadIdx.x; ck < K / 8; ck += blockDim.x)
+            *(u32x4*)(dst + tiled_offset(n, ck, k_stages)) = *(const u32x4*)(src + ck * 8);
+    }
 }
 
 // The first kernel of a call also clears the arrival counters its later kernels count in (a fill by a kernel, not a
@@ -173,15 +192,33 @@ __global__ __launch_bounds__(1024) void reduce_norm(float* __restrict__ x32, con
 }  // namespace
 
 void launch_pack_qkv(u16* dst, const u16* wq, const u16* wk, const u16* wv, int d, hipStream_t s) {
-    hipLaunchKernelGGL(pack_tiled, dim3(3 * d), dim3(256), 0, s, dst, wq, wk, wv, d, d, (int)PACK_QKV);
+    hipLaunchKernelGGL(pack_tiled<false>, dim3(3 * d), dim3(256), 0, s, dst, (const void*)wq, (const void*)wk,
+                       (const void*)wv, (const float*)nullptr, (const float*)nullptr, (const float*)nullptr, d, d,
+                       (int)PACK_QKV);
 }
 void launch_pack_gate_up(u16* dst, const u16* wg, const u16* wu, int d, int f, hipStream_t s) {
-    hipLaunchKernelGGL(pack_tiled, dim3(2 * f), dim3(256), 0, s, dst, wg, wu, (const u16*)nullptr, d, 0,
+    hipLaunchKernelGGL(pack_tiled<false>, dim3(2 * f), dim3(256), 0, s, dst, (const void*)wg, (const void*)wu,
+                       (const void*)nullptr, (const float*)nullptr, (const float*)nullptr, (const float*)nullptr, d, 0,
                        (int)PACK_GATE_UP);
 }
 void launch_pack_plain(u16* dst, const u16* w, int n_rows, int k, hipStream_t s) {
-    hipLaunchKernelGGL(pack_tiled, dim3(n_rows), dim3(256), 0, s, dst, w, (const u16*)nullptr, (const u16*)nullptr, k,
-                       0, (int)PACK_PLAIN);
+    hipLaunchKernelGGL(pack_tiled<false>, dim3(n_rows), dim3(256), 0, s, dst, (const void*)w, (const void*)nullptr,
+                       (const void*)nullptr, (const float*)nullptr, (const float*)nullptr, (const float*)nullptr, k, 0,
+                       (int)PACK_PLAIN);
+}
+// The same three layouts filled with the bf16 values of 4-bit matrices (codes + scales).
+void launch_expand_qkv(u16* dst, const void* cq, const void* ck, const void* cv, const float* sq, const float* sk,
+                       const float* sv, int d, hipStream_t s) {
+    hipLaunchKernelGGL(pack_tiled<true>, dim3(3 * d), dim3(256), 0, s, dst, cq, ck, cv, sq, sk, sv, d, d, (int)PACK_QKV);
+}
+void launch_expand_gate_up(u16* dst, const void* cg, const void* cu, const float* sg, const float* su, int d, int f,
+                           hipStream_t s) {
+    hipLaunchKernelGGL(pack_tiled<true>, dim3(2 * f), dim3(256), 0, s, dst, cg, cu, (const void*)nullptr, sg, su,
+                       (const float*)nullptr, d, 0, (int)PACK_GATE_UP);
+}
+void launch_expand_plain(u16* dst, const void* c, const float* sc, int n_rows, int k, hipStream_t s) {
+    hipLaunchKernelGGL(pack_tiled<true>, dim3(n_rows), dim3(256), 0, s, dst, c, (const void*)nullptr,
+                       (const void*)nullptr, sc, (const float*)nullptr, (const float*)nullptr, k, 0, (int)PACK_PLAIN);
 }
 void launch_rope_table(float2* tab, int n, int pos0, float theta, int* zero, int n_zero, hipStream_t s) {
     hipLaunchKernelGGL(rope_table, dim3((n * 64 + 255) / 256), dim3(256), 0, s, tab, n, pos0, theta, zero, n_zero);

@@ -96,7 +96,8 @@ jup_status_t jup_diag_kernel_name(const jup_stage_t* stage, int32_t kernel_id, i
         case JUP_K_GEMM_DOWN: kind = jup::GEMM_DOWN; break;
         default: return jup::set_error(JUP_EINVAL, "%s: kernel id %d is not a projection", me, kernel_id);
     }
-    if (c.dtype != JUP_BF16) return jup::set_error(JUP_EINVAL, "%s: only JUP_BF16 stages pick among tilings", me);
+    if (c.dtype != JUP_BF16 && !(c.dtype == JUP_BF16_W4 && c.w4_expanded && n_tokens > 64))
+        return jup::set_error(JUP_EINVAL, "%s: only the bf16 projections pick among tilings", me);
     jup::gemm_kernel_name(kind, n_tokens, c.d_model, c.d_ffn, overlapped != 0, buf, size);
     return JUP_OK;
 }

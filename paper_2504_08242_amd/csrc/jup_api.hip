@@ -44,6 +44,8 @@ const char* check_cfg(const jup_stage_config_t* c) {
     if (!c) return "cfg is NULL";
     if (c->dtype != JUP_F32 && c->dtype != JUP_BF16 && c->dtype != JUP_BF16_W4)
         return "dtype must be JUP_F32, JUP_BF16 or JUP_BF16_W4";
+    if (c->w4_expanded != 0 && !(c->w4_expanded == 1 && c->dtype == JUP_BF16_W4))
+        return "w4_expanded must be 0, or 1 for a JUP_BF16_W4 stage";
     if (c->n_layers < 0 || c->n_layers > 4096) return "n_layers out of range";
     if (c->d_model <= 0 || c->n_heads <= 0 || c->head_dim <= 0 || c->d_ffn <= 0) return "sizes must be positive";
     if ((int64_t)c->n_heads * c->head_dim != c->d_model) return "d_model must equal n_heads * head_dim";
@@ -94,6 +96,12 @@ PackedLayout packed_layout(const jup_stage_config_t& c) {
         p.so = off;    off += align_up(d * d / 128 * 4);
         p.sgu = off;   off += align_up(2 * f * d / 128 * 4);
         p.sdown = off; off += align_up(d * f / 128 * 4);
+        if (c.w4_expanded) {
+            p.xqkv = off;  off += align_up(3 * d * d * 2);
+            p.xo = off;    off += align_up(d * d * 2);
+            p.xgu = off;   off += align_up(2 * f * d * 2);
+            p.xdown = off; off += align_up(d * f * 2);
+        }
     }
     p.layer_bytes = off;
     return p;
@@ -669,9 +677,14 @@ jup_status_t jup_stage_prefill_chunks(jup_stage_t* stage, const void* hidden_in,
         return fail(JUP_EINVAL, "%s: hidden_in and hidden_out must be 16-byte aligned", me);
 
     const size_t row_bytes = (size_t)stage->cfg.d_model * elem_size(stage->cfg);
-    jup_overlap* o = stage->cfg.dtype == JUP_BF16 && stage->cfg.n_layers > 0 ? stage->overlap : nullptr;
+    // the bf16 projections overlap; those of a 4-bit stage do when every chunk is long enough to run on its bf16 copy
+    bool bf16_gemms = stage->cfg.dtype == JUP_BF16 || (stage->cfg.dtype == JUP_BF16_W4 && stage->cfg.w4_expanded);
     int busy = 0;  // chunks with tokens so far
-    for (int c = 0; c < n_chunks; ++c) busy += chunk_tokens[c] > 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        busy += chunk_tokens[c] > 0;
+        if (stage->cfg.dtype == JUP_BF16_W4 && chunk_tokens[c] > 0 && chunk_tokens[c] <= 64) bf16_gemms = false;
+    }
+    jup_overlap* o = bf16_gemms && stage->cfg.n_layers > 0 ? stage->overlap : nullptr;
     if (!o || busy < 2) {  // one after the other on the caller's stream
         int32_t pos = pos_offset;
         const char* in = (const char*)hidden_in;

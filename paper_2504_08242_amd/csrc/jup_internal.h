@@ -25,6 +25,9 @@ struct PackedLayout {
     // 4-bit stages: the four sections above hold packed codes (half a byte per weight) and these the packed fp32
     // scales, one per 128 input features of an output row
     size_t sqkv, so, sgu, sdown;
+    // 4-bit stages created with w4_expanded: bf16 copies of the four matrices in the bf16 path's tiled layout, read
+    // by chunks too long for the 4-bit kernels
+    size_t xqkv, xo, xgu, xdown;
     size_t layer_bytes;
 };
 PackedLayout packed_layout(const jup_stage_config_t& c);

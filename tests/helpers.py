@@ -62,7 +62,7 @@ class Pair:
     """An oracle stage and a GPU stage built from the same seeded tensors."""
 
     def __init__(self, cfg, dtype, seed, max_positions, max_chunk_tokens, weight_std=0.02, layers_np=None,
-                 oracle_positions=None):
+                 oracle_positions=None, w4_expanded=False):
         import torch
         self.cfg, self.dtype, self.seed = dict(cfg), dtype, seed
         bf16 = dtype != "f32"
@@ -77,7 +77,7 @@ class Pair:
                                                                                     weight_std=weight_std)
             self.oracle = oracle.OracleStage(cfg, self.layers_np, oracle_positions or max_positions)
             dev_layers = jb.upload_layers(self.layers_np, dtype)
-        self.stage = jb.Stage(cfg, dtype, dev_layers, max_chunk_tokens)
+        self.stage = jb.Stage(cfg, dtype, dev_layers, max_chunk_tokens, w4_expanded=w4_expanded)
         torch.cuda.synchronize()
         del dev_layers  # the stage keeps its own packed copy
         self.kv = jb.KvCache(cfg, dtype, max_positions)

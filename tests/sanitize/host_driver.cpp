@@ -21,8 +21,8 @@
 
 static void* const FAKE = (void*)0x700000000000ull;  // 256-byte aligned, never touched
 
-static jup_stage_config_t cfg_7b(int dtype) { return {8, 4096, 32, 128, 11008, 1e-5f, 1e4f, dtype}; }
-static jup_stage_config_t cfg_tiny() { return {2, 256, 4, 64, 688, 1e-5f, 1e4f, JUP_F32}; }
+static jup_stage_config_t cfg_7b(int dtype) { return {8, 4096, 32, 128, 11008, 1e-5f, 1e4f, dtype, 0}; }
+static jup_stage_config_t cfg_tiny() { return {2, 256, 4, 64, 688, 1e-5f, 1e4f, JUP_F32, 0}; }
 
 static void stage_and_cache_validation() {
     jup_stage_config_t c = cfg_7b(JUP_BF16), t = cfg_tiny();

@@ -984,6 +984,58 @@ def test_w4_stage_equals_the_bf16_stage_on_weights_both_can_hold():
     assert rel_l2(pq.kv_gpu()[:, :, :, :53], pb.kv_gpu()[:, :, :, :53]) <= 3e-3
 
 
+def test_w4_expanded_stage_runs_long_chunks_on_its_bf16_copy():
+    """A 4-bit stage created with w4_expanded: chunks of more than 64 rows take the bf16 projections on
+    bf16(scale * (code - 8)), shorter ones stream the codes; both against the oracle on the exact expansion (one
+    more rounding of the weights than the codes carry: same bar), cache included."""
+    p = Pair(LLAMA7B_2L, "w4", seed=98, max_positions=700, max_chunk_tokens=256, w4_expanded=True)
+    chunks = [200, 5, 65, 64, 256, 1, 97]
+    h = p.hidden(sum(chunks))
+    g, o = p.run_both(h, chunks)
+    p.check(g, o, "expanded stage, chunk by chunk")
+    row = 0
+    for n in chunks:
+        p.check(g[row:row + n], o[row:row + n], f"expanded stage, chunk of {n} at {row}")
+        row += n
+    kv = p.kv_gpu()[:, :, :, :row]
+    for l in range(2):
+        p.check(kv[l], p.oracle.kv[l, :, :, :row], f"expanded stage, cache layer {l}")
+    # up to 64 rows the expanded stage IS the codes-only stage: bit-identical
+    lean = Pair(LLAMA7B_2L, "w4", seed=98, max_positions=128, max_chunk_tokens=64, layers_np=p.layers_np)
+    p.kv.reset()
+    row = 0
+    for n in [64, 5, 33]:
+        assert np.array_equal(p.gpu_chunk(h[row:row + n], row), lean.gpu_chunk(h[row:row + n], row)), n
+        row += n
+    assert np.array_equal(kv_bits(p.kv)[..., :row, :], kv_bits(lean.kv)[..., :row, :])
+
+
+def test_w4_expanded_copy_is_the_rounded_expansion_bitwise():
+    """Pins the expansion kernel: a bf16 stage built from round_to_bf16(scale * (code - 8)), computed on the host,
+    gives bit-identical results to the expanded 4-bit stage on chunks of more than 64 rows (same kernels, same
+    operands), also through the overlapped multi-chunk call."""
+    from oracle import w4
+    cfg = LLAMA7B_2L
+    layers = si.make_w4_layers(cfg, seed=99)
+    full = w4.dequantize_layers(layers)
+    for w in full:
+        for n in w4.MATRIX_NAMES:
+            w[n] = si.round_to_bf16(w[n].astype(np.float32))
+    pq = Pair(cfg, "w4", seed=99, max_positions=600, max_chunk_tokens=256, layers_np=layers, w4_expanded=True)
+    pb = Pair(cfg, "bf16", seed=99, max_positions=600, max_chunk_tokens=256, layers_np=full)
+    h = pq.hidden(96 + 256 + 130)
+    row = 0
+    for n in [96, 256, 130]:
+        assert np.array_equal(pq.gpu_chunk(h[row:row + n], row), pb.gpu_chunk(h[row:row + n], row)), n
+        row += n
+    assert np.array_equal(kv_bits(pq.kv)[..., :row, :], kv_bits(pb.kv)[..., :row, :])
+    pq.stage.enable_overlap(4)
+    pb.stage.enable_overlap(4)
+    yq, _ = run_chunks_case(pq, [128, 128, 128, 98], exact=False)
+    yb, _ = run_chunks_case(pb, [128, 128, 128, 98], exact=False)
+    assert np.array_equal(yq, yb)
+
+
 def test_w4_stage_creation_rejects_missing_scales():
     torch = torch_mod()
     cfg = dict(si.LLAMA7B_STAGE, n_layers=1, d_model=256, n_heads=2, d_ffn=128)

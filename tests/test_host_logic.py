@@ -56,6 +56,16 @@ def test_size_queries():
     assert 8 * per_layer_w4 <= L.jup_stage_packed_bytes(ctypes.byref(w)) < 8 * per_layer_w4 + (1 << 20)
     assert L.jup_kv_bytes(ctypes.byref(w), 2048) == L.jup_kv_bytes(ctypes.byref(c), 2048)
     assert L.jup_stage_workspace_bytes(ctypes.byref(w), 64) == L.jup_stage_workspace_bytes(ctypes.byref(c), 64)
+    # with the bf16 copy for long chunks: two more bytes per weight; the field belongs to 4-bit stages only
+    x = jb.make_config(si.LLAMA7B_STAGE, "w4", w4_expanded=True)
+    assert (8 * (per_layer_w4 + 2 * n_weights) <= L.jup_stage_packed_bytes(ctypes.byref(x))
+            < 8 * (per_layer_w4 + 2 * n_weights) + (1 << 20))
+    assert L.jup_stage_workspace_bytes(ctypes.byref(x), 512) == L.jup_stage_workspace_bytes(ctypes.byref(c), 512)
+    x.w4_expanded = 2
+    assert L.jup_stage_packed_bytes(ctypes.byref(x)) == 0
+    c.w4_expanded = 1
+    assert L.jup_stage_packed_bytes(ctypes.byref(c)) == 0
+    c.w4_expanded = 0
     w.dtype = 3
     assert L.jup_stage_packed_bytes(ctypes.byref(w)) == 0
 
