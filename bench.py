@@ -18,6 +18,8 @@ those steps.  Beside it the JSON line carries
   roofline    the dominant kernel (the gate/up GEMM with the SwiGLU epilogue), timed in place with HIP events;
   cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample of the same workload.
 --calibrate-mfma adds `mfma_calibration`: what a bare MFMA loop on random operands sustains on this chip.
+--calibrate-fill adds `fill_calibration`: what the operand-fill path of the projection kernels (direct global->LDS
+loads of L2-resident data) moves, by bytes in flight, and the LDS read rate of a CU.
 
 Prints ONE JSON line.
 
@@ -115,6 +117,9 @@ def main():
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="also run a bare MFMA loop on random operands for about 150 ms and report what it sustains "
                          "(TFLOP/s, the shader clock it held) as `mfma_calibration`")
+    ap.add_argument("--calibrate-fill", action="store_true",
+                    help="also run the operand-fill probe (direct global->LDS loads from L2, 1 to 16 pieces of 1 KB per "
+                         "wave in flight) and the LDS read probe, and report them as `fill_calibration`")
     ap.add_argument("--lanes", type=int, default=4,
                     help="lanes enabled for the overlapped call (2..4; for chunks above 256 tokens the library uses all "
                          "of them only when the number of chunks is a multiple of four, else two)")
@@ -325,6 +330,35 @@ def main():
                             "clock_mhz_min": round(float(100.0 * (t[:, 0] / t[:, 1]).min()), 1)}
         del ops
 
+    fill_calibration = None
+    if args.calibrate_fill:
+        window = torch.ones(16 << 20, dtype=torch.uint8, device="cuda:0")   # every workgroup walks these 16 MiB: L2 hits
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        by_depth = {}
+        for depth in (1, 2, 4, 8, 16):
+            best = None
+            for _ in range(4):
+                ev[0].record()
+                nbytes = jb.diag_fill_probe(window, 256, depth, 4096)
+                ev[1].record()
+                torch.cuda.synchronize()
+                ms = ev[0].elapsed_time(ev[1])
+                best = ms if best is None else min(best, ms)
+            by_depth[f"{8 * depth}-{16 * depth} KB in flight per CU"] = round(nbytes / best / 1e9, 2)
+        lds = {}
+        ticks, sink = torch.zeros(256, dtype=torch.int64, device="cuda:0"), torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        for threads in (256, 512, 1024):
+            for _ in range(2):
+                per_wg = jb.diag_lds_read_probe(256, threads, 2000, ticks, sink)
+                torch.cuda.synchronize()
+            lds[f"{threads // 64} waves"] = round(per_wg / float(ticks.cpu().numpy().astype("float64").mean()), 1)
+        fill_calibration = {"l2_to_lds_tb_per_s": by_depth,
+                            "what": "256 workgroups x 8 waves copy 1 KB pieces of a 16 MiB window into LDS with direct "
+                                    "global->LDS loads (best of 4 launches of 8 GiB each); LDS read: 16 bytes per lane and "
+                                    "instruction, conflict-free, bytes per shader clock and CU",
+                            "lds_read_bytes_per_clk_per_cu": lds}
+        del window
+
     vendor_gemm = None
     if args.vendor_gemm:
         d_, f_, m_ = cfg["d_model"], cfg["d_ffn"], calls[0][0]
@@ -481,6 +515,7 @@ def main():
         "per_call": per_call,
         "overlapped": overlapped,
         "mfma_calibration": mfma_calibration,
+        "fill_calibration": fill_calibration,
         "vendor_gemm": vendor_gemm,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

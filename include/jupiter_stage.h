@@ -421,6 +421,25 @@ JUP_API jup_status_t jup_diag_kernel_name(const jup_stage_t *stage, int32_t kern
  */
 JUP_API jup_status_t jup_diag_clock_probe(int64_t ref_ticks, void *ticks, void *stream);
 
+/*
+ * What the operand-fill path of the projection kernels can move: n_workgroups x 8 waves copy 1 KB pieces of buf
+ * (DEVICE; every workgroup walks the same window of window_bytes >= 1 MiB, so the pieces come from L2) into LDS with
+ * direct global->LDS loads, `depth` (1, 2, 4, 8 or 16) pieces per wave in flight, pieces_per_wave (a multiple of 16)
+ * pieces each.  bytes (HOST out, may be NULL): bytes the launch moves.  The caller times the launch.
+ * Errors: JUP_EINVAL, JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_diag_fill_probe(const void *buf, size_t window_bytes, int32_t n_workgroups, int32_t depth,
+                                         int32_t pieces_per_wave, void *stream, double *bytes);
+
+/*
+ * LDS read rate of a CU: n_workgroups workgroups of `threads` lanes (a multiple of 64, up to 1024) read 16 KB per
+ * wave and trip from LDS, 16 bytes per lane and instruction without bank conflicts.  ticks (DEVICE, uint64
+ * [n_workgroups]): shader-clock ticks of each workgroup's loop; sink (DEVICE, one uint32, never written in practice);
+ * bytes_per_workgroup (HOST out, may be NULL).  Errors: JUP_EINVAL, JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_diag_lds_read_probe(int32_t n_workgroups, int32_t threads, int32_t trips, void *ticks,
+                                             void *sink, void *stream, double *bytes_per_workgroup);
+
 /* Message of the last error on this thread ("" if none). Never NULL. */
 JUP_API const char *jup_last_error(void);
 

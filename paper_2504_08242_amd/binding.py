@@ -79,6 +79,8 @@ def lib():
                                            ctypes.POINTER(i32)]),
             "jup_diag_mfma_loop": (i32, [vp, sz, i32, ctypes.c_int64, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]),
             "jup_diag_clock_probe": (i32, [ctypes.c_int64, vp, vp]),
+            "jup_diag_fill_probe": (i32, [vp, sz, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]),
+            "jup_diag_lds_read_probe": (i32, [i32, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]),
             "jup_diag_kernel_name": (i32, [vp, i32, i32, i32, ctypes.c_char_p, sz]),
             "jup_last_error": (ctypes.c_char_p, []),
         }
@@ -357,6 +359,24 @@ def diag_mfma_loop(operands, n_workgroups, iters_per_wave, ticks, sink, stream=N
                                     int(n_workgroups), int(iters_per_wave), ctypes.c_void_p(ticks.data_ptr()),
                                     ctypes.c_void_p(sink.data_ptr()), _stream_handle(stream), ctypes.byref(flop)))
     return flop.value
+
+
+def diag_fill_probe(buf, n_workgroups, depth, pieces_per_wave, stream=None):
+    """Enqueues the operand-fill probe (jup_diag_fill_probe) over the whole of `buf` (uint8 tensor on the GPU);
+    returns the bytes the launch moves."""
+    nbytes = ctypes.c_double()
+    _check(lib().jup_diag_fill_probe(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), int(n_workgroups),
+                                     int(depth), int(pieces_per_wave), _stream_handle(stream), ctypes.byref(nbytes)))
+    return nbytes.value
+
+
+def diag_lds_read_probe(n_workgroups, threads, trips, ticks, sink, stream=None):
+    """Enqueues the LDS read probe (jup_diag_lds_read_probe); ticks: int64 tensor [n_workgroups], sink: int32 tensor
+    [1], both on the GPU.  Returns the bytes one workgroup reads."""
+    nbytes = ctypes.c_double()
+    _check(lib().jup_diag_lds_read_probe(int(n_workgroups), int(threads), int(trips), ctypes.c_void_p(ticks.data_ptr()),
+                                         ctypes.c_void_p(sink.data_ptr()), _stream_handle(stream), ctypes.byref(nbytes)))
+    return nbytes.value
 
 
 def diag_clock_probe(ref_ticks, ticks, stream=None):

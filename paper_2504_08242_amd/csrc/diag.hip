@@ -61,6 +61,56 @@ __global__ __launch_bounds__(64) void clock_probe(unsigned long long ref_ticks, 
     }
 }
 
+// Fill-path probe: 8 waves per workgroup copy 1 KB pieces of `buf` (a window every workgroup walks, so the pieces
+// come from L2) into LDS with the direct global->LDS loads the GEMM ring uses, DEPTH pieces per wave in flight.
+// What it moves per second is the ceiling of the GEMM's operand fill.
+template <int DEPTH>
+__global__ __launch_bounds__(512) void fill_probe(const char* __restrict__ buf, size_t window, int pieces_per_wave) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char fill_lds[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = lds_byte_address(fill_lds);
+    const size_t wg_off = ((size_t)(blockIdx.x >> 3) * 65536) % window;  // workgroups b, b + 8, ... share an XCD and its L2
+    for (int i = 0; i < pieces_per_wave; i += DEPTH) {
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+            const size_t off = (wg_off + ((size_t)(i + u) * 8 + wave) * 1024) % window;
+            load_to_lds_16(uniform_ptr(buf + off), lane * 16, lds0 + (wave * 8 + (u & 7)) * 1024);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (DEPTH & 0xF) | ((DEPTH >> 4) << 14));  // vmcnt(DEPTH): one batch stays in flight
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing lands after the wave has gone
+}
+
+// LDS-read probe: every wave reads 1 KB per instruction (16 bytes per lane, consecutive: conflict-free), eight
+// instructions in flight at a time (issued as text, one wait per batch: the rate of the LDS, not the latency of one
+// read); lane 0 of the workgroup reports the shader-clock ticks of the loop.
+__global__ void lds_read_probe(int trips, unsigned long long* __restrict__ ticks, unsigned* __restrict__ sink) {
+    __shared__ __attribute__((aligned(1024))) unsigned char rd_lds[65536];
+    for (int i = threadIdx.x; i < 16384; i += blockDim.x) ((unsigned*)rd_lds)[i] = i;
+    __syncthreads();
+    const unsigned addr = lds_byte_address(rd_lds) + (threadIdx.x & 63) * 16 + ((threadIdx.x >> 6) & 3) * 1024;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const unsigned long long t0 = __builtin_amdgcn_s_memtime();
+    for (int i = 0; i < trips; ++i) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            u32x4 v[8];
+            asm volatile(
+                "ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:4096\n\tds_read_b128 %2, %8 offset:8192\n\t"
+                "ds_read_b128 %3, %8 offset:12288\n\tds_read_b128 %4, %8 offset:16384\n\tds_read_b128 %5, %8 offset:20480\n\t"
+                "ds_read_b128 %6, %8 offset:24576\n\tds_read_b128 %7, %8 offset:28672\n\ts_waitcnt lgkmcnt(0)"
+                : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3]), "=v"(v[4]), "=v"(v[5]), "=v"(v[6]), "=v"(v[7])
+                : "v"(addr + half * 32768)
+                : "memory");
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc[u & 3] ^= v[u][u & 3];
+        }
+    }
+    const unsigned long long t1 = __builtin_amdgcn_s_memtime();
+    if (threadIdx.x == 0) ticks[blockIdx.x] = t1 - t0;
+    if (acc[0] == 0x12345u && acc[1] == 7u) sink[0] = acc[2] ^ acc[3];  // keeps the reads alive; practically never true
+}
+
 }  // namespace
 }  // namespace jup
 
@@ -79,6 +129,46 @@ jup_status_t jup_diag_mfma_loop(const void* operands, size_t operand_bytes, int3
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return jup::set_error(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
     if (flop) *flop = (double)n_workgroups * 8.0 * (double)iters_per_wave * 8.0 * 2.0 * 32 * 32 * 16;
+    return JUP_OK;
+}
+
+jup_status_t jup_diag_fill_probe(const void* buf, size_t window_bytes, int32_t n_workgroups, int32_t depth,
+                                 int32_t pieces_per_wave, void* stream, double* bytes) {
+    const char* me = "jup_diag_fill_probe";
+    if (!buf) return jup::set_error(JUP_EINVAL, "%s: NULL buffer", me);
+    if (window_bytes < (1u << 20) || window_bytes % 1024)
+        return jup::set_error(JUP_EINVAL, "%s: the window must be at least 1 MiB and a multiple of 1 KiB", me);
+    if (n_workgroups < 1 || n_workgroups > 65536 || pieces_per_wave < 16 || pieces_per_wave % 16 || pieces_per_wave > (1 << 24))
+        return jup::set_error(JUP_EINVAL, "%s: n_workgroups or pieces_per_wave (a multiple of 16) out of range", me);
+    const hipStream_t s = (hipStream_t)stream;
+    switch (depth) {
+#define JUP_FILL_CASE(D)                                                                                              \
+        case D:                                                                                                       \
+            hipLaunchKernelGGL(jup::fill_probe<D>, dim3(n_workgroups), dim3(512), 65536, s, (const char*)buf, window_bytes, \
+                               pieces_per_wave);                                                                      \
+            break;
+        JUP_FILL_CASE(1) JUP_FILL_CASE(2) JUP_FILL_CASE(4) JUP_FILL_CASE(8) JUP_FILL_CASE(16)
+#undef JUP_FILL_CASE
+        default: return jup::set_error(JUP_EINVAL, "%s: depth must be 1, 2, 4, 8 or 16", me);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return jup::set_error(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
+    if (bytes) *bytes = (double)n_workgroups * 8.0 * (double)pieces_per_wave * 1024.0;
+    return JUP_OK;
+}
+
+jup_status_t jup_diag_lds_read_probe(int32_t n_workgroups, int32_t threads, int32_t trips, void* ticks, void* sink,
+                                     void* stream, double* bytes_per_workgroup) {
+    const char* me = "jup_diag_lds_read_probe";
+    if (!ticks || !sink) return jup::set_error(JUP_EINVAL, "%s: NULL buffer", me);
+    if (n_workgroups < 1 || n_workgroups > 65536 || trips < 1 || trips > (1 << 24) || threads < 64 || threads > 1024 ||
+        threads % 64)
+        return jup::set_error(JUP_EINVAL, "%s: n_workgroups, threads (a multiple of 64 up to 1024) or trips out of range", me);
+    hipLaunchKernelGGL(jup::lds_read_probe, dim3(n_workgroups), dim3(threads), 0, (hipStream_t)stream, trips,
+                       (unsigned long long*)ticks, (unsigned*)sink);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return jup::set_error(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
+    if (bytes_per_workgroup) *bytes_per_workgroup = (double)threads * 16.0 * 16.0 * (double)trips;
     return JUP_OK;
 }
 
