@@ -334,9 +334,10 @@ def run_fork_case(p, n_prefix, n_private, n_chunk, n_branches):
     p.kv.truncate(n_prefix - 1)
 
 
-def run_batched_branches_case(p, n_prefix, n_privates, n_chunk):
+def run_batched_branches_case(p, n_prefix, n_privates, n_chunk, exact=True, close=4e-3):
     """All branches advance by n_chunk tokens in ONE call; the result must equal one call per branch bit for
-    bit (outputs and caches), and the oracle within tolerance."""
+    bit (outputs and caches), and the oracle within tolerance.  exact=False: the batched rows run other projection
+    kernels than a single branch's: equal within `close` (rel-L2) instead; the oracle check is the same either way."""
     torch = torch_mod()
     nb = len(n_privates)
     prefix = p.hidden(n_prefix)
@@ -370,8 +371,18 @@ def run_batched_branches_case(p, n_prefix, n_privates, n_chunk):
     torch.cuda.synchronize()
     for b, fk in enumerate(forks):
         got = y[b * n_chunk:(b + 1) * n_chunk]
-        assert np.array_equal(got, seq_out[b]), f"branch {b}: batched output differs from the per-branch call"
-        assert np.array_equal(kv_bits(fk), seq_kv[b]), f"branch {b}: batched cache differs"
+        if exact:
+            assert np.array_equal(got, seq_out[b]), f"branch {b}: batched output differs from the per-branch call"
+            assert np.array_equal(kv_bits(fk), seq_kv[b]), f"branch {b}: batched cache differs"
+        else:
+            assert rel_l2(got, seq_out[b]) <= close, (b, rel_l2(got, seq_out[b]))
+            now, before = kv_bits(fk), seq_kv[b]
+            lo, hi = n_privates[b], n_privates[b] + n_chunk  # the chunk's slots in the fork's own buffer
+            rewritten = np.zeros(now.shape, bool)
+            rewritten[..., lo:hi, :] = True
+            assert np.array_equal(now[~rewritten], before[~rewritten]), f"branch {b}: other cache slots written"
+            as_f32 = lambda bits: (bits.astype(np.uint16).astype(np.uint32) << 16).view(np.float32)
+            assert rel_l2(as_f32(now[..., lo:hi, :]), as_f32(before[..., lo:hi, :])) <= close
         p.check(got, ora_out[b], f"branch {b} chunk (batched)")
         assert len(fk) == pos[b] + n_chunk
     # validation happens before anything is enqueued and leaves every cache as it was
@@ -1008,6 +1019,15 @@ def test_w4_expanded_stage_runs_long_chunks_on_its_bf16_copy():
         assert np.array_equal(p.gpu_chunk(h[row:row + n], row), lean.gpu_chunk(h[row:row + n], row)), n
         row += n
     assert np.array_equal(kv_bits(p.kv)[..., :row, :], kv_bits(lean.kv)[..., :row, :])
+
+
+def test_w4_expanded_stage_batched_branches_of_more_than_64_rows():
+    """Six branches of 16 tokens in one call are 96 rows: on a stage with the bf16 copy they take the bf16 projections
+    (with the per-branch cache append of the QKV epilogue), a single branch's 16 rows the 4-bit ones.  The two read
+    different forms of the weights (rounded to bf16 / exact), so they agree with each other only as closely as each
+    agrees with the oracle; every branch is checked against the oracle at the usual bar."""
+    p = Pair(LLAMA7B_2L, "w4", seed=94, max_positions=70, max_chunk_tokens=128, oracle_positions=110, w4_expanded=True)
+    run_batched_branches_case(p, n_prefix=70, n_privates=[9, 0, 17, 4, 11, 2], n_chunk=16, exact=False, close=1.5e-2)
 
 
 def test_w4_expanded_copy_is_the_rounded_expansion_bitwise():
