@@ -900,6 +900,51 @@ def test_c5_all_eight_branches_in_one_call():
     run_batched_branches_case(p, n_prefix=512, n_privates=[64] * 8, n_chunk=5)
 
 
+@pytest.mark.parametrize("dtype,expanded", [("bf16", False), ("w4", False), ("w4", True)])
+def test_random_chunk_lists_rollbacks_and_multi_chunk_calls(dtype, expanded):
+    """Seeded random histories of one sequence on a 2-layer 7B-shaped stage: chunks whose lengths sit on and beside
+    the tile edges of the kernels (31/32/33 ... 511/512), rollbacks to an earlier position (Sec. V-A) and
+    several chunks in one (possibly overlapped) call, every output and the final cache against the oracle."""
+    torch = torch_mod()
+    sizes_all = [1, 2, 5, 16, 17, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129, 200, 255, 256, 257, 384, 385, 511, 512]
+    rng = np.random.default_rng({"bf16": 11, "w4": 12}[dtype] + int(expanded))
+    cap = 1400
+    for case in range(2):
+        p = Pair(LLAMA7B_2L, dtype, seed=1100 + case, max_positions=cap, max_chunk_tokens=512, w4_expanded=expanded)
+        if case == 1:
+            p.stage.enable_overlap(int(rng.integers(2, 5)))
+        h = p.hidden(cap)
+        pos, history = 0, []
+        for _ in range(int(rng.integers(4, 8))):
+            kind = rng.random()
+            if kind < 0.2 and pos > 8:
+                pos = int(rng.integers(max(0, pos - 200), pos))
+                history.append(f"rollback to {pos}")
+            if kind > 0.7 and pos + 700 < cap:
+                sizes = [int(rng.choice(sizes_all[:18])) for _ in range(int(rng.integers(2, 5)))]
+                x = torch.from_numpy(h[pos:pos + sum(sizes)]).to(device="cuda:0", dtype=p.td)
+                y = to_numpy(p.stage.prefill_chunks(x, sizes, pos, p.kv))
+                torch.cuda.synchronize()
+                want, at = [], pos
+                for n in sizes:
+                    want.append(p.oracle.prefill_chunk(h[at:at + n], at))
+                    at += n
+                history.append(f"chunks {sizes} at {pos}")
+                p.check(y, np.concatenate(want), "; ".join(history))
+                pos = at
+            else:
+                n = min(int(rng.choice(sizes_all)), cap - pos)
+                if n <= 0:
+                    break
+                history.append(f"{n} at {pos}")
+                p.check(p.gpu_chunk(h[pos:pos + n], pos), p.oracle.prefill_chunk(h[pos:pos + n], pos), "; ".join(history))
+                pos += n
+        assert len(p.kv) == pos
+        kv = p.kv_gpu()[:, :, :, :pos]
+        for l in range(2):
+            p.check(kv[l], p.oracle.kv[l, :, :, :pos], f"cache layer {l} after " + "; ".join(history))
+
+
 # ------------------------------------------------------------------------------------------------
 # 4-bit stage (JUP_BF16_W4; the paper evaluates INT4 models, Sec. VI-A): the GPU reads codes and scales, the
 # oracle runs on the matrices they expand to.  Same bar as bf16: codes and scales are exact inputs on both sides.
