@@ -53,6 +53,16 @@ typedef struct jup_seq_plan jup_seq_plan_t; /* opaque: the solved tables for eve
  */
 JUP_API jup_status_t jup_seq_plan_create(const int32_t *xs, int32_t nx, const int32_t *ys, int32_t ny, const double *q,
                                  int32_t b, int32_t n_devices, int32_t s_max, jup_seq_plan_t **out);
+/*
+ * The same tables with the cut points l of Eq. 2 restricted to multiples of `granule` tokens (1..16384): every
+ * sub-sequence but the last is then a whole number of granules.  The paper's recurrence is granule = 1; on this GPU
+ * the stage's kernels work on tiles of 256 token rows, q(x, y) is a staircase in x (a chunk of 513 tokens costs as much
+ * as one of 768) that a coarse profiling grid does not show, and a plan is only as good as its q: granule = 256 keeps
+ * the planner on the points where the interpolated q is true.
+ */
+JUP_API jup_status_t jup_seq_plan_create_aligned(const int32_t *xs, int32_t nx, const int32_t *ys, int32_t ny,
+                                         const double *q, int32_t b, int32_t granule, int32_t n_devices,
+                                         int32_t s_max, jup_seq_plan_t **out);
 JUP_API void jup_seq_plan_destroy(jup_seq_plan_t *plan);
 
 /* q(x, y) as the planner sees it (the interpolation rule above); NaN for a NULL plan, x < 1 or y < 0. */

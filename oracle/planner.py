@@ -102,10 +102,12 @@ def layer_partition_bruteforce(t, mem, budget):
 
 # ---- Eq. 2 and 3: tokens into sub-sequences -----------------------------------------------------------
 class SequenceDP:
-    """W(1..y, k) of Eq. 2 and 3 for one latency function q and one minimum length b, memoised over (y, k)."""
+    """W(1..y, k) of Eq. 2 and 3 for one latency function q and one minimum length b, memoised over (y, k).
+    granule > 1 restricts the cut points l of Eq. 2 to multiples of granule (every sub-sequence but the last is then a
+    whole number of granules); granule = 1 is the recurrence as the paper states it."""
 
-    def __init__(self, q, b):
-        self.q, self.b = q, b
+    def __init__(self, q, b, granule=1):
+        self.q, self.b, self.granule = q, b, granule
         self._memo = {}
 
     def t_star(self, x, l):
@@ -120,6 +122,8 @@ class SequenceDP:
             else:
                 best, lens = INF, None
                 for l in range(1, y):
+                    if l % self.granule:
+                        continue
                     head, head_lens = self.W(l, k - 1)
                     v = max(head, self.t_star(y - l, l))
                     if v < best:
@@ -128,18 +132,20 @@ class SequenceDP:
         return self._memo[key]
 
 
-def sequence_partition_dp(q, y, k, b):
-    return SequenceDP(q, b).W(y, k)
+def sequence_partition_dp(q, y, k, b, granule=1):
+    return SequenceDP(q, b, granule).W(y, k)
 
 
-def compositions(y, k, b):
-    """All ways to write y as an ordered sum of k integers >= b."""
+def compositions(y, k, b, granule=1):
+    """All ways to write y as an ordered sum of k integers >= b, all but the last of them multiples of granule."""
     if k == 1:
         if y >= b:
             yield (y,)
         return
     for first in range(b, y - b * (k - 1) + 1):
-        for rest in compositions(y - first, k - 1, b):
+        if first % granule:
+            continue
+        for rest in compositions(y - first, k - 1, b, granule):
             yield (first,) + rest
 
 
@@ -152,9 +158,9 @@ def chunk_latencies(q, lengths):
     return out
 
 
-def sequence_partition_bruteforce(q, y, k, b):
+def sequence_partition_bruteforce(q, y, k, b, granule=1):
     best = INF
-    for lens in compositions(y, k, b):
+    for lens in compositions(y, k, b, granule):
         best = min(best, max(chunk_latencies(q, lens)))
     return best
 
@@ -165,10 +171,10 @@ def pipeline_latency(q, lengths, n_devices):
     return sum(h) + (n_devices - 1) * max(h)
 
 
-def choose_k(q, y, b, n_devices):
+def choose_k(q, y, b, n_devices, granule=1):
     """k in 1..4|D| minimising Eq. 4 over the partitions of Eq. 2; returns (k, lengths, latency). Ties: smallest k."""
     best = (None, None, INF)
-    dp = SequenceDP(q, b)
+    dp = SequenceDP(q, b, granule)
     for k in range(1, 4 * n_devices + 1):
         w, lens = dp.W(y, k)
         if lens is None or w == INF:

@@ -113,11 +113,18 @@ jup_status_t jup_plan_layers(int32_t n_layers, int32_t n_devices, const double* 
 
 jup_status_t jup_seq_plan_create(const int32_t* xs, int32_t nx, const int32_t* ys, int32_t ny, const double* q,
                                  int32_t b, int32_t n_devices, int32_t s_max, jup_seq_plan_t** out) {
+    return jup_seq_plan_create_aligned(xs, nx, ys, ny, q, b, 1, n_devices, s_max, out);
+}
+
+jup_status_t jup_seq_plan_create_aligned(const int32_t* xs, int32_t nx, const int32_t* ys, int32_t ny, const double* q,
+                                         int32_t b, int32_t granule, int32_t n_devices, int32_t s_max,
+                                         jup_seq_plan_t** out) {
     const char* me = "jup_seq_plan_create";
     if (out) *out = nullptr;
     if (!xs || !ys || !q || !out) return set_error(JUP_EINVAL, "%s: NULL argument", me);
     if (nx < 1 || ny < 1 || nx > 4096 || ny > 4096) return set_error(JUP_EINVAL, "%s: grid sizes must be in 1..4096", me);
     if (b < 1) return set_error(JUP_EINVAL, "%s: the minimum sub-sequence length b=%d must be at least 1", me, b);
+    if (granule < 1 || granule > 16384) return set_error(JUP_EINVAL, "%s: granule=%d is outside 1..16384", me, granule);
     if (n_devices < 1 || n_devices > 64) return set_error(JUP_EINVAL, "%s: n_devices=%d is outside 1..64", me, n_devices);
     if (s_max < 1 || s_max > 16384) return set_error(JUP_EINVAL, "%s: s_max=%d is outside 1..16384", me, s_max);
     if (xs[0] < 1 || ys[0] < 0) return set_error(JUP_EINVAL, "%s: xs must start at 1 or more, ys at 0 or more", me);
@@ -153,11 +160,12 @@ jup_status_t jup_seq_plan_create(const int32_t* xs, int32_t nx, const int32_t* y
         for (int k = 2; k <= K; ++k) {
             const double* prev = &p->W[p->at(k - 1, 0)];
             // W(1..l, k-1) is infinite below (k-1) b tokens and T*(y-l, l) above y - b: only the l between count
-            const long l_lo = (long)(k - 1) * b;
+            // (cut points are multiples of the granule: every sub-sequence but the last a whole number of granules)
+            const long l_lo = ((long)(k - 1) * b + granule - 1) / granule * granule;
             for (int y = 1; y <= S; ++y) {
                 double best = kInf;
                 int best_l = 0;
-                for (long l = l_lo; l <= (long)y - b; ++l) {
+                for (long l = l_lo; l <= (long)y - b; l += granule) {
                     const double v = std::fmax(prev[l], p->q_at(y - (int)l, (int)l));
                     if (v < best) { best = v; best_l = (int)l; }
                 }

@@ -27,6 +27,7 @@ def _lib():
         sig = {
             "jup_plan_layers": (_i32, [_i32, _i32, pd, pd, pd, pi, pd]),
             "jup_seq_plan_create": (_i32, [pi, _i32, pi, _i32, pd, _i32, _i32, _i32, ctypes.POINTER(_vp)]),
+            "jup_seq_plan_create_aligned": (_i32, [pi, _i32, pi, _i32, pd, _i32, _i32, _i32, _i32, ctypes.POINTER(_vp)]),
             "jup_seq_plan_destroy": (None, [_vp]),
             "jup_seq_plan_q": (_f64, [_vp, _i32, _i32]),
             "jup_seq_plan_partition": (_i32, [_vp, _i32, _i32, pi, pd, pd]),
@@ -59,15 +60,16 @@ def plan_layers(layer_time, layer_mem, mem_budget):
 class SeqPlan:
     """The solved sequence-partition tables for every prompt length up to s_max (Eq. 2-4)."""
 
-    def __init__(self, xs, ys, q, b, n_devices, s_max):
-        """q[i][j]: profiled latency of a sub-sequence of xs[i] tokens behind ys[j] cached ones."""
+    def __init__(self, xs, ys, q, b, n_devices, s_max, granule=1):
+        """q[i][j]: profiled latency of a sub-sequence of xs[i] tokens behind ys[j] cached ones.  granule: cut points
+        are multiples of it (jup_seq_plan_create_aligned; 1 = the paper's recurrence)."""
         assert len(q) == len(xs) and all(len(row) == len(ys) for row in q)
-        self.n_devices, self.s_max, self.b = int(n_devices), int(s_max), int(b)
+        self.n_devices, self.s_max, self.b, self.granule = int(n_devices), int(s_max), int(b), int(granule)
         self.handle = _vp()
         flat = [float(v) for row in q for v in row]
-        jb._check(_lib().jup_seq_plan_create(_arr(_i32, map(int, xs)), len(xs), _arr(_i32, map(int, ys)), len(ys),
-                                             _arr(_f64, flat), self.b, self.n_devices, self.s_max,
-                                             ctypes.byref(self.handle)))
+        jb._check(_lib().jup_seq_plan_create_aligned(_arr(_i32, map(int, xs)), len(xs), _arr(_i32, map(int, ys)), len(ys),
+                                                     _arr(_f64, flat), self.b, self.granule, self.n_devices, self.s_max,
+                                                     ctypes.byref(self.handle)))
 
     def q(self, x, y):
         return float(_lib().jup_seq_plan_q(self.handle, int(x), int(y)))
@@ -118,9 +120,12 @@ def main():
     ap.add_argument("--devices", type=int, default=4, help="stages of the pipeline, all as fast as the profiled one")
     ap.add_argument("--b", type=int, default=128, help="shortest sub-sequence that keeps the device busy")
     ap.add_argument("--lengths", type=int, nargs="+", default=[260, 512, 1024, 2048])
+    ap.add_argument("--granule", type=int, default=1,
+                    help="cut points are multiples of this many tokens (1: the paper's recurrence; 256: the row tile of "
+                         "this GPU's kernels, where a coarse q(x, y) table is true)")
     args = ap.parse_args()
     xs, ys, q = read_qxy_csv(args.qxy)
-    plan = SeqPlan(xs, ys, q, args.b, args.devices, max(args.lengths))
+    plan = SeqPlan(xs, ys, q, args.b, args.devices, max(args.lengths), granule=args.granule)
     for y in args.lengths:
         k, lens, lat = plan.best(y)
         one = plan.q(y, 0) * args.devices   # no intra-sequence pipelining: the prompt crosses the stages one by one

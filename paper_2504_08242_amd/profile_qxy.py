@@ -93,7 +93,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--model", choices=("7b", "13b"), default="7b")
     ap.add_argument("--layers", type=int, default=0, help="layers of the stage (default: the benchmark stage)")
-    ap.add_argument("--x", type=int, nargs="+", default=[16, 32, 64, 128, 256, 384, 512, 1024, 2048])
+    ap.add_argument("--x", type=int, nargs="+", default=[16, 32, 64, 128, 256, 384, 512, 768, 1024, 1536, 2048])
     ap.add_argument("--y", type=int, nargs="+", default=[0, 512, 1024, 2048, 4096, 8192])
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--csv", default="")

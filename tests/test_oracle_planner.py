@@ -114,6 +114,35 @@ def test_sequence_partition_dp_equals_enumeration():
                         assert max(op.chunk_latencies(q, lens)) == w
 
 
+def test_sequence_partition_with_aligned_cut_points():
+    """granule g: every sub-sequence but the last is a multiple of g.  DP == enumeration over exactly those
+    partitions; granule 1 is the unrestricted recurrence; a closed form: latency proportional to length, y = 4 g + 1
+    into 2 pieces: the cut is at 2 g (pieces 2 g and 2 g + 1), at 3 pieces at g and 2 g... the best of the aligned ones."""
+    rng = random.Random(5)
+    for trial in range(10):
+        tab = {(x, l): rng.choice([1.0, 2.0, 3.5, 5.0]) + 0.25 * x + 0.1 * l for x in range(1, 26) for l in range(26)}
+        q = lambda x, l: tab[(x, l)]
+        for g in (1, 2, 4, 5):
+            for y in range(1, 25):
+                for k in range(1, 5):
+                    for b in (1, 3):
+                        w, lens = op.sequence_partition_dp(q, y, k, b, g)
+                        assert w == op.sequence_partition_bruteforce(q, y, k, b, g), (trial, g, y, k, b)
+                        if w < INF:
+                            assert sum(lens) == y and len(lens) == k and min(lens) >= b
+                            assert all(x % g == 0 for x in lens[:-1]), (g, lens)
+                            assert max(op.chunk_latencies(q, lens)) == w
+                        if g == 1:
+                            assert (w, lens) == op.sequence_partition_dp(q, y, k, b)
+    q = lambda x, l: float(x)
+    assert op.sequence_partition_dp(q, 4 * 8 + 1, 2, 1, 8) == (17.0, (16, 17))
+    assert op.sequence_partition_dp(q, 4 * 8 + 1, 2, 1, 1) == (17.0, (16, 17))
+    assert op.sequence_partition_dp(q, 33, 3, 1, 8) == (16.0, (8, 16, 9))        # aligned: no better than a piece of 16
+    assert op.sequence_partition_dp(q, 33, 3, 1, 1)[0] == 11.0                   # unrestricted: 11 + 11 + 11
+    assert op.sequence_partition_dp(q, 7, 2, 1, 8) == (INF, None)                # no multiple of 8 below 7
+    assert op.choose_k(lambda x, l: 6.0 + x, 48, 1, 4, 16)[1] == (16, 16, 16)   # three aligned pieces beat 2 and 1
+
+
 def test_choice_of_k_minimises_the_latency_estimate():
     """Eq. 4 by hand: per-chunk overhead c, work proportional to length: Latency(k) = kc + y + (D-1)(c + y/k)."""
     c, y, D = 6.0, 48, 4

@@ -80,6 +80,47 @@ def test_sequence_tables_equal_the_oracle_for_every_length_and_count(b):
             assert len(lens) == k and sum(lens) == y
 
 
+@pytest.mark.parametrize("granule", [2, 4, 7])
+def test_aligned_sequence_tables_equal_the_oracle(granule):
+    """jup_seq_plan_create_aligned: cut points on multiples of the granule, against the oracle's restricted recurrence
+    and its enumeration; granule 1 is jup_seq_plan_create."""
+    rng = random.Random(20 + granule)
+    xs, ys, q = random_table(rng, 5, 4, 40, 60)
+    D, S, b = 2, 40, 3
+    plan = jp.SeqPlan(xs, ys, q, b=b, n_devices=D, s_max=S, granule=granule)
+    plain = jp.SeqPlan(xs, ys, q, b=b, n_devices=D, s_max=S)
+    one = jp.SeqPlan(xs, ys, q, b=b, n_devices=D, s_max=S, granule=1)
+    qf = lambda x, l: op.interp_q(xs, ys, q, x, l)
+    dp = op.SequenceDP(qf, b, granule)
+    for y in range(1, S + 1):
+        for k in range(1, 4 * D + 1):
+            want, _ = dp.W(y, k)
+            if want == INF:
+                with pytest.raises(jb.JupiterError) as ei:
+                    plan.partition(y, k)
+                assert ei.value.status == jb.JUP_ECAP
+            else:
+                lens, w, total = plan.partition(y, k)
+                assert w == pytest.approx(want, rel=1e-12), (y, k)
+                assert len(lens) == k and sum(lens) == y and min(lens) >= b
+                assert all(x % granule == 0 for x in lens[:-1]), lens
+                assert max(op.chunk_latencies(qf, lens)) == pytest.approx(w, rel=1e-12)
+                if y <= 16 and k <= 3:
+                    assert w == pytest.approx(op.sequence_partition_bruteforce(qf, y, k, b, granule), rel=1e-12)
+                assert w >= plain.partition(y, k)[1] * (1 - 1e-12)      # a restriction never helps
+            try:
+                assert one.partition(y, k) == plain.partition(y, k)
+            except jb.JupiterError:
+                pass
+        kb, lb, lat = op.choose_k(qf, y, b, D, granule)
+        if kb is not None:
+            k, lens, got = plan.best(y)
+            assert got == pytest.approx(lat, rel=1e-12), y
+    with pytest.raises(jb.JupiterError) as ei:
+        jp.SeqPlan(xs, ys, q, b=b, n_devices=D, s_max=S, granule=0)
+    assert ei.value.status == jb.JUP_EINVAL
+
+
 def test_sequence_partition_equals_enumeration_on_small_prompts():
     rng = random.Random(9)
     xs, ys, q = random_table(rng, 4, 3, 12, 12)
