@@ -101,7 +101,7 @@ struct W4Rows {
     bf16x8 a[RG][4];
 };
 
-template <int EPI, int RG, int WAVES>
+template <int EPI, int RG, int WAVES, bool STREAM_ONCE>
 __global__ __launch_bounds__(64 * WAVES) void gemm_w4(const GemmArgs a) {
     __shared__ float red[WAVES][16][W4_TILE_N];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -125,9 +125,17 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_w4(const GemmArgs a) {
     }
     const unsigned char* wbase = (const unsigned char*)a.W + (size_t)tile * G * 4096 + lane * 16;
     const float* sbase = a.w_scale + ((size_t)tile * G * 16 + r) * 4;
+    // STREAM_ONCE (one pass over the codes, up to 64 rows): every code is read exactly once, with the non-temporal hint,
+    // so that the stream does not push the KV cache and the activations out of the caches (measured at 5 rows per call:
+    // the attention launch behind the projections 15.0 -> 12.2 us, a step of 8 branches 3.96 -> 3.62 ms).  Longer chunks
+    // take several passes, which find the codes in L2.
     auto fetch_codes = [&](W4Codes& d, int g) {
 #pragma unroll
-        for (int cg = 0; cg < 4; ++cg) d.w[cg] = *(const u32x4*)(wbase + ((size_t)g * 4 + cg) * 1024);
+        for (int cg = 0; cg < 4; ++cg) {
+            const u32x4* src = (const u32x4*)(wbase + ((size_t)g * 4 + cg) * 1024);
+            if constexpr (STREAM_ONCE) d.w[cg] = __builtin_nontemporal_load(src);
+            else d.w[cg] = *src;
+        }
         d.sc = *(const float4*)(sbase + (size_t)g * 64);
     };
     const u32x4 zero_bits = {0u, 0u, 0u, 0u};
@@ -264,7 +272,9 @@ hipError_t launch_rg(GemmArgs a, hipStream_t s) {
     constexpr int WAVES = W4_WAVES;
     a.n_tiles = a.N / W4_TILE_N;
     a.m_tiles = (a.M + 16 * RG - 1) / (16 * RG);
-    hipLaunchKernelGGL((gemm_w4<EPI, RG, WAVES>), dim3(a.n_tiles * a.splits, a.m_tiles), dim3(64 * WAVES), 0, s, a);
+    const dim3 grid(a.n_tiles * a.splits, a.m_tiles);
+    if (a.m_tiles == 1) hipLaunchKernelGGL((gemm_w4<EPI, RG, WAVES, true>), grid, dim3(64 * WAVES), 0, s, a);
+    else hipLaunchKernelGGL((gemm_w4<EPI, RG, WAVES, false>), grid, dim3(64 * WAVES), 0, s, a);
     return hipGetLastError();
 }
 // Rows per pass over the codes: 16, 32 or 64 (a longer chunk takes several passes of 64).
