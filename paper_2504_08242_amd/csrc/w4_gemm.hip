@@ -266,9 +266,11 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_w4(const GemmArgs a) {
 
 template <int EPI, int RG>
 hipError_t launch_rg(GemmArgs a, hipStream_t s) {
-    // Eight waves per workgroup split its K range.  Measured on the 7B shapes at 64 rows per pass (246 registers per
-    // lane, so eight waves per CU either way): two workgroups of four waves per CU run gate/up 5 % faster and QKV
-    // 40 % slower than one of eight; at 5 rows 4, 8 and 16 waves measured within 5 % of each other.
+    // Eight waves per workgroup split its K range, whatever the row count: the order in which the K shares are summed
+    // is then the same for a branch submitted alone and batched with others, and the two give the same bits.  Measured
+    // on the 7B shapes at 64 rows per pass (246 registers per lane, so eight waves per CU either way): two workgroups of
+    // four waves per CU run gate/up 4-5 % faster (its 344 workgroups then fit one round instead of two) and QKV 40 %
+    // slower than one of eight; at 5 rows 4, 8 and 16 waves measured within 5 % of each other.
     constexpr int WAVES = W4_WAVES;
     a.n_tiles = a.N / W4_TILE_N;
     a.m_tiles = (a.M + 16 * RG - 1) / (16 * RG);
