@@ -522,19 +522,24 @@ int gemm_partial_col_blocks(int M, int N, int K) {
 // 16 x 128 and 8 x 64 tokens +3-4 % (no split at all: -4 % there); alone on the chip the same cap costs 8 % (one
 // launch then has to fill it).
 // The output projection of a prefill-sized chunk (K no longer than N, 129 to 512 rows) alone on the chip: 128 x 128
-// tiles with two splits instead of 256 x 128 tiles with four.  The K loop is a little slower (a third more LDS
-// traffic per flop), but half the partial sums are written and read back: measured at 512 rows of the 7B shapes, O
+// tiles with two splits (four for up to 256 rows) instead of 256 x 128 tiles with four.  The K loop is a little slower
+// (a third more LDS traffic per flop), but half the partial sums are written and read back: measured at 512 rows of the 7B shapes, O
 // projection 28.3 -> 29.4 us, the reduce + norm pass behind it 13.7 -> 10.2 us, the prompt +1.5 %.  (The same for the
 // down projection, whose K loop is 2.7 times as long, measured slower: 52.3 -> 59.4 us.)
 static bool square_prefill_projection(int M, int N, int K, bool shared) {
-    return !shared && M > 128 && M <= 512 && K <= N;  // (measured at 512 rows only; longer chunks keep the tall tile)
+    // (the down projection too for up to 256 rows: four splits of 86 stages instead of eight of 43; measured at 256
+    // rows 35.9 -> 36.5 us, the reduce + norm pass behind it reads half the partial sums, the prompt as 8 x 256 +1.5 %)
+    return !shared && M > 128 && M <= 512 && (K <= N || M <= 256);  // (longer chunks keep the tall tile)
 }
 
 int gemm_plan_splits(int M, int N, int K, bool shared) {
     if (square_prefill_projection(M, N, K, shared)) {
         const int tiles = div_up(M, 128) * div_up(N, 128);
         int splits = 1;
-        while (tiles * splits * 2 <= kCUs && (K / G_BK) % (splits * 2) == 0 && splits < 2) splits *= 2;
+        // (up to 256 rows two splits would leave half of the CUs idle: four; measured at 256 rows, O projection
+        // 25.7 -> 21.1 us, the reduce + norm pass behind it 9.8 -> 10.8 us)
+        const int cap = M <= 256 ? 4 : 2;
+        while (tiles * splits * 2 <= kCUs && (K / G_BK) % (splits * 2) == 0 && splits < cap) splits *= 2;
         return splits;
     }
     // beside other chunks' kernels: the widest tile of the chunk's row count (see launch_gemm_partial)
@@ -580,6 +585,9 @@ TileShape pick_qkv(int M, int N, bool shared_gpu) {
     if (shared_gpu && bmb == 4) return {4, 3, 4, 1};
     if (bmb == 2) return {2, 2, 2, 2};
     if (bmb == 4) return {4, 2, 4, 1};
+    // 129 to 256 rows alone on the chip: 128 x 96 tiles instead of 256 x 64 (at N = 12288 256 workgroups instead of 192,
+    // and 14 KB instead of 20 KB through the fill path per stage); measured at 256 rows: 48.9 -> 42.8 us
+    if (!shared_gpu && M > 128 && M <= 256) return {4, 3, 4, 1};
     static const int cands[] = {1, 2, 3};
     const int nb = pick_blocks(M, N, cands, 3);
     // Beside another chunk's kernels (overlapped multi-chunk call) half as many tiles of twice the width do the
