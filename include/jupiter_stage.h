@@ -423,7 +423,8 @@ JUP_API jup_status_t jup_diag_clock_probe(int64_t ref_ticks, void *ticks, void *
 
 /*
  * What the operand-fill path of the projection kernels can move: n_workgroups x 8 waves copy 1 KB pieces of buf
- * (DEVICE; every workgroup walks the same window of window_bytes >= 1 MiB, so the pieces come from L2) into LDS with
+ * (DEVICE; every workgroup walks the same window of window_bytes, a power of two between 1 MiB and 2 GiB that the
+ * buffer holds, so the pieces come from L2 when the window fits there) into LDS with
  * direct global->LDS loads, `depth` (1, 2, 4, 8 or 16) pieces per wave in flight, pieces_per_wave (a multiple of 16)
  * pieces each.  bytes (HOST out, may be NULL): bytes the launch moves.  The caller times the launch.
  * Errors: JUP_EINVAL, JUP_EDEVICE.

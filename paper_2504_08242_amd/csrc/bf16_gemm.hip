@@ -493,12 +493,13 @@ hipError_t gemm_configure() {
 // The projections whose N (= d_model) alone cannot fill the chip are split along K; the fp32 partial sums are
 // added up, in split order, by the reduce + norm kernel that follows.
 namespace {
-// splits for tiles of 32*nb columns: doubled while the grid stays within one round of workgroups and the K
-// stages divide evenly
+// splits for tiles of 32*nb columns: the largest count up to 8 that keeps the grid within one round of workgroups
+// and divides the K stages evenly (powers of two on the 7B shapes; d = 5120 and FFN 13824 also allow 5, 3 and 6)
 int splits_for(int M, int N, int K, int nb) {
     const int tiles = div_up(M, 32 * pick_row_blocks(M)) * div_up(N, 32 * nb);
     int splits = 1;
-    while (tiles * splits * 2 <= kCUs && (K / G_BK) % (splits * 2) == 0 && splits < 8) splits *= 2;
+    for (int s = 2; s <= 8; ++s)
+        if (tiles * s <= kCUs && (K / G_BK) % s == 0) splits = s;
     return splits;
 }
 }  // namespace

@@ -65,15 +65,17 @@ __global__ __launch_bounds__(64) void clock_probe(unsigned long long ref_ticks, 
 // come from L2) into LDS with the direct global->LDS loads the GEMM ring uses, DEPTH pieces per wave in flight.
 // What it moves per second is the ceiling of the GEMM's operand fill.
 template <int DEPTH>
-__global__ __launch_bounds__(512) void fill_probe(const char* __restrict__ buf, size_t window, int pieces_per_wave) {
+__global__ __launch_bounds__(512) void fill_probe(const char* __restrict__ buf, unsigned window, int pieces_per_wave) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char fill_lds[];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const unsigned lds0 = lds_byte_address(fill_lds);
-    const size_t wg_off = ((size_t)(blockIdx.x >> 3) * 65536) % window;  // workgroups b, b + 8, ... share an XCD and its L2
+    // (offsets in 32-bit arithmetic with a mask: a 64-bit remainder per piece costs a wave more time than the load)
+    const unsigned mask = window - 1u;                              // the window is a power of two
+    const unsigned wg_off = ((blockIdx.x >> 3) * 65536u) & mask;    // workgroups b, b + 8, ... share an XCD and its L2
     for (int i = 0; i < pieces_per_wave; i += DEPTH) {
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u) {
-            const size_t off = (wg_off + ((size_t)(i + u) * 8 + wave) * 1024) % window;
+            const unsigned off = (wg_off + ((unsigned)(i + u) * 8u + wave) * 1024u) & mask;
             load_to_lds_16(uniform_ptr(buf + off), lane * 16, lds0 + (wave * 8 + (u & 7)) * 1024);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70 | (DEPTH & 0xF) | ((DEPTH >> 4) << 14));  // vmcnt(DEPTH): one batch stays in flight
@@ -106,6 +108,7 @@ __global__ void lds_read_probe(int trips, unsigned long long* __restrict__ ticks
             for (int u = 0; u < 8; ++u) acc[u & 3] ^= v[u][u & 3];
         }
     }
+    __syncthreads();  // the slowest wave ends the measurement: the first wave is served first and finishes early
     const unsigned long long t1 = __builtin_amdgcn_s_memtime();
     if (threadIdx.x == 0) ticks[blockIdx.x] = t1 - t0;
     if (acc[0] == 0x12345u && acc[1] == 7u) sink[0] = acc[2] ^ acc[3];  // keeps the reads alive; practically never true
@@ -136,15 +139,15 @@ jup_status_t jup_diag_fill_probe(const void* buf, size_t window_bytes, int32_t n
                                  int32_t pieces_per_wave, void* stream, double* bytes) {
     const char* me = "jup_diag_fill_probe";
     if (!buf) return jup::set_error(JUP_EINVAL, "%s: NULL buffer", me);
-    if (window_bytes < (1u << 20) || window_bytes % 1024)
-        return jup::set_error(JUP_EINVAL, "%s: the window must be at least 1 MiB and a multiple of 1 KiB", me);
+    if (window_bytes < (1u << 20) || window_bytes > (1u << 31) || (window_bytes & (window_bytes - 1)))
+        return jup::set_error(JUP_EINVAL, "%s: the window must be a power of two between 1 MiB and 2 GiB", me);
     if (n_workgroups < 1 || n_workgroups > 65536 || pieces_per_wave < 16 || pieces_per_wave % 16 || pieces_per_wave > (1 << 24))
         return jup::set_error(JUP_EINVAL, "%s: n_workgroups or pieces_per_wave (a multiple of 16) out of range", me);
     const hipStream_t s = (hipStream_t)stream;
     switch (depth) {
 #define JUP_FILL_CASE(D)                                                                                              \
         case D:                                                                                                       \
-            hipLaunchKernelGGL(jup::fill_probe<D>, dim3(n_workgroups), dim3(512), 65536, s, (const char*)buf, window_bytes, \
+            hipLaunchKernelGGL(jup::fill_probe<D>, dim3(n_workgroups), dim3(512), 65536, s, (const char*)buf, (unsigned)window_bytes, \
                                pieces_per_wave);                                                                      \
             break;
         JUP_FILL_CASE(1) JUP_FILL_CASE(2) JUP_FILL_CASE(4) JUP_FILL_CASE(8) JUP_FILL_CASE(16)

@@ -15,7 +15,8 @@ def test_diag_entry_points_reject_bad_arguments_before_any_launch():
     bad_fill = [
         (None, 16 << 20, 256, 8, 4096),          # no buffer
         (FAKE, 1 << 19, 256, 8, 4096),           # window below 1 MiB
-        (FAKE, (16 << 20) + 512, 256, 8, 4096),  # not a multiple of 1 KiB
+        (FAKE, (16 << 20) + 1024, 256, 8, 4096), # not a power of two
+        (FAKE, 3 << 20, 256, 8, 4096),           # not a power of two
         (FAKE, 16 << 20, 0, 8, 4096),            # no workgroups
         (FAKE, 16 << 20, 256, 3, 4096),          # depth not offered
         (FAKE, 16 << 20, 256, 8, 100),           # pieces not a multiple of 16
