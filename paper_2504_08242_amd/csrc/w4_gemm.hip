@@ -128,7 +128,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_w4(const GemmArgs a) {
     // STREAM_ONCE (one pass over the codes, up to 64 rows): every code is read exactly once, with the non-temporal hint,
     // so that the stream does not push the KV cache and the activations out of the caches (measured at 5 rows per call:
     // the attention launch behind the projections 15.0 -> 12.2 us, a step of 8 branches 3.96 -> 3.62 ms).  Longer chunks
-    // take several passes, which find the codes in L2.
+    // take several passes, which find the codes in L2, and inside an overlapped call the other chunks' launches find them
+    // in the caches (as for the bf16 kernels: not measured separately for the codes).
     auto fetch_codes = [&](W4Codes& d, int g) {
 #pragma unroll
         for (int cg = 0; cg < 4; ++cg) {
@@ -275,7 +276,7 @@ hipError_t launch_rg(GemmArgs a, hipStream_t s) {
     a.n_tiles = a.N / W4_TILE_N;
     a.m_tiles = (a.M + 16 * RG - 1) / (16 * RG);
     const dim3 grid(a.n_tiles * a.splits, a.m_tiles);
-    if (a.m_tiles == 1) hipLaunchKernelGGL((gemm_w4<EPI, RG, WAVES, true>), grid, dim3(64 * WAVES), 0, s, a);
+    if (a.m_tiles == 1 && !a.shared_gpu) hipLaunchKernelGGL((gemm_w4<EPI, RG, WAVES, true>), grid, dim3(64 * WAVES), 0, s, a);
     else hipLaunchKernelGGL((gemm_w4<EPI, RG, WAVES, false>), grid, dim3(64 * WAVES), 0, s, a);
     return hipGetLastError();
 }
