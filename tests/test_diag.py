@@ -62,3 +62,29 @@ def test_diag_probes_run_and_report_plausible_rates():
     torch.cuda.synchronize()
     shader, ref = clk.cpu().tolist()
     assert ref >= 100_000 and 300.0 < 100.0 * shader / ref < 3000.0      # MHz
+
+
+@pytest.mark.gpu
+def test_kernel_name_reports_the_documented_tile_policy():
+    """jup_diag_kernel_name names the instantiation a projection of n tokens runs as (what ties a counter reading on file
+    to the tiling that runs today).  The shapes the design document gives for the 7B-shaped stage, alone on the chip and
+    inside an overlapped call: a change of the policy has to show up here and there."""
+    from paper_2504_08242_amd import synth_inputs as si
+    cfg = dict(si.LLAMA7B_STAGE, n_layers=1)
+    layers = si.make_layers(cfg, seed=5, bf16=True)
+    stage = jb.Stage(cfg, "bf16", jb.upload_layers(layers, "bf16"), 2048)
+    K = jb.KERNEL_IDS
+    want = {   # (kernel, rows, overlapped): <row blocks, column blocks, waves along M, waves along N, epilogue>
+        ("gemm_gate_up", 512, False): "gemm_bf16<8,6,4,2,2>", ("gemm_qkv", 512, False): "gemm_bf16<4,6,4,2,0>",
+        ("gemm_o", 512, False): "gemm_bf16<4,4,4,2,1>", ("gemm_down", 512, False): "gemm_bf16<8,4,4,2,1>",
+        ("gemm_gate_up", 512, True): "gemm_bf16<8,8,4,2,2>", ("gemm_qkv", 512, True): "gemm_bf16<8,6,4,2,0>",
+        ("gemm_qkv", 256, False): "gemm_bf16<4,3,4,1,0>", ("gemm_gate_up", 256, False): "gemm_bf16<8,3,4,1,2>",
+        ("gemm_o", 256, False): "gemm_bf16<4,4,4,2,1>", ("gemm_down", 256, False): "gemm_bf16<4,4,4,2,1>",
+        ("gemm_qkv", 128, False): "gemm_bf16<4,2,4,1,0>", ("gemm_gate_up", 128, False): "gemm_bf16<4,3,4,1,2>",
+        ("gemm_qkv", 64, False): "gemm_bf16<2,2,2,2,0>", ("gemm_gate_up", 64, False): "gemm_bf16<2,3,2,3,2>",
+        ("gemm_gate_up", 5, False): "gemm_bf16<1,3,1,3,2>", ("gemm_qkv", 5, False): "gemm_bf16<2,2,2,2,0>",
+        ("gemm_gate_up", 1024, False): "gemm_bf16<8,6,4,2,2>", ("gemm_qkv", 1024, False): "gemm_bf16<8,3,8,1,0>",
+    }
+    got = {k: stage.kernel_name(K[k[0]], k[1], k[2]) for k in want}
+    assert got == want, {k: (got[k], want[k]) for k in want if got[k] != want[k]}
+    stage.destroy()
