@@ -486,7 +486,11 @@ hipError_t launch_chunk_attention(const u16* q, u16* o, int n, int d_model, int 
     }
     // chunks of up to 256 tokens behind a long cached sequence: several workgroups per query block (key splits)
     const int splits = att_key_splits(n, (pos0 + n + kKT - 1) / kKT);
-    if (n <= 64) {
+    // 32 queries per workgroup up to 64 tokens, and up to 128 when the launch has the chip to itself (twice the
+    // workgroups of the 64-query variant, which a launch this small needs more than shared tile fills: measured on
+    // 128-token chunks, 7B shapes 18.4 -> 17.0 us, 13B shapes 14.6 -> 13.0 us; inside an overlapped call the same
+    // choice costs 2-3.5 %, at 256 tokens it gains nothing)
+    if (n <= (shared_gpu ? 64 : 128)) {
         const int wgs = (n + 31) / 32 * n_heads;
         if (!split_fits(sc, wgs, splits, 32)) return hipErrorInvalidValue;
         hipLaunchKernelGGL((chunk_attention_bf16<1, 2>), dim3(wgs, splits), dim3(768), kAttLds, s, q, o, n, d_model,
