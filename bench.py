@@ -19,7 +19,8 @@ those steps.  Beside it the JSON line carries
   cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample of the same workload.
 --calibrate-mfma adds `mfma_calibration`: what a bare MFMA loop on random operands sustains on this chip.
 --calibrate-fill adds `fill_calibration`: what the operand-fill path of the projection kernels (direct global->LDS
-loads of L2-resident data) moves, by bytes in flight, and the LDS read rate of a CU.
+loads of L2-resident data) moves, by bytes in flight, what the same loads stream out of HBM when every byte is read
+once (the floor of a short-chunk projection: by grid size, and per launch by bytes moved), and the LDS read rate of a CU.
 
 Prints ONE JSON line.
 
@@ -119,7 +120,8 @@ def main():
                          "(TFLOP/s, the shader clock it held) as `mfma_calibration`")
     ap.add_argument("--calibrate-fill", action="store_true",
                     help="also run the operand-fill probe (direct global->LDS loads from L2, 1 to 16 pieces of 1 KB per "
-                         "wave in flight) and the LDS read probe, and report them as `fill_calibration`")
+                         "wave in flight), the HBM stream probe (disjoint regions read once) and the LDS read probe, and report "
+                         "them as `fill_calibration`")
     ap.add_argument("--lanes", type=int, default=4,
                     help="lanes enabled for the overlapped call (2..4; for chunks above 256 tokens the library uses all "
                          "of them only when the number of chunks is a multiple of four, else two)")
@@ -352,10 +354,33 @@ def main():
                 per_wg = jb.diag_lds_read_probe(256, threads, 2000, ticks, sink)
                 torch.cuda.synchronize()
             lds[f"{threads // 64} waves"] = round(per_wg / float(ticks.cpu().numpy().astype("float64").mean()), 1)
-        fill_calibration = {"l2_to_lds_tb_per_s": by_depth,
+        # the weight stream of a short-chunk projection with everything else taken away: disjoint regions, read once
+        big = torch.ones(2 << 30, dtype=torch.uint8, device="cuda:0")
+        seg = 256 << 20   # bytes of the launches timed by grid size; the 2 GiB buffer keeps every launch cold
+        def stream_launches(n_launch, n_wg, ppw):   # back to back on the stream, like the kernels of a call
+            ev[0].record()
+            nb = jb.diag_stream_probe(big, n_wg, 4, ppw, n_launch)
+            ev[1].record()
+            torch.cuda.synchronize()
+            return nb, ev[0].elapsed_time(ev[1]) / n_launch
+        by_grid = {}
+        for n_wg in (128, 192, 230, 256):
+            ppw = (seg // n_wg // 8192) // 4 * 4
+            best = min(stream_launches(8, n_wg, ppw)[1] for _ in range(3))
+            by_grid[f"{n_wg} workgroups"] = round(n_wg * ppw * 8192 / best / 1e9, 2)
+        by_size = {}
+        for ppw in (4, 12, 16, 24, 44, 48, 88):   # x 256 workgroups x 8 KiB: 8.4 .. 184.5 MB, the projections' weight bytes
+            best = min(stream_launches(32, 256, ppw)[1] for _ in range(3))
+            by_size[f"{256 * ppw * 8192 / 1e6:.1f} MB"] = round(1e3 * best, 2)
+        del big
+        fill_calibration = {"hbm_to_lds_tb_per_s": by_grid, "hbm_to_lds_launch_us_256_workgroups": by_size,
+                            "l2_to_lds_tb_per_s": by_depth,
                             "what": "256 workgroups x 8 waves copy 1 KB pieces of a 16 MiB window into LDS with direct "
                                     "global->LDS loads (best of 4 launches of 8 GiB each); LDS read: 16 bytes per lane and "
-                                    "instruction, conflict-free, bytes per shader clock and CU",
+                                    "instruction, conflict-free, bytes per shader clock and CU; hbm_to_lds: workgroups of "
+                                    "8 waves stream disjoint regions once (4 pieces of 1 KB per wave in flight), rate of "
+                                    "256 MiB launches by grid size and microseconds per launch by bytes moved, launches "
+                                    "enqueued back to back like the kernels of a call",
                             "lds_read_bytes_per_clk_per_cu": lds}
         del window
 

@@ -433,6 +433,18 @@ JUP_API jup_status_t jup_diag_fill_probe(const void *buf, size_t window_bytes, i
                                          int32_t pieces_per_wave, void *stream, double *bytes);
 
 /*
+ * Floor of a projection that streams its weights once: n_workgroups x 8 waves copy disjoint contiguous regions of buf
+ * (DEVICE, buf_bytes long; pieces_per_wave x 8 KiB per workgroup) into LDS with direct global->LDS loads, `depth`
+ * (1, 2, 4, 8 or 16; pieces_per_wave is a multiple of it) pieces of 1 KiB per wave in flight; nothing is read twice
+ * inside a launch.  n_launches (1..4096) launches are enqueued back to back, like the kernels of a call; successive
+ * launches read successive parts of the buffer, round robin (a buffer several times the last-level cache keeps every
+ * launch cold).  bytes (HOST out, may be NULL): bytes all launches move.  The caller times them.  Errors: JUP_EINVAL
+ * (also when the buffer is too short for one launch), JUP_EDEVICE.
+ */
+JUP_API jup_status_t jup_diag_stream_probe(const void *buf, size_t buf_bytes, int32_t n_workgroups, int32_t depth,
+                                           int32_t pieces_per_wave, int32_t n_launches, void *stream, double *bytes);
+
+/*
  * LDS read rate of a CU: n_workgroups workgroups of `threads` lanes (a multiple of 64, up to 1024) read 16 KB per
  * wave and trip from LDS, 16 bytes per lane and instruction without bank conflicts.  ticks (DEVICE, uint64
  * [n_workgroups]): shader-clock ticks of each workgroup's loop; sink (DEVICE, one uint32, never written in practice);

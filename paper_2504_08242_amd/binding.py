@@ -80,6 +80,7 @@ def lib():
             "jup_diag_mfma_loop": (i32, [vp, sz, i32, ctypes.c_int64, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]),
             "jup_diag_clock_probe": (i32, [ctypes.c_int64, vp, vp]),
             "jup_diag_fill_probe": (i32, [vp, sz, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]),
+            "jup_diag_stream_probe": (i32, [vp, sz, i32, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]),
             "jup_diag_lds_read_probe": (i32, [i32, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]),
             "jup_diag_kernel_name": (i32, [vp, i32, i32, i32, ctypes.c_char_p, sz]),
             "jup_last_error": (ctypes.c_char_p, []),
@@ -367,6 +368,17 @@ def diag_fill_probe(buf, n_workgroups, depth, pieces_per_wave, stream=None):
     nbytes = ctypes.c_double()
     _check(lib().jup_diag_fill_probe(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), int(n_workgroups),
                                      int(depth), int(pieces_per_wave), _stream_handle(stream), ctypes.byref(nbytes)))
+    return nbytes.value
+
+
+def diag_stream_probe(buf, n_workgroups, depth, pieces_per_wave, n_launches=1, stream=None):
+    """Enqueues the weight-stream probe (jup_diag_stream_probe) n_launches times back to back: n_workgroups disjoint
+    regions of `buf` (uint8 tensor on the GPU) streamed once into LDS per launch, successive launches on successive parts
+    of the buffer; returns the bytes all launches move."""
+    nbytes = ctypes.c_double()
+    _check(lib().jup_diag_stream_probe(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), int(n_workgroups),
+                                       int(depth), int(pieces_per_wave), int(n_launches), _stream_handle(stream),
+                                       ctypes.byref(nbytes)))
     return nbytes.value
 
 

@@ -83,6 +83,25 @@ __global__ __launch_bounds__(512) void fill_probe(const char* __restrict__ buf, 
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing lands after the wave has gone
 }
 
+// Stream probe: the weight stream of a short-chunk projection with everything else taken away.  Every workgroup (8
+// waves) copies its own contiguous region of `buf` into LDS with the same direct loads, DEPTH pieces of 1 KB per wave in
+// flight; nothing is read twice, so the bytes come from HBM.  What it moves per second, and how long a launch of a
+// projection's size takes, is the floor of a kernel that streams that many weight bytes once.
+template <int DEPTH>
+__global__ __launch_bounds__(512) void stream_probe(const char* __restrict__ buf, size_t region, int pieces_per_wave) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char fill_lds[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = lds_byte_address(fill_lds);
+    const char* base = buf + (size_t)blockIdx.x * region + (size_t)wave * 1024;
+    for (int i = 0; i < pieces_per_wave; i += DEPTH) {
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u)
+            load_to_lds_16(uniform_ptr(base + (size_t)(i + u) * 8192), lane * 16, lds0 + (wave * 8 + (u & 7)) * 1024);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (DEPTH & 0xF) | ((DEPTH >> 4) << 14));  // vmcnt(DEPTH): one batch stays in flight
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing lands after the wave has gone
+}
+
 // LDS-read probe: every wave reads 1 KB per instruction (16 bytes per lane, consecutive: conflict-free), eight
 // instructions in flight at a time (issued as text, one wait per batch: the rate of the LDS, not the latency of one
 // read); lane 0 of the workgroup reports the shader-clock ticks of the loop.
@@ -157,6 +176,40 @@ jup_status_t jup_diag_fill_probe(const void* buf, size_t window_bytes, int32_t n
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return jup::set_error(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
     if (bytes) *bytes = (double)n_workgroups * 8.0 * (double)pieces_per_wave * 1024.0;
+    return JUP_OK;
+}
+
+jup_status_t jup_diag_stream_probe(const void* buf, size_t buf_bytes, int32_t n_workgroups, int32_t depth,
+                                   int32_t pieces_per_wave, int32_t n_launches, void* stream, double* bytes) {
+    const char* me = "jup_diag_stream_probe";
+    if (!buf) return jup::set_error(JUP_EINVAL, "%s: NULL buffer", me);
+    if (depth != 1 && depth != 2 && depth != 4 && depth != 8 && depth != 16)
+        return jup::set_error(JUP_EINVAL, "%s: depth must be 1, 2, 4, 8 or 16", me);
+    if (n_workgroups < 1 || n_workgroups > 65536 || pieces_per_wave < depth || pieces_per_wave % depth || pieces_per_wave > (1 << 24))
+        return jup::set_error(JUP_EINVAL, "%s: n_workgroups or pieces_per_wave (a multiple of depth) out of range", me);
+    const size_t region = (size_t)pieces_per_wave * 8192;  // 8 waves x 1 KB per piece
+    if (n_launches < 1 || n_launches > 4096) return jup::set_error(JUP_EINVAL, "%s: n_launches out of range", me);
+    const size_t per_launch = region * (size_t)n_workgroups;
+    if (buf_bytes / region < (size_t)n_workgroups)
+        return jup::set_error(JUP_EINVAL, "%s: the buffer holds %zu bytes, a launch reads %zu", me, buf_bytes, per_launch);
+    const size_t slots = buf_bytes / per_launch;  // successive launches read successive parts of the buffer, round robin
+    const hipStream_t s = (hipStream_t)stream;
+    for (int32_t i = 0; i < n_launches; ++i) {
+        const char* part = (const char*)buf + (size_t)(i % slots) * per_launch;
+        switch (depth) {
+#define JUP_STREAM_CASE(D)                                                                                            \
+            case D:                                                                                                   \
+                hipLaunchKernelGGL(jup::stream_probe<D>, dim3(n_workgroups), dim3(512), 65536, s, part, region,        \
+                                   pieces_per_wave);                                                                  \
+                break;
+            JUP_STREAM_CASE(1) JUP_STREAM_CASE(2) JUP_STREAM_CASE(4) JUP_STREAM_CASE(8) JUP_STREAM_CASE(16)
+#undef JUP_STREAM_CASE
+            default: return jup::set_error(JUP_EINVAL, "%s: depth must be 1, 2, 4, 8 or 16", me);
+        }
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return jup::set_error(JUP_EDEVICE, "%s: %s", me, hipGetErrorString(e));
+    if (bytes) *bytes = (double)n_launches * (double)per_launch;
     return JUP_OK;
 }
 

@@ -24,6 +24,17 @@ def test_diag_entry_points_reject_bad_arguments_before_any_launch():
     for buf, window, wgs, depth, pieces in bad_fill:
         rc = L.jup_diag_fill_probe(buf, window, wgs, depth, pieces, None, ctypes.byref(nbytes))
         assert rc == jb.JUP_EINVAL and jb.last_error(), (window, wgs, depth, pieces)
+    bad_stream = [
+        (None, 1 << 30, 256, 4, 16, 1),     # no buffer
+        (FAKE, 1 << 20, 256, 4, 16, 1),     # buffer shorter than 256 regions of 128 KiB
+        (FAKE, 1 << 30, 0, 4, 16, 1),       # no workgroups
+        (FAKE, 1 << 30, 256, 3, 15, 1),     # depth not offered
+        (FAKE, 1 << 30, 256, 4, 18, 1),     # pieces not a multiple of the depth
+        (FAKE, 1 << 30, 256, 4, 16, 0),     # no launches
+    ]
+    for buf, nbuf, wgs, depth, pieces, launches in bad_stream:
+        rc = L.jup_diag_stream_probe(buf, nbuf, wgs, depth, pieces, launches, None, ctypes.byref(nbytes))
+        assert rc == jb.JUP_EINVAL and jb.last_error(), (nbuf, wgs, depth, pieces, launches)
     for wgs, threads, trips, ticks, sink in [(256, 512, 100, None, FAKE), (256, 500, 100, FAKE, FAKE),
                                              (256, 2048, 100, FAKE, FAKE), (0, 512, 100, FAKE, FAKE),
                                              (256, 512, 0, FAKE, FAKE)]:
@@ -50,6 +61,15 @@ def test_diag_probes_run_and_report_plausible_rates():
         rates[depth] = nbytes / ev[0].elapsed_time(ev[1]) / 1e9   # TB/s
     assert 1.0 < rates[1] < 64.0 and 1.0 < rates[8] < 64.0, rates       # an L2 -> LDS rate, not a no-op and not nonsense
     assert rates[8] > rates[1], rates                                    # more in flight is faster
+    big = torch.ones(256 << 20, dtype=torch.uint8, device="cuda:0")
+    for _ in range(2):
+        ev[0].record()
+        nbytes = jb.diag_stream_probe(big, 256, 4, 32, 4)   # four launches of 64 MiB over the four quarters of the buffer
+        ev[1].record()
+        torch.cuda.synchronize()
+    assert nbytes == 4 * 256 * 32 * 8192
+    assert 0.5 < nbytes / ev[0].elapsed_time(ev[1]) / 1e9 < 8.0    # TB/s out of HBM: below the published peak
+    del big
     ticks = torch.zeros(64, dtype=torch.int64, device="cuda:0")
     sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
     per_wg = jb.diag_lds_read_probe(64, 1024, 500, ticks, sink)
